@@ -1,0 +1,81 @@
+"""Seeded synthetic inputs and workload shapes.
+
+This module holds no arithmetic of the attention method: it only names the workload shapes and
+draws Q, K, V.  Both the GPU path and the CPU oracle are fed from here so that they see identical
+bits.  The tensors stand in for post-RoPE FLUX.1-dev activations at the resolutions the paper
+evaluates (Sec. 4.1, Tables 2, 3 and 7): the shapes (512 text tokens, 24 heads x 128 channels,
+one latent token per 16x16 pixels) are the ones the paper's printed FLOP counts imply; the
+values are i.i.d. N(0,1), rounded once to the storage dtype.
+"""
+from dataclasses import dataclass
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    n_text: int
+    gridH: int
+    gridW: int
+    head_dim: int
+    r: int
+    dtype: str  # "bf16" or "f32"
+    seed: int
+    per_head_q_scale: bool = False  # Q of head h multiplied by s_h ~ U[0.5, 2] (varies logit sharpness)
+
+    @property
+    def N(self):
+        return self.n_text + self.gridH * self.gridW
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+
+
+WORKLOADS = {
+    w.name: w
+    for w in [
+        Workload("tiny", 1, 1, 8, 16, 16, 64, 4, "f32", 0),
+        Workload("flux-1024", 1, 24, 512, 64, 64, 128, 16, "bf16", 1),
+        Workload("flux-2048-r16", 1, 24, 512, 128, 128, 128, 16, "bf16", 2),
+        Workload("flux-2048-r8", 1, 24, 512, 128, 128, 128, 8, "bf16", 2),
+        Workload("flux-4096-r32", 1, 24, 512, 256, 256, 128, 32, "bf16", 3),
+        Workload("flux-4096-192x320-r32", 1, 24, 512, 192, 320, 128, 32, "bf16", 4),
+        Workload("flux-8k-r16", 1, 24, 512, 512, 512, 128, 16, "bf16", 5, per_head_q_scale=True),
+    ]
+}
+
+
+def make_qkv(w, device="cpu"):
+    """Draw Q, K, V of shape [B, H, N, head_dim] for workload `w` on `device`, head by head.
+
+    The generator lives on `device`; CPU and GPU streams differ, so draw once and hand the same
+    tensors (or copies of them) to every consumer."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    shape = (w.B, w.H, w.N, w.head_dim)
+    out = [torch.empty(shape, dtype=w.torch_dtype, device=dev) for _ in range(3)]
+    q_scale = torch.ones(w.H, dtype=torch.float32, device=dev)
+    if w.per_head_q_scale:
+        q_scale = 0.5 + 1.5 * torch.rand(w.H, generator=g, dtype=torch.float32, device=dev)
+    for b in range(w.B):
+        for h in range(w.H):
+            for t, dst in enumerate(out):
+                x = torch.randn((w.N, w.head_dim), generator=g, dtype=torch.float32, device=dev)
+                if t == 0:
+                    x = x * q_scale[h]
+                dst[b, h].copy_(x)  # one round-to-nearest-even into the storage dtype
+    return out[0], out[1], out[2]
+
+
+def make_qkv_shape(B, H, n_text, gridH, gridW, head_dim, dtype, seed, device="cpu", q_scale=1.0):
+    """Same recipe for an ad-hoc shape (edge-case tests)."""
+    w = Workload("adhoc", B, H, n_text, gridH, gridW, head_dim, 1, dtype, seed)
+    Q, K, V = make_qkv(w, device)
+    if q_scale != 1.0:
+        Q = (Q.float() * q_scale).to(Q.dtype)
+    return Q, K, V
