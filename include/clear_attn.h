@@ -1,0 +1,121 @@
+/*
+ * clear_attn.h -- C ABI of the MI355X (gfx950) CLEAR local-attention forward pass.
+ *
+ * The operation (arXiv 2412.16112): softmax attention of Eq. 1 (Sec. 2),
+ *     O = softmax(Q K^T / sqrt(head_dim)) V,
+ * restricted to the pairs allowed by the mask of Eq. 3 (Sec. 3.2): a text query attends to every
+ * key; an image query attends to every text key and to the image keys whose squared Euclidean
+ * distance on the gridH x gridW token raster is strictly below r^2.  The window is cut off at the
+ * image border (no wrap-around, no shifting) -- the reading that reproduces the FLOP counts of
+ * Tables 2, 3 and 7.
+ *
+ * Tensor layout (all entry points): Q, K, V, O are DEVICE pointers to contiguous
+ * [B, H, N, head_dim] arrays, N = n_text + gridH*gridW.  Rows 0 .. n_text-1 of the N axis are the
+ * text tokens; row n_text + y*gridW + x is image token (y, x), raster order.  Base pointers must be
+ * 16-byte aligned; O must not overlap Q, K or V.  Inputs are taken as given (post-RoPE); the only
+ * scaling applied is 1/sqrt(head_dim).  Values must be finite.
+ *
+ * Supported: dtype CLEAR_BF16 with head_dim 128 (MFMA path; fp32 accumulation, one round-to-nearest
+ * -even to bf16 on output) and dtype CLEAR_F32 with head_dim 64 (plain fp32 accuracy path).
+ * n_text >= 0, gridH, gridW >= 1, r >= 1, N < 2^31 / head_dim is NOT required (64-bit offsets).
+ *
+ * Errors: every function returns a clear_status; nothing throws or aborts; invalid arguments are
+ * rejected before any device work.  clear_attn_last_error gives a human-readable reason.
+ * Thread safety: a context may be used by one thread at a time; distinct contexts are independent.
+ * All functions run on the current HIP device; a context belongs to the device current at create.
+ */
+#ifndef CLEAR_ATTN_H
+#define CLEAR_ATTN_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct clear_attn_ctx clear_attn_ctx; /* opaque, owned by the library */
+
+typedef enum {
+    CLEAR_OK = 0,
+    CLEAR_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, r < 1, misaligned pointer */
+    CLEAR_ERR_UNSUPPORTED = 2, /* (dtype, head_dim) pair without a kernel */
+    CLEAR_ERR_ALLOC = 3,       /* host or device allocation failed */
+    CLEAR_ERR_HIP = 4,         /* a HIP runtime call failed; see clear_attn_last_error */
+    CLEAR_ERR_MISMATCH = 5     /* forward() shape arguments differ from those given to create() */
+} clear_status;
+
+typedef enum { CLEAR_BF16 = 0, CLEAR_F32 = 1 } clear_dtype;
+
+#define CLEAR_TILE_PARTIAL 0 /* some slot pair of the two tiles is masked or outside the grid */
+#define CLEAR_TILE_FULL 1    /* every slot pair is inside the grid and unmasked */
+
+/*
+ * Builds the tile schedule for (gridH, gridW, r) with the tile shapes of the kernel chosen for
+ * (dtype, head_dim), and uploads it.  Allocates device memory and synchronises the device.
+ * *out is written only on CLEAR_OK.  (Schedule: Sec. 3.2 fixes which pairs exist; the tiling is
+ * this library's.)
+ */
+int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r,
+                      int dtype);
+
+/*
+ * Pre-sizes the workspace that the text-query rows need (partial results of the key-split dense
+ * pass, Sec. 3.2 "each text query gathers from all text and image tokens") for batch*heads = BH.
+ * forward() calls this itself when it meets a larger B*H than any before, which allocates and
+ * synchronises; call reserve first if forward must not allocate.  Returns CLEAR_ERR_ALLOC on failure.
+ */
+int clear_attn_reserve(clear_attn_ctx* ctx, int BH);
+
+/*
+ * Enqueues one forward pass (Eq. 1 under the mask of Eq. 3) on `stream` (a hipStream_t; NULL is
+ * the default stream) and returns without synchronising.  n_text, gridH, gridW, head_dim, r must
+ * equal the values given to create (CLEAR_ERR_MISMATCH otherwise, nothing launched).  B, H >= 1.
+ * The caller owns Q, K, V, O and the stream, and must keep them alive until the stream has
+ * finished the work.  Two forwards of one context may not overlap in time (shared workspace).
+ */
+int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
+                       int B, int H, int n_text, int gridH, int gridW, int head_dim, int r,
+                       void* stream);
+
+/* Frees the context and its device memory.  NULL is a no-op.  The caller must have synchronised
+ * any stream still running a forward of this context. */
+void clear_attn_destroy(clear_attn_ctx* ctx);
+
+/* ---- introspection (host only, no device work) -------------------------------------------- */
+
+/* sum(M) of Eq. 3 per (batch, head) from a lattice-point count; the FLOP estimate of the paper
+ * (Fig. 2 caption) is 4 * sumM * channels. */
+int clear_attn_mask_count(int n_text, int gridH, int gridW, int r, unsigned long long* sumM);
+
+/* Tile shapes used for (dtype, head_dim): query tiles q_tile_h x q_tile_w and key tiles
+ * k_tile_h x k_tile_w, both aligned to the grid origin and numbered row-major. */
+int clear_attn_tile_shape(int head_dim, int dtype, int* q_tile_h, int* q_tile_w, int* k_tile_h,
+                          int* k_tile_w);
+
+/*
+ * Host-only schedule builder.  For each query tile (row-major) the ascending list of key tiles
+ * holding at least one in-grid, unmasked (query, key) image pair, with CLEAR_TILE_FULL /
+ * CLEAR_TILE_PARTIAL flags.  Text keys are attended by every query and are not listed.
+ * Call once with row_ptr = col_idx = flags = NULL to get *n_q_tiles and *n_pairs, then with
+ * caller-owned arrays row_ptr[*n_q_tiles + 1], col_idx[*n_pairs], flags[*n_pairs].
+ */
+int clear_attn_schedule_host(int gridH, int gridW, int r, int q_tile_h, int q_tile_w, int k_tile_h,
+                             int k_tile_w, int* n_q_tiles, long long* n_pairs, int* row_ptr,
+                             int* col_idx, unsigned char* flags);
+
+/* The schedule a context holds (same content as clear_attn_schedule_host for its tile shapes). */
+int clear_attn_schedule_size(const clear_attn_ctx* ctx, int* q_tile_h, int* q_tile_w, int* k_tile_h,
+                             int* k_tile_w, int* n_q_tiles, long long* n_pairs);
+int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_idx,
+                             unsigned char* flags);
+
+/* Number of (query slot, key slot) pairs per (batch, head) that the kernels actually push through
+ * the matrix pipeline, masked and padding slots included ("executed" work; useful work is sumM). */
+int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head);
+
+/* Reason of the last failure on this context (or of the last failed create when ctx is NULL).
+ * The string is owned by the library and valid until the next call on the same context/thread. */
+const char* clear_attn_last_error(const clear_attn_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLEAR_ATTN_H */

@@ -1,0 +1,172 @@
+"""Thin ctypes binding of libclear_attn.so: the same names as include/clear_attn.h, argument
+marshalling only.  PyTorch tensors are used for device memory and streams; every step of the
+attention runs in the HIP kernels.  There is no fallback: a missing library raises."""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libclear_attn.so")
+
+CLEAR_OK, CLEAR_ERR_INVALID_ARG, CLEAR_ERR_UNSUPPORTED, CLEAR_ERR_ALLOC, CLEAR_ERR_HIP, CLEAR_ERR_MISMATCH = range(6)
+CLEAR_BF16, CLEAR_F32 = 0, 1
+CLEAR_TILE_PARTIAL, CLEAR_TILE_FULL = 0, 1
+
+EXPORTS = [
+    "clear_attn_create", "clear_attn_reserve", "clear_attn_forward", "clear_attn_destroy",
+    "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
+    "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
+    "clear_attn_last_error",
+]
+
+_lib = None
+
+
+class ClearAttnError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("clear_attn status %d: %s" % (status, message))
+        self.status = status
+
+
+def lib():
+    """The loaded C library (raises if it has not been built: python -m paper_2412_16112_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libclear_attn.so is not built (run: python -m paper_2412_16112_amd.build); "
+                              "there is no non-HIP fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        i, vp, ip = ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)
+        ullp, llp = ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(ctypes.c_longlong)
+        L.clear_attn_create.argtypes = [ctypes.POINTER(vp), i, i, i, i, i, i]
+        L.clear_attn_reserve.argtypes = [vp, i]
+        L.clear_attn_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_destroy.argtypes = [vp]
+        L.clear_attn_destroy.restype = None
+        L.clear_attn_mask_count.argtypes = [i, i, i, i, ullp]
+        L.clear_attn_tile_shape.argtypes = [i, i, ip, ip, ip, ip]
+        L.clear_attn_schedule_host.argtypes = [i, i, i, i, i, i, i, ip, llp, vp, vp, vp]
+        L.clear_attn_schedule_size.argtypes = [vp, ip, ip, ip, ip, ip, llp]
+        L.clear_attn_schedule_copy.argtypes = [vp, vp, vp, vp]
+        L.clear_attn_executed_pairs.argtypes = [vp, ullp]
+        L.clear_attn_last_error.argtypes = [vp]
+        L.clear_attn_last_error.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("clear_attn_destroy", "clear_attn_last_error"):
+                getattr(L, name).restype = i
+        _lib = L
+    return _lib
+
+
+def _check(status, ctx=None):
+    if status != CLEAR_OK:
+        raise ClearAttnError(status, lib().clear_attn_last_error(ctx).decode())
+
+
+def clear_attn_mask_count(n_text, gridH, gridW, r):
+    out = ctypes.c_ulonglong(0)
+    _check(lib().clear_attn_mask_count(n_text, gridH, gridW, r, ctypes.byref(out)))
+    return int(out.value)
+
+
+def clear_attn_tile_shape(head_dim, dtype):
+    v = [ctypes.c_int(0) for _ in range(4)]
+    _check(lib().clear_attn_tile_shape(head_dim, dtype, *[ctypes.byref(x) for x in v]))
+    return tuple(int(x.value) for x in v)
+
+
+def clear_attn_schedule_host(gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_tile_w):
+    """Returns (row_ptr int32[n_q_tiles+1], col_idx int32[n_pairs], flags uint8[n_pairs])."""
+    nq, npairs = ctypes.c_int(0), ctypes.c_longlong(0)
+    args = (gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_tile_w)
+    _check(lib().clear_attn_schedule_host(*args, ctypes.byref(nq), ctypes.byref(npairs), None, None, None))
+    row_ptr = np.zeros(nq.value + 1, dtype=np.int32)
+    col_idx = np.zeros(max(1, npairs.value), dtype=np.int32)
+    flags = np.zeros(max(1, npairs.value), dtype=np.uint8)
+    _check(lib().clear_attn_schedule_host(*args, ctypes.byref(nq), ctypes.byref(npairs), row_ptr.ctypes.data,
+                                          col_idx.ctypes.data, flags.ctypes.data))
+    return row_ptr, col_idx[:npairs.value], flags[:npairs.value]
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return CLEAR_BF16
+    if t.dtype == torch.float32:
+        return CLEAR_F32
+    raise ClearAttnError(CLEAR_ERR_UNSUPPORTED, "tensors must be bfloat16 or float32")
+
+
+class ClearAttn:
+    """Owns one clear_attn_ctx (clear_attn_create / clear_attn_forward / clear_attn_destroy)."""
+
+    def __init__(self, n_text, gridH, gridW, head_dim, r, dtype):
+        self._ctx = ctypes.c_void_p(None)
+        self.shape = (n_text, gridH, gridW, head_dim, r)
+        self.dtype = dtype
+        _check(lib().clear_attn_create(ctypes.byref(self._ctx), n_text, gridH, gridW, head_dim, r, dtype))
+
+    def reserve(self, BH):
+        _check(lib().clear_attn_reserve(self._ctx, BH), self._ctx)
+
+    def forward(self, Q, K, V, O=None, stream=None):
+        """Q, K, V: contiguous device tensors [B, H, N, head_dim]; enqueues on `stream` (default: torch's current)."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        for t in (Q, K, V):
+            if not (t.is_cuda and t.is_contiguous() and t.dim() == 4 and t.dtype == Q.dtype and t.shape == Q.shape):
+                raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "Q, K, V must be contiguous device tensors of one shape and dtype")
+        if _dtype_code(Q) != self.dtype:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor dtype differs from the context's")
+        B, H, N, d = Q.shape
+        if N != n_text + gridH * gridW or d != head_dim:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape differs from the context's")
+        if O is None:
+            O = torch.empty_like(Q)
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        _check(lib().clear_attn_forward(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H,
+                                        n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
+        return O
+
+    def schedule_size(self):
+        v = [ctypes.c_int(0) for _ in range(5)]
+        npairs = ctypes.c_longlong(0)
+        _check(lib().clear_attn_schedule_size(self._ctx, *[ctypes.byref(x) for x in v], ctypes.byref(npairs)), self._ctx)
+        return tuple(int(x.value) for x in v) + (int(npairs.value),)
+
+    def schedule_copy(self):
+        *_, nq, npairs = self.schedule_size()
+        row_ptr = np.zeros(nq + 1, dtype=np.int32)
+        col_idx = np.zeros(max(1, npairs), dtype=np.int32)
+        flags = np.zeros(max(1, npairs), dtype=np.uint8)
+        _check(lib().clear_attn_schedule_copy(self._ctx, row_ptr.ctypes.data, col_idx.ctypes.data, flags.ctypes.data), self._ctx)
+        return row_ptr, col_idx[:npairs], flags[:npairs]
+
+    def executed_pairs(self):
+        out = ctypes.c_ulonglong(0)
+        _check(lib().clear_attn_executed_pairs(self._ctx, ctypes.byref(out)), self._ctx)
+        return int(out.value)
+
+    def destroy(self):
+        if self._ctx:
+            lib().clear_attn_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def clear_attn_forward_once(Q, K, V, n_text, gridH, gridW, r):
+    """create + forward + destroy for one call (tests, smoke)."""
+    ctx = ClearAttn(n_text, gridH, gridW, Q.shape[-1], r, _dtype_code(Q))
+    try:
+        import torch
+        O = ctx.forward(Q, K, V)
+        torch.cuda.synchronize(Q.device)
+        return O
+    finally:
+        ctx.destroy()

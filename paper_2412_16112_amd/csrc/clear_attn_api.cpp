@@ -1,0 +1,297 @@
+// C ABI of the CLEAR local-attention library: argument checks, context, schedule upload, launch.
+#include "../../include/clear_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "clear_internal.h"
+
+using namespace clear;
+
+struct clear_attn_ctx {
+    int n_text = 0, gridH = 0, gridW = 0, head_dim = 0, r = 0, dtype = 0;
+    int device = 0;
+    Schedule sched;
+    int* d_row_ptr = nullptr;
+    int* d_col_idx = nullptr;
+    // text-query workspace, grown on demand
+    int ws_BH = 0;         // capacity in (batch*head) units
+    int ws_max_splits = 0;  // splits the workspace is sized for
+    float* d_ws_o = nullptr;
+    float* d_ws_ml = nullptr;
+    std::string err;
+};
+
+static thread_local std::string g_create_error;
+
+static int fail(clear_attn_ctx* ctx, int code, const std::string& msg)
+{
+    if (ctx) ctx->err = msg; else g_create_error = msg;
+    return code;
+}
+
+static int check_shape(int n_text, int gridH, int gridW, int r, std::string* why)
+{
+    if (n_text < 0) { *why = "n_text must be >= 0"; return CLEAR_ERR_INVALID_ARG; }
+    if (gridH < 1 || gridW < 1) { *why = "gridH and gridW must be >= 1"; return CLEAR_ERR_INVALID_ARG; }
+    if (r < 1) { *why = "r must be >= 1"; return CLEAR_ERR_INVALID_ARG; }
+    if (r > 32768) { *why = "r must be <= 32768"; return CLEAR_ERR_INVALID_ARG; }
+    if ((long long)gridH * gridW + n_text > 0x7fffffffLL) { *why = "n_text + gridH*gridW must fit in 31 bits"; return CLEAR_ERR_INVALID_ARG; }
+    return CLEAR_OK;
+}
+
+static int check_kernel(int head_dim, int dtype, std::string* why)
+{
+    if (dtype != CLEAR_BF16 && dtype != CLEAR_F32) { *why = "dtype must be CLEAR_BF16 or CLEAR_F32"; return CLEAR_ERR_INVALID_ARG; }
+    if (head_dim < 1) { *why = "head_dim must be >= 1"; return CLEAR_ERR_INVALID_ARG; }
+    if (dtype == CLEAR_BF16 && head_dim == 128) return CLEAR_OK;
+    if (dtype == CLEAR_F32 && head_dim == 64) return CLEAR_OK;
+    *why = "supported kernels: bf16 with head_dim 128, f32 with head_dim 64";
+    return CLEAR_ERR_UNSUPPORTED;
+}
+
+// The maximum number of key splits of the text-query pass; the workspace is sized for it.
+static int max_text_splits(long long N)
+{
+    // at least 512 keys per split, at most 64 splits
+    long long s = (N + 511) / 512;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return (int)s;
+}
+
+// Splits for a given batch*heads: enough workgroups to fill 256 CUs a few times over.
+static void choose_text_splits(long long N, int BH, int n_tq_tiles, int* n_splits, int* split_keys)
+{
+    const int max_s = max_text_splits(N);
+    long long want = (1024 + (long long)BH * n_tq_tiles - 1) / ((long long)BH * n_tq_tiles);
+    if (want < 1) want = 1;
+    if (want > max_s) want = max_s;
+    long long keys = (N + want - 1) / want;
+    keys = ((keys + kKeyTileKeys - 1) / kKeyTileKeys) * kKeyTileKeys;  // whole 64-key stages
+    *split_keys = (int)keys;
+    *n_splits = (int)((N + keys - 1) / keys);
+}
+
+extern "C" {
+
+int clear_attn_mask_count(int n_text, int gridH, int gridW, int r, unsigned long long* sumM)
+{
+    std::string why;
+    if (!sumM) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "sumM is NULL");
+    int rc = check_shape(n_text, gridH, gridW, r, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+    *sumM = mask_count(n_text, gridH, gridW, r);
+    return CLEAR_OK;
+}
+
+int clear_attn_tile_shape(int head_dim, int dtype, int* q_tile_h, int* q_tile_w, int* k_tile_h, int* k_tile_w)
+{
+    std::string why;
+    int rc = check_kernel(head_dim, dtype, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+    if (!q_tile_h || !q_tile_w || !k_tile_h || !k_tile_w) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL output pointer");
+    if (dtype == CLEAR_BF16) { *q_tile_h = kBf16QTileH; *q_tile_w = kBf16QTileW; }
+    else { *q_tile_h = kF32QTileH; *q_tile_w = kF32QTileW; }
+    *k_tile_h = kKeyTileH;
+    *k_tile_w = kKeyTileW;
+    return CLEAR_OK;
+}
+
+int clear_attn_schedule_host(int gridH, int gridW, int r, int q_tile_h, int q_tile_w, int k_tile_h, int k_tile_w,
+                             int* n_q_tiles, long long* n_pairs, int* row_ptr, int* col_idx, unsigned char* flags)
+{
+    std::string why;
+    int rc = check_shape(0, gridH, gridW, r, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+    if (q_tile_h < 1 || q_tile_w < 1 || k_tile_h < 1 || k_tile_w < 1) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "tile sizes must be >= 1");
+    if (!n_q_tiles || !n_pairs) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "n_q_tiles / n_pairs is NULL");
+    const bool sizes_only = !row_ptr && !col_idx && !flags;
+    if (!sizes_only && (!row_ptr || !col_idx || !flags)) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "row_ptr, col_idx and flags must be all NULL or all set");
+    Schedule s;
+    try {
+        build_schedule(gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_tile_w, &s);
+    } catch (const std::bad_alloc&) {
+        return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
+    }
+    *n_q_tiles = (int)s.row_ptr.size() - 1;
+    *n_pairs = (long long)s.col_idx.size();
+    if (!sizes_only) {
+        memcpy(row_ptr, s.row_ptr.data(), s.row_ptr.size() * sizeof(int));
+        memcpy(col_idx, s.col_idx.data(), s.col_idx.size() * sizeof(int));
+        memcpy(flags, s.flags.data(), s.flags.size());
+    }
+    return CLEAR_OK;
+}
+
+int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r, int dtype)
+{
+    std::string why;
+    if (!out) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "out is NULL");
+    int rc = check_shape(n_text, gridH, gridW, r, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+    rc = check_kernel(head_dim, dtype, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+
+    clear_attn_ctx* ctx = new (std::nothrow) clear_attn_ctx;
+    if (!ctx) return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory");
+    ctx->n_text = n_text; ctx->gridH = gridH; ctx->gridW = gridW;
+    ctx->head_dim = head_dim; ctx->r = r; ctx->dtype = dtype;
+    int qth, qtw, kth, ktw;
+    clear_attn_tile_shape(head_dim, dtype, &qth, &qtw, &kth, &ktw);
+    try {
+        build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &ctx->sched);
+    } catch (const std::bad_alloc&) {
+        delete ctx;
+        return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
+    }
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_row_ptr, ctx->sched.row_ptr.size() * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_col_idx, (ctx->sched.col_idx.size() + 1) * sizeof(int));
+    if (e == hipSuccess) e = hipMemcpy(ctx->d_row_ptr, ctx->sched.row_ptr.data(), ctx->sched.row_ptr.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !ctx->sched.col_idx.empty())
+        e = hipMemcpy(ctx->d_col_idx, ctx->sched.col_idx.data(), ctx->sched.col_idx.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        std::string msg = std::string("HIP error in create: ") + hipGetErrorString(e);
+        const int code = (e == hipErrorOutOfMemory) ? CLEAR_ERR_ALLOC : CLEAR_ERR_HIP;
+        clear_attn_destroy(ctx);
+        return fail(nullptr, code, msg);
+    }
+    *out = ctx;
+    return CLEAR_OK;
+}
+
+int clear_attn_reserve(clear_attn_ctx* ctx, int BH)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    if (BH < 1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be >= 1");
+    if (ctx->n_text == 0 || BH <= ctx->ws_BH) return CLEAR_OK;
+    const long long N = (long long)ctx->n_text + (long long)ctx->gridH * ctx->gridW;
+    const int splits = max_text_splits(N);
+    hipError_t e = hipDeviceSynchronize();  // a running forward may still use the old workspace
+    if (e == hipSuccess && ctx->d_ws_o) e = hipFree(ctx->d_ws_o);
+    if (e == hipSuccess && ctx->d_ws_ml) e = hipFree(ctx->d_ws_ml);
+    ctx->d_ws_o = ctx->d_ws_ml = nullptr;
+    ctx->ws_BH = 0;
+    const size_t rows = (size_t)BH * splits * ctx->n_text;
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_ws_o, rows * ctx->head_dim * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_ws_ml, rows * 2 * sizeof(float));
+    if (e != hipSuccess) {
+        if (ctx->d_ws_o) (void)hipFree(ctx->d_ws_o);
+        ctx->d_ws_o = nullptr;
+        (void)hipGetLastError();
+        return fail(ctx, e == hipErrorOutOfMemory ? CLEAR_ERR_ALLOC : CLEAR_ERR_HIP,
+                    std::string("workspace allocation failed: ") + hipGetErrorString(e));
+    }
+    ctx->ws_BH = BH;
+    ctx->ws_max_splits = splits;
+    return CLEAR_OK;
+}
+
+int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
+                       int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    if (!Q || !K || !V || !O) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be non-NULL");
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be 16-byte aligned");
+    if (B < 1 || H < 1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "B and H must be >= 1");
+    if ((long long)B * H > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "B*H must be <= 65535");
+    if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
+        return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
+    {
+        // O must not overlap an input
+        const long long N = (long long)n_text + (long long)gridH * gridW;
+        const size_t bytes = (size_t)B * H * N * head_dim * (ctx->dtype == CLEAR_BF16 ? 2 : 4);
+        const uintptr_t o0 = (uintptr_t)O, o1 = o0 + bytes;
+        const void* ins[3] = {Q, K, V};
+        for (const void* in : ins) {
+            const uintptr_t i0 = (uintptr_t)in, i1 = i0 + bytes;
+            if (o0 < i1 && i0 < o1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "O overlaps an input tensor");
+        }
+    }
+    const int BH = B * H;
+    const long long N = (long long)n_text + (long long)gridH * gridW;
+    const Schedule& s = ctx->sched;
+    const long long n_q_tiles = (long long)s.n_qty * s.n_qtx;
+    if (n_q_tiles * BH > 0x7fffffffLL) return fail(ctx, CLEAR_ERR_INVALID_ARG, "too many workgroups: B*H*query tiles must fit in 31 bits");
+
+    FwdParams p;
+    memset(&p, 0, sizeof(p));
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.B = B; p.H = H; p.n_text = n_text; p.gridH = gridH; p.gridW = gridW; p.r2 = r * r;
+    p.N = N;
+    p.n_q_tiles = (int)n_q_tiles;
+    p.n_qtx = s.n_qtx;
+    p.n_ktx = s.n_ktx;
+    p.row_ptr = ctx->d_row_ptr;
+    p.col_idx = ctx->d_col_idx;
+    p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
+    if (n_text > 0) {
+        int rc = clear_attn_reserve(ctx, BH);
+        if (rc != CLEAR_OK) return rc;
+        const int per_block = ctx->dtype == CLEAR_BF16 ? bf16_text_queries_per_block() : f32_text_queries_per_block();
+        p.n_tq_tiles = (n_text + per_block - 1) / per_block;
+        choose_text_splits(N, BH, p.n_tq_tiles, &p.n_splits, &p.split_keys);
+        if (p.n_splits > ctx->ws_max_splits) return fail(ctx, CLEAR_ERR_HIP, "internal: split count exceeds workspace");
+        p.ws_o = ctx->d_ws_o;
+        p.ws_ml = ctx->d_ws_ml;
+    }
+    hipError_t e = (ctx->dtype == CLEAR_BF16) ? launch_bf16_d128(p, (hipStream_t)stream) : launch_f32_d64(p, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+void clear_attn_destroy(clear_attn_ctx* ctx)
+{
+    if (!ctx) return;
+    if (ctx->d_row_ptr) (void)hipFree(ctx->d_row_ptr);
+    if (ctx->d_col_idx) (void)hipFree(ctx->d_col_idx);
+    if (ctx->d_ws_o) (void)hipFree(ctx->d_ws_o);
+    if (ctx->d_ws_ml) (void)hipFree(ctx->d_ws_ml);
+    delete ctx;
+}
+
+int clear_attn_schedule_size(const clear_attn_ctx* ctx, int* q_tile_h, int* q_tile_w, int* k_tile_h, int* k_tile_w,
+                             int* n_q_tiles, long long* n_pairs)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    const Schedule& s = ctx->sched;
+    if (q_tile_h) *q_tile_h = s.qth;
+    if (q_tile_w) *q_tile_w = s.qtw;
+    if (k_tile_h) *k_tile_h = s.kth;
+    if (k_tile_w) *k_tile_w = s.ktw;
+    if (n_q_tiles) *n_q_tiles = (int)s.row_ptr.size() - 1;
+    if (n_pairs) *n_pairs = (long long)s.col_idx.size();
+    return CLEAR_OK;
+}
+
+int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_idx, unsigned char* flags)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    const Schedule& s = ctx->sched;
+    if (row_ptr) memcpy(row_ptr, s.row_ptr.data(), s.row_ptr.size() * sizeof(int));
+    if (col_idx) memcpy(col_idx, s.col_idx.data(), s.col_idx.size() * sizeof(int));
+    if (flags) memcpy(flags, s.flags.data(), s.flags.size());
+    return CLEAR_OK;
+}
+
+int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head)
+{
+    if (!ctx || !pairs_per_head) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL argument");
+    *pairs_per_head = (ctx->dtype == CLEAR_BF16) ? executed_pairs_bf16(ctx->sched, ctx->n_text, 0)
+                                                 : executed_pairs_f32(ctx->sched, ctx->n_text);
+    return CLEAR_OK;
+}
+
+const char* clear_attn_last_error(const clear_attn_ctx* ctx)
+{
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+}  // extern "C"

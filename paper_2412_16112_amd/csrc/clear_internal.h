@@ -1,0 +1,67 @@
+// Internal declarations shared by the host API and the kernel launchers (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <vector>
+
+namespace clear {
+
+// Geometry of the bf16 MFMA kernels: a wave owns a 4 x 8 patch of queries (32 = one MFMA N
+// dimension); a workgroup owns NWY x NWX such patches; a key tile is 8 x 8 image tokens staged as
+// two 4 x 8 blocks of 32 keys (one MFMA M dimension each).
+constexpr int kWaveQH = 4, kWaveQW = 8;
+constexpr int kKeyBlockH = 4, kKeyBlockW = 8;
+constexpr int kKeyTileH = 8, kKeyTileW = 8;
+constexpr int kKeyTileKeys = kKeyTileH * kKeyTileW;  // 64 keys per staged tile
+constexpr int kBf16NWY = 4, kBf16NWX = 2;            // workgroup = 16 x 16 queries, 8 waves
+constexpr int kBf16QTileH = kBf16NWY * kWaveQH, kBf16QTileW = kBf16NWX * kWaveQW;
+constexpr int kTextQueriesPerWave = 32;
+
+// fp32 accuracy path: one thread per query, 16 x 16 queries per workgroup, same key tiles.
+constexpr int kF32QTileH = 16, kF32QTileW = 16;
+
+struct Schedule {
+    int gridH = 0, gridW = 0, r = 0;
+    int qth = 0, qtw = 0, kth = 0, ktw = 0;
+    int n_qty = 0, n_qtx = 0, n_kty = 0, n_ktx = 0;
+    std::vector<int> row_ptr;        // n_q_tiles + 1
+    std::vector<int> col_idx;        // key tile ids, ascending per query tile
+    std::vector<unsigned char> flags;  // CLEAR_TILE_FULL / CLEAR_TILE_PARTIAL
+};
+
+// Host-side integer geometry (schedule.cpp)
+void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s);
+unsigned long long mask_count(int n_text, int gridH, int gridW, int r);
+// Pairs fed to the matrix pipeline per (batch, head) by the bf16 kernels (image pass + text-query pass).
+unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys);
+// Pairs visited by the fp32 path (it tests every slot of every staged tile).
+unsigned long long executed_pairs_f32(const Schedule& s, int n_text);
+
+struct FwdParams {
+    const void* Q;
+    const void* K;
+    const void* V;
+    void* O;
+    int B, H, n_text, gridH, gridW, r2;
+    long long N;       // tokens per (batch, head)
+    int n_q_tiles;     // image query tiles per head
+    int n_qtx;         // query tiles per tile row
+    int n_ktx;         // key tiles per tile row
+    const int* row_ptr;  // device CSR
+    const int* col_idx;
+    float scale_log2e;  // log2(e) / sqrt(head_dim)
+    // text-query pass: dense rows split along the keys, partial results merged afterwards
+    int n_tq_tiles;   // text query tiles per head
+    int n_splits;     // key splits
+    int split_keys;   // keys per split, multiple of 64
+    float* ws_o;      // [B*H][n_splits][n_text][head_dim] un-normalised partial outputs
+    float* ws_ml;     // [B*H][n_splits][n_text][2]        running max (raw logit) and denominator
+};
+
+// Launchers (kernels_bf16.hip, kernels_f32.hip).  Each returns the first HIP error met.
+hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream);
+hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream);
+int bf16_text_queries_per_block();
+int f32_text_queries_per_block();
+
+}  // namespace clear

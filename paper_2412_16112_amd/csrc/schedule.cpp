@@ -1,0 +1,113 @@
+// Host-side integer geometry of the CLEAR mask (Eq. 3, Sec. 3.2): tile schedule, sum(M), and the
+// count of pairs the kernels execute.  No device code here.
+#include "block_class.h"
+#include "clear_internal.h"
+
+namespace clear {
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Smallest |a - b| for a in [a0, a1], b in [b0, b1].
+static inline int interval_gap(int a0, int a1, int b0, int b1)
+{
+    if (b0 > a1) return b0 - a1;
+    if (a0 > b1) return a0 - b1;
+    return 0;
+}
+
+void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s)
+{
+    s->gridH = gridH; s->gridW = gridW; s->r = r;
+    s->qth = qth; s->qtw = qtw; s->kth = kth; s->ktw = ktw;
+    s->n_qty = ceil_div(gridH, qth); s->n_qtx = ceil_div(gridW, qtw);
+    s->n_kty = ceil_div(gridH, kth); s->n_ktx = ceil_div(gridW, ktw);
+    s->row_ptr.assign(1, 0);
+    s->col_idx.clear();
+    s->flags.clear();
+    const long long r2 = (long long)r * r;
+    for (int ty = 0; ty < s->n_qty; ++ty)
+        for (int tx = 0; tx < s->n_qtx; ++tx) {
+            // extent of the query tile inside the grid
+            const int qy0 = ty * qth, qy1 = imin(qy0 + qth, gridH) - 1;
+            const int qx0 = tx * qtw, qx1 = imin(qx0 + qtw, gridW) - 1;
+            const bool q_inside = (qy0 + qth <= gridH) && (qx0 + qtw <= gridW);
+            // key tiles that can come within distance r-1 on each axis
+            const int kty_lo = imax(0, (qy0 - (r - 1)) / kth - 1), kty_hi = imin(s->n_kty - 1, (qy1 + r - 1) / kth);
+            const int ktx_lo = imax(0, (qx0 - (r - 1)) / ktw - 1), ktx_hi = imin(s->n_ktx - 1, (qx1 + r - 1) / ktw);
+            for (int ky = kty_lo; ky <= kty_hi; ++ky)
+                for (int kx = ktx_lo; kx <= ktx_hi; ++kx) {
+                    const int ky0 = ky * kth, ky1 = imin(ky0 + kth, gridH) - 1;
+                    const int kx0 = kx * ktw, kx1 = imin(kx0 + ktw, gridW) - 1;
+                    const long long dy = interval_gap(qy0, qy1, ky0, ky1), dx = interval_gap(qx0, qx1, kx0, kx1);
+                    if (dy * dy + dx * dx >= r2) continue;  // no pair closer than r: not listed
+                    const bool k_inside = (ky0 + kth <= gridH) && (kx0 + ktw <= gridW);
+                    const long long fy = imax(qy1 - ky0, ky1 - qy0), fx = imax(qx1 - kx0, kx1 - qx0);
+                    const bool full = q_inside && k_inside && fy * fy + fx * fx < r2;
+                    s->col_idx.push_back(ky * s->n_ktx + kx);
+                    s->flags.push_back(full ? 1 : 0);
+                }
+            s->row_ptr.push_back((int)s->col_idx.size());
+        }
+}
+
+unsigned long long mask_count(int n_text, int gridH, int gridW, int r)
+{
+    // Each offset (dy, dx) of the open disc occurs (gridH - |dy|)(gridW - |dx|) times on the raster.
+    const unsigned long long n_img = (unsigned long long)gridH * gridW, N = n_img + n_text;
+    unsigned long long img = 0;
+    const long long r2 = (long long)r * r;
+    for (long long dy = -(r - 1); dy <= r - 1; ++dy) {
+        const long long ady = dy < 0 ? -dy : dy;
+        if (ady >= gridH) continue;
+        for (long long dx = -(r - 1); dx <= r - 1; ++dx) {
+            const long long adx = dx < 0 ? -dx : dx;
+            if (adx >= gridW || dx * dx + dy * dy >= r2) continue;
+            img += (unsigned long long)(gridH - ady) * (unsigned long long)(gridW - adx);
+        }
+    }
+    return (unsigned long long)n_text * N + n_img * n_text + img;
+}
+
+unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys)
+{
+    (void)text_split_keys;  // splits are multiples of the 64-key stage: the block count does not depend on them
+    const long long N = (long long)n_text + (long long)s.gridH * s.gridW;
+    unsigned long long blocks = 0;  // executed (32 query x 32 key) blocks
+    const int n_text_tiles = ceil_div(n_text, kKeyTileKeys);
+    const int nwy = s.qth / kWaveQH, nwx = s.qtw / kWaveQW;
+    for (int ty = 0; ty < s.n_qty; ++ty)
+        for (int tx = 0; tx < s.n_qtx; ++tx) {
+            const int qt = ty * s.n_qtx + tx;
+            for (int wy = 0; wy < nwy; ++wy)
+                for (int wx = 0; wx < nwx; ++wx) {
+                    const int y0 = ty * s.qth + wy * kWaveQH, x0 = tx * s.qtw + wx * kWaveQW;
+                    if (y0 >= s.gridH || x0 >= s.gridW) continue;  // wave has no query: it computes nothing
+                    for (int t = 0; t < n_text_tiles; ++t)
+                        for (int kb = 0; kb < 2; ++kb)
+                            blocks += classify_linear_block((long long)t * kKeyTileKeys + 32 * kb, 32, n_text) != kBlockSkip;
+                    for (int e = s.row_ptr[qt]; e < s.row_ptr[qt + 1]; ++e) {
+                        const int ky0 = (s.col_idx[e] / s.n_ktx) * s.kth, kx0 = (s.col_idx[e] % s.n_ktx) * s.ktw;
+                        for (int kb = 0; kb < 2; ++kb)
+                            blocks += classify_image_block(y0, x0, kWaveQH, kWaveQW, ky0 + kKeyBlockH * kb, kx0, kKeyBlockH,
+                                                           kKeyBlockW, s.gridH, s.gridW, s.r * s.r) != kBlockSkip;
+                    }
+                }
+        }
+    // text-query pass: every wave that holds at least one text query visits every 32-key block of [0, N)
+    const unsigned long long text_waves = (unsigned long long)ceil_div(n_text, kTextQueriesPerWave);
+    blocks += text_waves * (unsigned long long)((N + 31) / 32);
+    return blocks * 1024ull;
+}
+
+unsigned long long executed_pairs_f32(const Schedule& s, int n_text)
+{
+    const long long N = (long long)n_text + (long long)s.gridH * s.gridW;
+    const unsigned long long n_text_tiles = (unsigned long long)ceil_div(n_text, kKeyTileKeys);
+    unsigned long long pairs = 0;
+    for (size_t qt = 0; qt + 1 < s.row_ptr.size(); ++qt)
+        pairs += (n_text_tiles + (unsigned long long)(s.row_ptr[qt + 1] - s.row_ptr[qt])) * kKeyTileKeys * (unsigned long long)(s.qth * s.qtw);
+    pairs += (unsigned long long)n_text * (unsigned long long)(((N + kKeyTileKeys - 1) / kKeyTileKeys) * kKeyTileKeys);
+    return pairs;
+}
+
+}  // namespace clear
