@@ -1,0 +1,131 @@
+#!/usr/bin/env python3
+"""Benchmark of the CLEAR local-attention forward pass on one MI355X.
+
+A "step" is one whole forward pass (image-query kernel + text-query kernel + merge) over one
+synthetic batch of the FLUX-8K shape (B=1, H=24, head_dim=128, 512x512 token grid + 512 text
+tokens, r=16, bf16), inputs resident in HBM before the timed region.  Prints ONE JSON line:
+useful TFLOP/s = 4*sum(M)*d*H*B / time (the paper's FLOP estimate, Fig. 2 caption), plus executed
+TFLOP/s (tile waste included), the roofline of the dominant kernel, and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="flux-8k-r16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-image-rows", type=int, default=1536)
+    ap.add_argument("--cpu-text-rows", type=int, default=24)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported. "
+              "Heads are independent, so N GPUs would each take H/N heads with no communication inside the op." % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2412_16112_amd import clear_attn as ca
+    from paper_2412_16112_amd.inputs import WORKLOADS, make_qkv
+
+    w = WORKLOADS[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    Q, K, V = make_qkv(w, dev)
+    O = torch.empty_like(Q)
+    dtype_code = ca.CLEAR_BF16 if w.dtype == "bf16" else ca.CLEAR_F32
+    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, dtype_code)
+    ctx.reserve(w.B * w.H)
+
+    for _ in range(args.warmup):
+        ctx.forward(Q, K, V, O)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.forward(Q, K, V, O)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-kernel durations, HIP events on the launch stream
+    phase_ms = ctx.forward_profile(Q, K, V, O, reps=max(3, args.steps))
+
+    BH = w.B * w.H
+    sum_m = ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r)
+    useful_flop = 4.0 * sum_m * w.head_dim * BH
+    exec_pairs = ctx.executed_pairs()
+    executed_flop = 4.0 * exec_pairs * w.head_dim * BH
+    useful_tflops = useful_flop / (ms_per_step * 1e-3) / 1e12
+    executed_tflops = executed_flop / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the image-query kernel.  Algorithmic work = 4*d FLOP per unmasked pair of its rows.
+    sum_m_image_rows = sum_m - w.n_text * w.N
+    img_flop = 4.0 * sum_m_image_rows * w.head_dim * BH
+    img_ms = phase_ms[0]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(w.name, {}).get("image_query_kernel_bytes_per_launch")
+    roofline = {
+        "bound": "mfma", "kernel": "clear_fwd_bf16_kernel<image queries>",
+        "achieved": img_flop / (img_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": img_flop / (img_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+        "kernel_ms": {"image_query": phase_ms[0], "text_query": phase_ms[1], "text_merge": phase_ms[2]},
+    }
+
+    result = {
+        "metric": "local-attn useful TFLOP/s (4*sumM*d)", "value": useful_tflops, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text,
+                   "gridH": w.gridH, "gridW": w.gridW, "r": w.r, "sum_M_per_head": sum_m},
+        "useful_tflops": useful_tflops, "executed_tflops": executed_tflops,
+        "useful_frac_of_mfma_peak": useful_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "executed_frac_of_mfma_peak": executed_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "executed_over_useful": executed_flop / useful_flop,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import clear_oracle as orc
+        rng = np.random.default_rng(12345)
+        rows_t = rng.choice(w.n_text, size=min(w.n_text, args.cpu_text_rows), replace=False) if w.n_text else np.zeros(0, int)
+        rows_i = w.n_text + rng.choice(w.gridH * w.gridW, size=min(w.gridH * w.gridW, args.cpu_image_rows), replace=False)
+        rows = np.sort(np.concatenate([rows_t, rows_i])).astype(np.int64)
+        h = w.H // 2
+        q, k, v = (t[0, h].float().cpu().double().numpy() for t in (Q, K, V))
+        tc0 = time.perf_counter()
+        ref, _, _, cnt = orc.attention_rows(q, k, v, rows, w.n_text, w.gridH, w.gridW, w.r, return_stats=True)
+        tc1 = time.perf_counter()
+        got = O[0, h][torch.from_numpy(rows).to(dev)].float().cpu().numpy()
+        diff = got - ref
+        cpu_flop = 4.0 * float(cnt.sum()) * w.head_dim
+        result["cpu_baseline"] = {
+            "value": cpu_flop / (tc1 - tc0) / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "%d text rows + %d image rows of head %d (fp64 dense-masked loop over all %d keys per row), %.1f s"
+                      % (len(rows_t), len(rows_i), h, w.N, tc1 - tc0),
+            "us_per_query_row": (tc1 - tc0) * 1e6 / len(rows),
+        }
+        result["check_vs_oracle"] = {"rows": int(len(rows)), "max_abs": float(np.abs(diff).max()),
+                                     "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
+    ctx.destroy()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -75,6 +75,17 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
                        int B, int H, int n_text, int gridH, int gridW, int head_dim, int r,
                        void* stream);
 
+/*
+ * Timing aid for benchmarks: same arguments and checks as clear_attn_forward, but runs the three
+ * kernels of a forward pass one after the other, each `reps` times back to back between two HIP
+ * events on `stream`, and SYNCHRONISES.  phase_ms[0..2] receive the average milliseconds per launch
+ * of (0) the image-query kernel (Eq. 3's windowed rows), (1) the text-query kernel (dense rows,
+ * split along the keys) and (2) the merge of those splits.  O holds a valid result afterwards.
+ */
+int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V,
+                               void* O, int B, int H, int n_text, int gridH, int gridW,
+                               int head_dim, int r, void* stream, int reps, float* phase_ms);
+
 /* Frees the context and its device memory.  NULL is a no-op.  The caller must have synchronised
  * any stream still running a forward of this context. */
 void clear_attn_destroy(clear_attn_ctx* ctx);

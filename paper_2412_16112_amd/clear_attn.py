@@ -14,7 +14,8 @@ CLEAR_BF16, CLEAR_F32 = 0, 1
 CLEAR_TILE_PARTIAL, CLEAR_TILE_FULL = 0, 1
 
 EXPORTS = [
-    "clear_attn_create", "clear_attn_reserve", "clear_attn_forward", "clear_attn_destroy",
+    "clear_attn_create", "clear_attn_reserve", "clear_attn_forward", "clear_attn_forward_profile",
+    "clear_attn_destroy",
     "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
     "clear_attn_last_error",
@@ -42,6 +43,7 @@ def lib():
         L.clear_attn_create.argtypes = [ctypes.POINTER(vp), i, i, i, i, i, i]
         L.clear_attn_reserve.argtypes = [vp, i]
         L.clear_attn_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp, i, ctypes.POINTER(ctypes.c_float)]
         L.clear_attn_destroy.argtypes = [vp]
         L.clear_attn_destroy.restype = None
         L.clear_attn_mask_count.argtypes = [i, i, i, i, ullp]
@@ -128,6 +130,17 @@ class ClearAttn:
         _check(lib().clear_attn_forward(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H,
                                         n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
+
+    def forward_profile(self, Q, K, V, O, reps=5, stream=None):
+        """Average milliseconds per launch of (image-query, text-query, merge) kernels; synchronises."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        ms = (ctypes.c_float * 3)()
+        _check(lib().clear_attn_forward_profile(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H,
+                                                n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s), reps, ms), self._ctx)
+        return tuple(float(x) for x in ms)
 
     def schedule_size(self):
         v = [ctypes.c_int(0) for _ in range(5)]

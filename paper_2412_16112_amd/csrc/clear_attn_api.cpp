@@ -194,8 +194,9 @@ int clear_attn_reserve(clear_attn_ctx* ctx, int BH)
     return CLEAR_OK;
 }
 
-int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
-                       int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+// Validates the arguments of a forward call and fills the kernel parameters.
+static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
+                           int n_text, int gridH, int gridW, int head_dim, int r, FwdParams* out)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (!Q || !K || !V || !O) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be non-NULL");
@@ -204,9 +205,9 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
     if ((long long)B * H > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "B*H must be <= 65535");
     if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
         return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
+    const long long N = (long long)n_text + (long long)gridH * gridW;
     {
         // O must not overlap an input
-        const long long N = (long long)n_text + (long long)gridH * gridW;
         const size_t bytes = (size_t)B * H * N * head_dim * (ctx->dtype == CLEAR_BF16 ? 2 : 4);
         const uintptr_t o0 = (uintptr_t)O, o1 = o0 + bytes;
         const void* ins[3] = {Q, K, V};
@@ -216,7 +217,6 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
         }
     }
     const int BH = B * H;
-    const long long N = (long long)n_text + (long long)gridH * gridW;
     const Schedule& s = ctx->sched;
     const long long n_q_tiles = (long long)s.n_qty * s.n_qtx;
     if (n_q_tiles * BH > 0x7fffffffLL) return fail(ctx, CLEAR_ERR_INVALID_ARG, "too many workgroups: B*H*query tiles must fit in 31 bits");
@@ -242,8 +242,52 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
         p.ws_o = ctx->d_ws_o;
         p.ws_ml = ctx->d_ws_ml;
     }
-    hipError_t e = (ctx->dtype == CLEAR_BF16) ? launch_bf16_d128(p, (hipStream_t)stream) : launch_f32_d64(p, (hipStream_t)stream);
+    *out = p;
+    return CLEAR_OK;
+}
+
+static hipError_t launch(const clear_attn_ctx* ctx, const FwdParams& p, hipStream_t stream, int phase)
+{
+    return (ctx->dtype == CLEAR_BF16) ? launch_bf16_d128(p, stream, phase) : launch_f32_d64(p, stream, phase);
+}
+
+int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
+                       int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+{
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &p);
+    if (rc != CLEAR_OK) return rc;
+    hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
+                               int n_text, int gridH, int gridW, int head_dim, int r, void* stream, int reps,
+                               float* phase_ms)
+{
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &p);
+    if (rc != CLEAR_OK) return rc;
+    if (!phase_ms || reps < 1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "phase_ms must be non-NULL and reps >= 1");
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    hipError_t e = hipEventCreate(&ev[0]);
+    if (e == hipSuccess) e = hipEventCreate(&ev[1]);
+    for (int phase = 0; phase < 3 && e == hipSuccess; ++phase) {
+        phase_ms[phase] = 0.f;
+        if (phase != kPhaseImage && n_text == 0) continue;
+        e = hipEventRecord(ev[0], st);
+        for (int i = 0; i < reps && e == hipSuccess; ++i) e = launch(ctx, p, st, phase);
+        if (e == hipSuccess) e = hipEventRecord(ev[1], st);
+        if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
+        phase_ms[phase] = ms / (float)reps;
+    }
+    if (ev[0]) (void)hipEventDestroy(ev[0]);
+    if (ev[1]) (void)hipEventDestroy(ev[1]);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("profile run failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }
 

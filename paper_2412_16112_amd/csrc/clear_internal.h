@@ -59,8 +59,10 @@ struct FwdParams {
 };
 
 // Launchers (kernels_bf16.hip, kernels_f32.hip).  Each returns the first HIP error met.
-hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream);
-hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream);
+// phase: kPhaseAll, or one of the three kernels of a forward pass (used to time them one by one).
+enum Phase : int { kPhaseAll = -1, kPhaseImage = 0, kPhaseTextQuery = 1, kPhaseTextMerge = 2 };
+hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase);
+hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
 int f32_text_queries_per_block();
 

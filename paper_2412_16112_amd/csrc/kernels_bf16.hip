@@ -405,14 +405,19 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 
 int bf16_text_queries_per_block() { return kBf16NWY * kBf16NWX * kTextQueriesPerWave; }
 
-hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream)
+hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase)
 {
     const int BH = p.B * p.H;
-    hipError_t e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_q_tiles, stream);
-    if (e != hipSuccess) return e;
-    if (p.n_text > 0) {
+    hipError_t e = hipSuccess;
+    if (phase == kPhaseAll || phase == kPhaseImage) {
+        e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_q_tiles, stream);
+        if (e != hipSuccess) return e;
+    }
+    if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextQuery)) {
         e = launch_fwd<kBf16NWY, kBf16NWX, true>(p, BH * p.n_tq_tiles * p.n_splits, stream);
         if (e != hipSuccess) return e;
+    }
+    if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextMerge)) {
         hipLaunchKernelGGL(clear_text_merge_kernel<__bf16>, dim3(BH * p.n_text), dim3(128), 0, stream, p, D);
         e = hipGetLastError();
     }

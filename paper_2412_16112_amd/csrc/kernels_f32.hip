@@ -185,16 +185,21 @@ __global__ void __launch_bounds__(D) clear_text_merge_f32_kernel(const FwdParams
 
 int f32_text_queries_per_block() { return NT; }
 
-hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream)
+hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase)
 {
     const int BH = p.B * p.H;
-    hipLaunchKernelGGL(clear_fwd_f32_kernel<false>, dim3(BH * p.n_q_tiles), dim3(NT), 0, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (p.n_text > 0) {
+    hipError_t e = hipSuccess;
+    if (phase == kPhaseAll || phase == kPhaseImage) {
+        hipLaunchKernelGGL(clear_fwd_f32_kernel<false>, dim3(BH * p.n_q_tiles), dim3(NT), 0, stream, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextQuery)) {
         hipLaunchKernelGGL(clear_fwd_f32_kernel<true>, dim3(BH * p.n_tq_tiles * p.n_splits), dim3(NT), 0, stream, p);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
+    }
+    if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextMerge)) {
         hipLaunchKernelGGL(clear_text_merge_f32_kernel, dim3(BH * p.n_text), dim3(D), 0, stream, p);
         e = hipGetLastError();
     }
