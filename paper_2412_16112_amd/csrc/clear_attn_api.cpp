@@ -138,6 +138,9 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
     rc = check_kernel(head_dim, dtype, &why);
     if (rc != CLEAR_OK) return fail(nullptr, rc, why);
 
+    if (dtype == CLEAR_BF16 && (long long)n_text + (long long)gridH * gridW > (1LL << 24) - 1)
+        return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "bf16 kernels address one head with 32-bit byte offsets: n_text + gridH*gridW must be < 2^24");
+
     clear_attn_ctx* ctx = new (std::nothrow) clear_attn_ctx;
     if (!ctx) return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory");
     ctx->n_text = n_text; ctx->gridH = gridH; ctx->gridW = gridW;

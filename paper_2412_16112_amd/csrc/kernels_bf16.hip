@@ -31,49 +31,57 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int D = 128;               // head_dim
 constexpr int ROW_BYTES = D * 2;     // one token row of K or V
-constexpr int KS = ROW_BYTES + 16;   // LDS row stride of K tiles (bytes): 16-byte pad spreads the 32 key rows of a b128 read over all banks
-constexpr int VS = ROW_BYTES + 64;   // LDS row stride of V tiles (bytes): 4 consecutive key rows x 64 B cover all 64 banks
 constexpr int TILE_KEYS = kKeyTileKeys;
+constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
+constexpr int NSTAGE = 4;                          // ring of staged key tiles (K + V = 32 KB each)
 constexpr float LAZY_RESCALE_LOG2 = 8.0f;  // re-base the running maximum only when it rises by more than 2^8
 constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)
 
-struct StageDesc {
-    int linear;       // 1: keys are tokens [a, a + 64) clipped to limit b; 0: image tile with origin (a, b)
-    long long a, b;
-};
+// LDS layout of a staged tile: 64 rows of 256 B, unpadded (the LDS-direct load writes 1 KB = 4 rows per
+// wave instruction), with the 16-byte chunks of each row permuted: logical chunk c of row k sits in
+// slot c ^ swz(k).  swz is a bijection on 16 consecutive rows (the 32 key rows of a K read spread over
+// all banks) and sends 4 consecutive rows to 4 different 64-byte quads (so does the transposed V read).
+__host__ __device__ constexpr int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
 __device__ __forceinline__ float wave_pair_max(float x)
 {
     // lanes l and l ^ 32 hold the two halves of one query's scores
-#if __has_builtin(__builtin_amdgcn_permlane32_swap)
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-#else
-    return fmaxf(x, __shfl_xor(x, 32));
-#endif
 }
 
 __device__ __forceinline__ float wave_pair_sum(float x)
 {
-#if __has_builtin(__builtin_amdgcn_permlane32_swap)
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-#else
-    return x + __shfl_xor(x, 32);
-#endif
+}
+
+// One 16-byte-per-lane load from global memory straight into LDS: the wave writes 1 KB starting at
+// lds_addr (wave-uniform), lane i at lds_addr + 16 i; lane i reads gbase + voff.  Counted by vmcnt.
+// Written as asm so that the compiler does not serialise later LDS reads behind it; the kernel waits
+// with explicit s_waitcnt vmcnt before the barrier that publishes the tile.
+__device__ __forceinline__ void load_to_lds_16B(const void* gbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));  // expcnt, lgkmcnt unconstrained
 }
 
 template <int NWY, int NWX, bool TEXTQ>
 __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const FwdParams p)
 {
     constexpr int NW = NWY * NWX;
-    constexpr int NT = NW * 64;
-    constexpr int NCH = (TILE_KEYS * 16) / NT;  // 16-byte chunks of K (and of V) per thread per stage
-    static_assert(NCH * NT == TILE_KEYS * 16, "tile must split evenly over the threads");
+    constexpr int NI = 16 / NW;       // 1 KB load instructions per wave per tile, for K and for V each
+    constexpr int LPT = 2 * NI;       // loads per thread per stage
+    static_assert(NI * NW == 16, "64 rows = 16 instructions of 4 rows");
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* const ldsK = smem;                          // [2][64][KS]
-    unsigned char* const ldsV = smem + 2 * TILE_KEYS * KS;     // [2][64][VS]
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NSTAGE][K tile | V tile]
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -108,7 +116,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
     // ---- this lane's query
     int wy0 = 0, wx0 = 0;  // origin of the wave's 4 x 8 query patch (image mode)
     int qy = 0, qx = 0;
-    long long q_token;
+    int q_token;
     bool q_valid, wave_has_queries;
     if (TEXTQ) {
         const int q0 = qt * (NW * 32) + wave * 32;
@@ -123,24 +131,28 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
         qx = wx0 + (qi & 7);
         q_valid = qy < p.gridH && qx < p.gridW;
         wave_has_queries = wy0 < p.gridH && wx0 < p.gridW;
-        q_token = (long long)p.n_text + (long long)imin(qy, p.gridH - 1) * p.gridW + imin(qx, p.gridW - 1);
+        q_token = p.n_text + imin(qy, p.gridH - 1) * p.gridW + imin(qx, p.gridW - 1);
     }
 
     // Q^T as MFMA B operand: 8 contraction steps of 16 channels; this lane supplies channels 16*s + 8*hh .. +7
     bf16x8 qf[8];
     {
-        const __bf16* qrow = Qh + q_token * D + 8 * hh;
+        const __bf16* qrow = Qh + (long long)q_token * D + 8 * hh;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
+        // pin the fragments in registers now: otherwise the wait for these loads lands inside the key loop,
+        // where it would also drain the tile prefetches
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
     }
 
-    // ---- stage list
+    // ---- stage list: tokens [lin_begin, lin_limit) in 64-key tiles, then (image mode) the CSR row
     int n_stages, n_lin_stages, csr_begin = 0;
-    long long lin_begin = 0, lin_limit = 0;
+    int lin_begin = 0, lin_limit = 0;
     if (TEXTQ) {
-        lin_begin = (long long)split * p.split_keys;
-        lin_limit = lin_begin + p.split_keys < p.N ? lin_begin + p.split_keys : p.N;
-        n_lin_stages = (int)((lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS);
+        lin_begin = split * p.split_keys;
+        lin_limit = (long long)lin_begin + p.split_keys < p.N ? lin_begin + p.split_keys : (int)p.N;
+        n_lin_stages = (lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS;
         n_stages = n_lin_stages;
     } else {
         lin_limit = p.n_text;
@@ -149,50 +161,40 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
         n_stages = n_lin_stages + (p.row_ptr[qt + 1] - csr_begin);
     }
 
-    auto stage_desc = [&](int i) -> StageDesc {
-        StageDesc sd;
+    // Tile origin of stage i: linear -> (first token, -1); image -> (row, col) of the 8 x 8 tile.
+    auto stage_origin = [&](int i, int& a, int& b) {
         if (i < n_lin_stages) {
-            sd.linear = 1;
-            sd.a = lin_begin + (long long)i * TILE_KEYS;
-            sd.b = lin_limit;
+            a = lin_begin + i * TILE_KEYS;
+            b = -1;
         } else {
             const int id = p.col_idx[csr_begin + i - n_lin_stages];
-            sd.linear = 0;
-            sd.a = (id / p.n_ktx) * kKeyTileH;
-            sd.b = (id % p.n_ktx) * kKeyTileW;
+            a = (id / p.n_ktx) * kKeyTileH;
+            b = (id % p.n_ktx) * kKeyTileW;
         }
-        return sd;
     };
 
-    // global -> register staging of one 64-key tile (addresses clamped to valid tokens; slots beyond
-    // the range or the grid are masked in the compute)
-    uint4 kreg[NCH], vreg[NCH];
-    auto load_stage = [&](const StageDesc& sd) {
+    // ---- LDS-direct staging.  Load instruction ii (0..15) of a tile covers rows 4 ii .. 4 ii + 3; lane i
+    // writes slot i % 16 of row 4 ii + i / 16 and therefore fetches logical chunk (i % 16) ^ swz(row).
+    // Addresses are clamped to valid tokens; slots beyond the range or the grid are masked in the compute.
+    auto issue_stage = [&](int i) {
+        int a, b;
+        stage_origin(i, a, b);
+        const unsigned buf = lds_base + (unsigned)(i % NSTAGE) * (2 * TILE_BYTES);
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const int c = tid + i * NT;
-            const int slot = c >> 4, cc = c & 15;
-            long long token;
-            if (sd.linear) {
-                token = sd.a + slot;
-                if (token > sd.b - 1) token = sd.b - 1;
+        for (int n = 0; n < NI; ++n) {
+            const int ii = wave * NI + n;
+            const int row = 4 * ii + (lane >> 4);
+            int token;
+            if (b < 0) {
+                token = imin(a + row, lin_limit - 1);
             } else {
-                const int ky = imin((int)sd.a + (slot >> 3), p.gridH - 1);
-                const int kx = imin((int)sd.b + (slot & 7), p.gridW - 1);
-                token = (long long)p.n_text + (long long)ky * p.gridW + kx;
+                const int ky = imin(a + (row >> 3), p.gridH - 1);
+                const int kx = imin(b + (row & 7), p.gridW - 1);
+                token = p.n_text + ky * p.gridW + kx;
             }
-            const long long off = token * ROW_BYTES + cc * 16;
-            kreg[i] = *(const uint4*)(Kh + off);
-            vreg[i] = *(const uint4*)(Vh + off);
-        }
-    };
-    auto store_stage = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const int c = tid + i * NT;
-            const int slot = c >> 4, cc = c & 15;
-            *(uint4*)(ldsK + buf * (TILE_KEYS * KS) + slot * KS + cc * 16) = kreg[i];
-            *(uint4*)(ldsV + buf * (TILE_KEYS * VS) + slot * VS + cc * 16) = vreg[i];
+            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
+            load_to_lds_16B(Kh, voff, buf + ii * 1024);
+            load_to_lds_16B(Vh, voff, buf + TILE_BYTES + ii * 1024);
         }
     };
 
@@ -206,125 +208,151 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
     float l_run = 0.f;     // this lane's share of the denominator
     const float c = p.scale_log2e;
 
-    // LDS read offsets that do not depend on the stage
-    const int k_read_off = qi * KS + 16 * hh;  // + 32*kb*KS + 32*s
-    // transpose load: within each group of 16 lanes, lane j addresses key row j/4 and channels 4*(j%4)..+3;
-    // it receives channel (lane % 16) of the group's 16-channel slice for the 4 key rows
-    const int j16 = lane & 15;
-    const int v_read_off = (4 * hh + (j16 >> 2)) * VS + 2 * (16 * ((lane >> 4) & 1) + 4 * (j16 & 3));
-
-    StageDesc cur = stage_desc(0);
-    if (n_stages > 0) {
-        load_stage(cur);
-        store_stage(0);
+    // ---- per-lane LDS read offsets inside a 32-key block (block and buffer offsets are added later)
+    // K operand: row qi, logical chunk 2 ks + hh
+    unsigned k_off[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_off[ks] = (unsigned)(qi * ROW_BYTES + (((2 * ks + hh) ^ swz(qi)) << 4));
+    // V operand (transpose load): within each group of 16 lanes, lane j addresses key row j/4 and
+    // channels 4*(j%4)..+3 of the group's 16-channel slice; it receives channel (lane % 16) for 4 rows.
+    // Rows of the first load: 4 hh + j/4 (+ 16 s2); of the second: + 8.
+    unsigned v_off[4][2];
+    {
+        const int j = lane & 15, g2 = (lane >> 4) & 1;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) {
+                const int row = 4 * hh + (j >> 2) + 8 * hi;  // swz(row + 16 s2 + 32 kb) == swz(row)
+                const int chunk = 4 * db + 2 * g2 + ((j & 3) >> 1);
+                v_off[db][hi] = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
+            }
     }
-    __syncthreads();
+
+    // ---- prologue: NSTAGE - 1 tiles in flight
+#pragma unroll
+    for (int i = 0; i < NSTAGE - 1; ++i)
+        if (i < n_stages) issue_stage(i);
 
     for (int st = 0; st < n_stages; ++st) {
-        const int buf = st & 1;
-        StageDesc nxt = cur;
-        if (st + 1 < n_stages) {
-            nxt = stage_desc(st + 1);
-            load_stage(nxt);
+        // tile st has landed once at most NSTAGE - 2 younger tiles are outstanding (all of them exist
+        // only away from the tail)
+        if (st + NSTAGE - 2 < n_stages)
+            wait_vmcnt<(NSTAGE - 2) * LPT>();
+        else
+            wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();  // every wave's part of tile st is in LDS; every wave is done with tile st - 1
+        asm volatile("" ::: "memory");
+        if (st + NSTAGE - 1 < n_stages) issue_stage(st + NSTAGE - 1);  // overwrites the buffer of tile st - 1
+
+        int ta, tb;
+        stage_origin(st, ta, tb);
+        const bool linear = tb < 0;
+        int cls[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            if (!wave_has_queries)
+                cls[kb] = kBlockSkip;
+            else if (linear)
+                cls[kb] = classify_linear_block(ta + 32 * kb, 32, lin_limit);
+            else
+                cls[kb] = TEXTQ ? kBlockSkip
+                                : classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH * kb, tb, kKeyBlockH,
+                                                       kKeyBlockW, p.gridH, p.gridW, p.r2);
         }
+        if (cls[0] == kBlockSkip && cls[1] == kBlockSkip) continue;
 
-        if (wave_has_queries) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                int cls;
-                if (cur.linear)
-                    cls = classify_linear_block(cur.a + 32 * kb, 32, cur.b);
-                else
-                    cls = TEXTQ ? kBlockSkip
-                                : classify_image_block(wy0, wx0, kWaveQH, kWaveQW, (int)cur.a + kKeyBlockH * kb, (int)cur.b,
-                                                       kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
-                if (cls == kBlockSkip) continue;
+        const unsigned char* const tileK = smem + (st % NSTAGE) * (2 * TILE_BYTES);
+        const unsigned char* const tileV = tileK + TILE_BYTES;
 
-                // S^T = K_blk Q^T
-                f32x16 s;
+        // S^T = K_blk Q^T for the active blocks
+        f32x16 s[2];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = 0.f;
-                const unsigned char* kb_ptr = ldsK + buf * (TILE_KEYS * KS) + kb * 32 * KS + k_read_off;
+        for (int kb = 0; kb < 2; ++kb) {
+            if (cls[kb] == kBlockSkip) {
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 a = *(const bf16x8*)(kb_ptr + 32 * ks);
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
-                }
-
-                // element mask: register r of this lane is key slot 8*(r/4) + 4*hh + r%4 of the block
-                if (cls == kBlockPartial) {
-                    if (cur.linear) {
-                        const long long base = cur.a + 32 * kb + 4 * hh;
+                for (int r = 0; r < 16; ++r) s[kb][r] = -INFINITY;
+                continue;
+            }
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (base + 8 * (r >> 2) + (r & 3) >= cur.b) s[r] = -INFINITY;
-                    } else {
-                        const int ky0 = (int)cur.a + kKeyBlockH * kb, kx0 = (int)cur.b + 4 * hh;
-                        int dx2[4];
-                        bool xin[4];
+            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const int dx = kx0 + t - qx;
-                            dx2[t] = dx * dx;
-                            xin[t] = kx0 + t < p.gridW;
-                        }
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 a = *(const bf16x8*)(tileK + kb * 32 * ROW_BYTES + k_off[ks]);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+            }
+            // element mask: register r of this lane is key slot 8*(r/4) + 4*hh + r%4 of the block
+            if (cls[kb] == kBlockPartial) {
+                if (linear) {
+                    const int base = ta + 32 * kb + 4 * hh;
 #pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int dy = ky0 + g - qy;
-                            const int lim = (ky0 + g < p.gridH) ? p.r2 - dy * dy : 0;  // dx^2 must stay below lim
+                    for (int r = 0; r < 16; ++r)
+                        if (base + 8 * (r >> 2) + (r & 3) >= lin_limit) s[kb][r] = -INFINITY;
+                } else {
+                    const int ky0 = ta + kKeyBlockH * kb, kx0 = tb + 4 * hh;
+                    int dx2[4];
 #pragma unroll
-                            for (int t = 0; t < 4; ++t)
-                                if (!(xin[t] && dx2[t] < lim)) s[4 * g + t] = -INFINITY;
-                        }
+                    for (int t = 0; t < 4; ++t) {
+                        const int dx = kx0 + t - qx;
+                        dx2[t] = (kx0 + t < p.gridW) ? dx * dx : 0x7fffffff;  // columns beyond the grid never pass
                     }
-                }
-
-                // online softmax (Eq. 1), lazily re-based
-                float mx = fmaxf(s[0], s[1]);
 #pragma unroll
-                for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
-                mx = wave_pair_max(mx);
-                const float m_new = fmaxf(m_run, mx);
-                if (__builtin_amdgcn_ballot_w64((m_new - m_run) * c > LAZY_RESCALE_LOG2) != 0) {
-                    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                    l_run *= alpha;
+                    for (int g = 0; g < 4; ++g) {
+                        const int dy = ky0 + g - qy;
+                        const int lim = (ky0 + g < p.gridH) ? p.r2 - dy * dy : 0;  // dx^2 must stay below lim
 #pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-                    m_run = m_new;
-                }
-                const float mc = m_run * c;
-                bf16x8 pf[2];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -mc));
-                    l_run += pv;
-                    pf[r >> 3][r & 7] = (__bf16)pv;
-                }
-
-                // O^T += V_blk^T P^T: contraction step s2 pairs P registers 8*s2 .. 8*s2+7 with key slots
-                // 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}
-                const unsigned char* vb_ptr = ldsV + buf * (TILE_KEYS * VS) + kb * 32 * VS + v_read_off;
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-#pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        const unsigned char* a0 = vb_ptr + (16 * s2) * VS + db * 64;
-                        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(a0));
-                        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(a0 + 8 * VS));
-                        union { struct { short4v lo, hi; } h; bf16x8 v; } u;
-                        u.h.lo = lo;
-                        u.h.hi = hi;
-                        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[s2], oacc[db], 0, 0, 0);
+                        for (int t = 0; t < 4; ++t)
+                            if (!(dx2[t] < lim)) s[kb][4 * g + t] = -INFINITY;
                     }
                 }
             }
         }
 
-        if (st + 1 < n_stages) store_stage(buf ^ 1);
-        __syncthreads();
-        cur = nxt;
+        // online softmax (Eq. 1) over the 64 keys, lazily re-based
+        float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+        mx = wave_pair_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        if (__builtin_amdgcn_ballot_w64((m_new - m_run) * c > LAZY_RESCALE_LOG2) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            m_run = m_new;
+        }
+        const float mc = m_run * c;
+
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            if (cls[kb] == kBlockSkip) continue;
+            bf16x8 pf[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], c, -mc));
+                l_run += pv;
+                pf[r >> 3][r & 7] = (__bf16)pv;
+            }
+            // O^T += V_blk^T P^T: contraction step s2 pairs P registers 8*s2 .. 8*s2+7 with key slots
+            // 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}
+            const unsigned char* vb = tileV + kb * 32 * ROW_BYTES;
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + v_off[db][0]));
+                    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + v_off[db][1]));
+                    union { struct { short4v lo, hi; } h; bf16x8 v; } u;
+                    u.h.lo = lo;
+                    u.h.hi = hi;
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[s2], oacc[db], 0, 0, 0);
+                }
+            }
+        }
     }
 
     // ---- epilogue
@@ -348,7 +376,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
     } else {
         if (q_valid) {
             const float inv = 1.0f / l_tot;
-            __bf16* orow = (__bf16*)p.O + head_off + q_token * D;
+            __bf16* orow = (__bf16*)p.O + head_off + (long long)q_token * D;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -389,7 +417,7 @@ __global__ void __launch_bounds__(128) clear_text_merge_kernel(const FwdParams p
 template <int NWY, int NWX, bool TEXTQ>
 hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 {
-    const size_t smem = 2 * TILE_KEYS * (KS + VS);
+    const size_t smem = (size_t)NSTAGE * 2 * TILE_BYTES;
     auto kern = clear_fwd_bf16_kernel<NWY, NWX, TEXTQ>;
     static bool attr_set = false;  // the attribute is per function, set once per process
     if (!attr_set) {
