@@ -17,6 +17,8 @@
 // against its own 4 x 8 query patch and skips the blocks its disc cannot reach.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "block_class.h"
 #include "clear_internal.h"
 
@@ -34,7 +36,7 @@ constexpr int ROW_BYTES = D * 2;     // one token row of K or V
 constexpr int TILE_KEYS = kKeyTileKeys;
 constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
 constexpr int NSTAGE = 4;                          // ring of staged key tiles (K + V = 32 KB each)
-constexpr float LAZY_RESCALE_LOG2 = 8.0f;  // re-base the running maximum only when it rises by more than 2^8
+constexpr float FAST_HEADROOM_LOG2 = 60.0f;  // the fast pass lets 2^{(s - m_ref) c} grow up to 2^60 before it gives up
 constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)
 
 // LDS layout of a staged tile: 64 rows of 256 B, unpadded (the LDS-direct load writes 1 KB = 4 rows per
@@ -70,6 +72,265 @@ __device__ __forceinline__ void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));  // expcnt, lgkmcnt unconstrained
+}
+
+struct WaveState {
+    f32x16 oacc[4];  // O^T tiles: channel 32*db + 8*(reg/4) + 4*hh + reg%4 of this lane's query
+    float m_run;     // running maximum, raw logits (may lag the true maximum by < 2^8 in the exponent)
+    float l_run;     // this lane's share of the denominator
+    float c;         // log2(e) / sqrt(head_dim)
+};
+
+struct LaneOffsets {
+    unsigned k[8];     // K operand reads, one per contraction step
+    unsigned v[4][2];  // V transpose reads, per 32-channel slice and per half of the 16-key contraction step
+};
+
+enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2 };
+
+struct MaskArgs {
+    int a, b;  // linear: first token of the tile, token limit; image: tile origin (row, col)
+    int hh, qy, qx, gridH, gridW, r2;
+};
+
+// Sets the scores of inadmissible (query, key) pairs of key block kb to -inf.  Register r of this lane
+// is key slot 8*(r/4) + 4*hh + r%4 of the block (Eq. 3 for image keys; the token limit for linear tiles).
+template <int MASK>
+__device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma)
+{
+    if (MASK == kMaskLinear) {
+        const int base = ma.a + 32 * kb + 4 * ma.hh;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (base + 8 * (r >> 2) + (r & 3) >= ma.b) s[r] = -INFINITY;
+    } else if (MASK == kMaskImage) {
+        const int ky0 = ma.a + kKeyBlockH * kb, kx0 = ma.b + 4 * ma.hh;
+        int dx2[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int dx = kx0 + t - ma.qx;
+            dx2[t] = (kx0 + t < ma.gridW) ? dx * dx : 0x7fffffff;  // columns beyond the grid never pass
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int dy = ky0 + g - ma.qy;
+            const int lim = (ky0 + g < ma.gridH) ? ma.r2 - dy * dy : 0;  // dx^2 must stay below lim
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (!(dx2[t] < lim)) s[4 * g + t] = -INFINITY;
+        }
+    }
+}
+
+// p = 2^{(s - m) c} for the 16 scores of one block; returns their sum; packs them as the B operand of P V.
+__device__ __forceinline__ float exp_block(const f32x16& s, float c, float mc, bf16x8 (&pf)[2])
+{
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -mc));
+        sum += pv;
+        pf[r >> 3][r & 7] = (__bf16)pv;
+    }
+    return sum;
+}
+
+__device__ __forceinline__ float max_block(const f32x16& s)
+{
+    float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    return mx;
+}
+
+// Scheduling hints: ask the backend to emit, in this order, `n` instructions of the given class.
+// Classes (LLVM AMDGPU sched_group_barrier masks): 0x2 VALU, 0x8 MFMA, 0x100 LDS read.
+#define SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier((mask), (n), 0)
+
+__device__ __forceinline__ bf16x8 read_v_operand(const unsigned char* vb, int s2, unsigned off_lo, unsigned off_hi)
+{
+    const short4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + off_lo));
+    const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + off_hi));
+    union { struct { short4v lo, hi; } h; bf16x8 v; } u;
+    u.h.lo = lo4;
+    u.h.hi = hi4;
+    return u.v;
+}
+
+__device__ __forceinline__ f32x16 qk_block(const unsigned char* kblk, const LaneOffsets& lo, const bf16x8 (&qf)[8])
+{
+    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *(const bf16x8*)(kblk + lo.k[ks]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
+    }
+    return s;
+}
+
+// O^T += V_blk^T P^T for one 32-key block.  The contraction step s2 pairs P registers 8*s2 .. 8*s2+7
+// with key slots 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}.
+__device__ __forceinline__ void pv_block(f32x16 (&oacc)[4], const unsigned char* vblk, const LaneOffsets& lo, const bf16x8 (&pf)[2])
+{
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(vblk, s2, lo.v[db][0], lo.v[db][1]), pf[s2], oacc[db], 0, 0, 0);
+}
+
+// Careful pass, one staged tile: block by block, exact running maximum, O and the denominator rescaled
+// at every block (Eq. 1 as a textbook online softmax).  Slow; only runs when the fast pass gave up.
+__device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo, const unsigned char* tileK,
+                                              int cls0, int cls1, bool linear, const MaskArgs& ma)
+{
+#pragma unroll 1
+    for (int kb = 0; kb < 2; ++kb) {
+        const int cls = kb ? cls1 : cls0;
+        if (cls == kBlockSkip) continue;
+        f32x16 s = qk_block(tileK + kb * 32 * ROW_BYTES, lo, qf);
+        if (cls == kBlockPartial) {
+            if (linear)
+                apply_mask<kMaskLinear>(s, kb, ma);
+            else
+                apply_mask<kMaskImage>(s, kb, ma);
+        }
+        const float m_new = fmaxf(ws.m_run, wave_pair_max(max_block(s)));
+        const float alpha = __builtin_amdgcn_exp2f((ws.m_run - m_new) * ws.c);
+        ws.l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ws.oacc[db][r] *= alpha;
+        ws.m_run = m_new;
+        bf16x8 pf[2];
+        ws.l_run += exp_block(s, ws.c, m_new * ws.c, pf);
+        pv_block(ws.oacc, tileK + TILE_BYTES + kb * 32 * ROW_BYTES, lo, pf);
+    }
+}
+
+// Reference maximum of the fast pass: a query adopts the maximum of the first block in which it sees an
+// admissible key (nothing has been accumulated for it before, so nothing needs rescaling) and keeps it.
+// Returns the lanes whose scores outgrow the headroom; the fast pass result is discarded if any does.
+__device__ __forceinline__ unsigned long long adopt_reference(WaveState& ws, float mx_pair)
+{
+    ws.m_run = (ws.m_run == M_INIT) ? fmaxf(mx_pair, M_INIT) : ws.m_run;
+    return __builtin_amdgcn_ballot_w64((mx_pair - ws.m_run) * ws.c > FAST_HEADROOM_LOG2);
+}
+
+// Pins the instruction order: nothing is scheduled across this point.
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// p = 2^{s c - mc} for elements [R0, R1) of one block; adds them to sum; packs them as bf16.
+template <int R0, int R1>
+__device__ __forceinline__ void exp_slice(const f32x16& s, float c, float mc, float& sum, bf16x8 (&pf)[2])
+{
+#pragma unroll
+    for (int r = R0; r < R1; ++r) {
+        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -mc));
+        sum += pv;
+        pf[r >> 3][r & 7] = (__bf16)pv;
+    }
+}
+
+__device__ __forceinline__ bf16x8 read_k_operand(const unsigned char* kblk, unsigned off)
+{
+    return *(const bf16x8*)(kblk + off);
+}
+
+// Fast pass, one staged tile.  The reference maximum of a query never moves once set, so O is only
+// ever touched by the matrix pipeline and there is no data-dependent branch.
+// NB = 2 processes both 32-key blocks as one hand-ordered pipeline of 32 matrix instructions:
+//   slots  0- 7  S of block 0
+//   slots  8-15  S of block 1          | mask, maximum, reference, P[0..7] of block 0
+//   slots 16-19  P V of block 0, keys of P[0..7]   | P[8..15] of block 0
+//   slots 20-23  P V of block 0, keys of P[8..15]  | mask, maximum, reference, P[0..7] of block 1
+//   slots 24-27  P V of block 1, keys of P[0..7]   | P[8..15] of block 1
+//   slots 28-31  P V of block 1, keys of P[8..15]
+// LDS operands are read two slots ahead of the matrix instruction that consumes them.
+// NB = 1 processes block kb0 only.  Returns the lanes that ran out of headroom.
+template <int NB, int MASK>
+__device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo,
+                                                         const unsigned char* tileK, int kb0, const MaskArgs& ma)
+{
+    const unsigned char* const kbase = tileK + kb0 * 32 * ROW_BYTES;
+    const unsigned char* const vbase = kbase + TILE_BYTES;
+    const float c = ws.c;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bf16x8 pf0[2], pf1[2];
+    unsigned long long bad;
+    float sum = 0.f;
+
+    if (NB == 1) {
+        f32x16 s0 = qk_block(kbase, lo, qf);
+        apply_mask<MASK>(s0, kb0, ma);
+        bad = adopt_reference(ws, wave_pair_max(max_block(s0)));
+        sum = exp_block(s0, c, ws.m_run * c, pf0);
+        pv_block(ws.oacc, vbase, lo, pf0);
+        ws.l_run += sum;
+        return bad;
+    }
+
+    // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
+    auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
+    auto v_operand = [&](int slot) {
+        const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
+        return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
+    };
+    bf16x8 op[3];
+    op[0] = k_operand(0);
+    op[1] = k_operand(1);
+    f32x16 s0 = zero, s1 = zero;
+    float mc = 0.f;
+#pragma unroll
+    for (int slot = 0; slot < 32; ++slot) {
+        // prefetch the operand of slot + 2
+        if (slot + 2 < 16)
+            op[(slot + 2) % 3] = k_operand(slot + 2);
+        else if (slot + 2 < 32)
+            op[(slot + 2) % 3] = v_operand(slot + 2);
+        // matrix instruction of this slot
+        if (slot < 8)
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot], s0, 0, 0, 0);
+        else if (slot < 16)
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot - 8], s1, 0, 0, 0);
+        else if (slot < 24)
+            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], pf0[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+        else
+            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], pf1[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+        // vector work riding along
+        if (slot == 8) {
+            apply_mask<MASK>(s0, kb0, ma);
+            bad = adopt_reference(ws, wave_pair_max(max_block(s0)));
+            mc = ws.m_run * c;
+        }
+        if (slot == 9) exp_slice<0, 1>(s0, c, mc, sum, pf0);
+        if (slot == 10) exp_slice<1, 2>(s0, c, mc, sum, pf0);
+        if (slot == 11) exp_slice<2, 3>(s0, c, mc, sum, pf0);
+        if (slot == 12) exp_slice<3, 4>(s0, c, mc, sum, pf0);
+        if (slot == 13) exp_slice<4, 5>(s0, c, mc, sum, pf0);
+        if (slot == 14) exp_slice<5, 6>(s0, c, mc, sum, pf0);
+        if (slot == 15) exp_slice<6, 8>(s0, c, mc, sum, pf0);
+        if (slot == 16) exp_slice<8, 10>(s0, c, mc, sum, pf0);
+        if (slot == 17) exp_slice<10, 12>(s0, c, mc, sum, pf0);
+        if (slot == 18) exp_slice<12, 14>(s0, c, mc, sum, pf0);
+        if (slot == 19) exp_slice<14, 16>(s0, c, mc, sum, pf0);
+        if (slot == 20) {
+            apply_mask<MASK>(s1, kb0 + 1, ma);
+            bad |= adopt_reference(ws, wave_pair_max(max_block(s1)));
+            mc = ws.m_run * c;
+        }
+        if (slot == 21) exp_slice<0, 2>(s1, c, mc, sum, pf1);
+        if (slot == 22) exp_slice<2, 5>(s1, c, mc, sum, pf1);
+        if (slot == 23) exp_slice<5, 8>(s1, c, mc, sum, pf1);
+        if (slot == 24) exp_slice<8, 10>(s1, c, mc, sum, pf1);
+        if (slot == 25) exp_slice<10, 12>(s1, c, mc, sum, pf1);
+        if (slot == 26) exp_slice<12, 14>(s1, c, mc, sum, pf1);
+        if (slot == 27) exp_slice<14, 16>(s1, c, mc, sum, pf1);
+        SCHED_FENCE();
+    }
+    ws.l_run += sum;
+    return bad;
 }
 
 template <int NWY, int NWX, bool TEXTQ>
@@ -199,24 +460,17 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
     };
 
     // ---- running softmax state: one query per lane (shared with lane ^ 32)
-    f32x16 oacc[4];  // O^T tiles: channel 32*db + 8*(reg/4) + 4*hh + reg%4 of this lane's query
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m_run = M_INIT;  // running maximum, raw logits (may lag the true maximum by < 2^8 in the exponent)
-    float l_run = 0.f;     // this lane's share of the denominator
-    const float c = p.scale_log2e;
+    WaveState ws;
+    ws.c = p.scale_log2e;
 
     // ---- per-lane LDS read offsets inside a 32-key block (block and buffer offsets are added later)
     // K operand: row qi, logical chunk 2 ks + hh
-    unsigned k_off[8];
+    LaneOffsets lo;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) k_off[ks] = (unsigned)(qi * ROW_BYTES + (((2 * ks + hh) ^ swz(qi)) << 4));
+    for (int ks = 0; ks < 8; ++ks) lo.k[ks] = (unsigned)(qi * ROW_BYTES + (((2 * ks + hh) ^ swz(qi)) << 4));
     // V operand (transpose load): within each group of 16 lanes, lane j addresses key row j/4 and
     // channels 4*(j%4)..+3 of the group's 16-channel slice; it receives channel (lane % 16) for 4 rows.
     // Rows of the first load: 4 hh + j/4 (+ 16 s2); of the second: + 8.
-    unsigned v_off[4][2];
     {
         const int j = lane & 15, g2 = (lane >> 4) & 1;
 #pragma unroll
@@ -225,16 +479,19 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
             for (int hi = 0; hi < 2; ++hi) {
                 const int row = 4 * hh + (j >> 2) + 8 * hi;  // swz(row + 16 s2 + 32 kb) == swz(row)
                 const int chunk = 4 * db + 2 * g2 + ((j & 3) >> 1);
-                v_off[db][hi] = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
+                lo.v[db][hi] = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
             }
     }
 
-    // ---- prologue: NSTAGE - 1 tiles in flight
-#pragma unroll
-    for (int i = 0; i < NSTAGE - 1; ++i)
-        if (i < n_stages) issue_stage(i);
-
-    for (int st = 0; st < n_stages; ++st) {
+    // Per-stage bookkeeping shared by both paths: wait for tile st, publish it, refill the ring, and
+    // classify the tile's two key blocks against this wave's query patch.
+    struct StageInfo {
+        int cls0, cls1;
+        bool linear;
+        const unsigned char* tileK;
+        MaskArgs ma;
+    };
+    auto begin_stage = [&](int st) -> StageInfo {
         // tile st has landed once at most NSTAGE - 2 younger tiles are outstanding (all of them exist
         // only away from the tail)
         if (st + NSTAGE - 2 < n_stages)
@@ -245,116 +502,94 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
         asm volatile("" ::: "memory");
         if (st + NSTAGE - 1 < n_stages) issue_stage(st + NSTAGE - 1);  // overwrites the buffer of tile st - 1
 
+        StageInfo si;
         int ta, tb;
         stage_origin(st, ta, tb);
-        const bool linear = tb < 0;
-        int cls[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (!wave_has_queries)
-                cls[kb] = kBlockSkip;
-            else if (linear)
-                cls[kb] = classify_linear_block(ta + 32 * kb, 32, lin_limit);
-            else
-                cls[kb] = TEXTQ ? kBlockSkip
-                                : classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH * kb, tb, kKeyBlockH,
-                                                       kKeyBlockW, p.gridH, p.gridW, p.r2);
+        si.linear = tb < 0;
+        if (!wave_has_queries) {
+            si.cls0 = si.cls1 = kBlockSkip;
+        } else if (si.linear) {
+            si.cls0 = classify_linear_block(ta, 32, lin_limit);
+            si.cls1 = classify_linear_block(ta + 32, 32, lin_limit);
+        } else if (TEXTQ) {
+            si.cls0 = si.cls1 = kBlockSkip;
+        } else {
+            si.cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+            si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH,
+                                           p.gridW, p.r2);
         }
-        if (cls[0] == kBlockSkip && cls[1] == kBlockSkip) continue;
+        si.tileK = smem + (st % NSTAGE) * (2 * TILE_BYTES);
+        si.ma.hh = hh;
+        si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
+        si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
+        si.ma.qy = qy; si.ma.qx = qx; si.ma.gridH = p.gridH; si.ma.gridW = p.gridW; si.ma.r2 = p.r2;
+        return si;
+    };
 
-        const unsigned char* const tileK = smem + (st % NSTAGE) * (2 * TILE_BYTES);
-        const unsigned char* const tileV = tileK + TILE_BYTES;
-
-        // S^T = K_blk Q^T for the active blocks
-        f32x16 s[2];
+    // One pass over the stage list.  CAREFUL = false: fast pass (fixed reference maximum); returns the
+    // lanes that ran out of headroom.  CAREFUL = true: exact online softmax, slow.
+    auto run_pass = [&](auto careful_tag) -> unsigned long long {
+        constexpr bool CAREFUL = decltype(careful_tag)::value;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (cls[kb] == kBlockSkip) {
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[kb][r] = -INFINITY;
-                continue;
+            for (int r = 0; r < 16; ++r) ws.oacc[db][r] = 0.f;
+        ws.m_run = M_INIT;
+        ws.l_run = 0.f;
+        unsigned long long bad = 0;
+        // prologue: NSTAGE - 1 tiles in flight
+#pragma unroll
+        for (int i = 0; i < NSTAGE - 1; ++i)
+            if (i < n_stages) issue_stage(i);
+        if (CAREFUL) {
+            for (int st = 0; st < n_stages; ++st) {
+                const StageInfo si = begin_stage(st);
+                careful_stage(ws, qf, lo, si.tileK, si.cls0, si.cls1, si.linear, si.ma);
             }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 a = *(const bf16x8*)(tileK + kb * 32 * ROW_BYTES + k_off[ks]);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+        } else {
+            // Three consecutive ranges of the stage list, one loop each, so that every loop body has a
+            // single shape: whole 64-key linear tiles, the ragged linear tile (at most one), image tiles.
+            const int n_lin_whole = (lin_limit - lin_begin) / TILE_KEYS;
+            int st = 0;
+            for (; st < n_lin_whole; ++st) {
+                const StageInfo si = begin_stage(st);
+                if (wave_has_queries) bad |= fast_stage<2, kMaskNone>(ws, qf, lo, si.tileK, 0, si.ma);
             }
-            // element mask: register r of this lane is key slot 8*(r/4) + 4*hh + r%4 of the block
-            if (cls[kb] == kBlockPartial) {
-                if (linear) {
-                    const int base = ta + 32 * kb + 4 * hh;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (base + 8 * (r >> 2) + (r & 3) >= lin_limit) s[kb][r] = -INFINITY;
-                } else {
-                    const int ky0 = ta + kKeyBlockH * kb, kx0 = tb + 4 * hh;
-                    int dx2[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int dx = kx0 + t - qx;
-                        dx2[t] = (kx0 + t < p.gridW) ? dx * dx : 0x7fffffff;  // columns beyond the grid never pass
-                    }
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int dy = ky0 + g - qy;
-                        const int lim = (ky0 + g < p.gridH) ? p.r2 - dy * dy : 0;  // dx^2 must stay below lim
-#pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            if (!(dx2[t] < lim)) s[kb][4 * g + t] = -INFINITY;
-                    }
+            for (; st < n_lin_stages; ++st) {
+                const StageInfo si = begin_stage(st);
+                if (si.cls0 != kBlockSkip && si.cls1 != kBlockSkip)
+                    bad |= fast_stage<2, kMaskLinear>(ws, qf, lo, si.tileK, 0, si.ma);
+                else if (si.cls0 != kBlockSkip)
+                    bad |= fast_stage<1, kMaskLinear>(ws, qf, lo, si.tileK, 0, si.ma);
+            }
+            if (!TEXTQ) {
+                for (; st < n_stages; ++st) {
+                    const StageInfo si = begin_stage(st);
+                    if (si.cls0 != kBlockSkip && si.cls1 != kBlockSkip)
+                        bad |= fast_stage<2, kMaskImage>(ws, qf, lo, si.tileK, 0, si.ma);
+                    else if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip)
+                        bad |= fast_stage<1, kMaskImage>(ws, qf, lo, si.tileK, si.cls0 != kBlockSkip ? 0 : 1, si.ma);
                 }
             }
         }
+        return bad;
+    };
 
-        // online softmax (Eq. 1) over the 64 keys, lazily re-based
-        float mx = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-        mx = wave_pair_max(mx);
-        const float m_new = fmaxf(m_run, mx);
-        if (__builtin_amdgcn_ballot_w64((m_new - m_run) * c > LAZY_RESCALE_LOG2) != 0) {
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            m_run = m_new;
-        }
-        const float mc = m_run * c;
-
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (cls[kb] == kBlockSkip) continue;
-            bf16x8 pf[2];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], c, -mc));
-                l_run += pv;
-                pf[r >> 3][r & 7] = (__bf16)pv;
-            }
-            // O^T += V_blk^T P^T: contraction step s2 pairs P registers 8*s2 .. 8*s2+7 with key slots
-            // 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}
-            const unsigned char* vb = tileV + kb * 32 * ROW_BYTES;
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + v_off[db][0]));
-                    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + v_off[db][1]));
-                    union { struct { short4v lo, hi; } h; bf16x8 v; } u;
-                    u.h.lo = lo;
-                    u.h.hi = hi;
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[s2], oacc[db], 0, 0, 0);
-                }
-            }
-        }
+    // Fast pass first.  If any query of the workgroup met a score more than 2^FAST_HEADROOM_LOG2 above
+    // its reference (in the exponent), the whole workgroup repeats the tile walk with the careful pass.
+    __shared__ int s_redo;
+    if (tid == 0) s_redo = 0;  // ordered before any write below by the barriers of the stage loop
+    const unsigned long long bad = run_pass(std::false_type{});
+    if (bad != 0 && lane == 0) s_redo = 1;
+    __syncthreads();
+    if (s_redo != 0) {
+        __syncthreads();  // every wave has read the flag and left the ring buffers
+        run_pass(std::true_type{});
     }
 
+    const float m_run = ws.m_run;
+    const float l_run = ws.l_run;
+    f32x16(&oacc)[4] = ws.oacc;
     // ---- epilogue
     const float l_tot = wave_pair_sum(l_run);
     if (TEXTQ) {
