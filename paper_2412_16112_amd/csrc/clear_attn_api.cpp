@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <string>
@@ -18,7 +19,11 @@ struct clear_attn_ctx {
     int device = 0;
     Schedule sched;
     int* d_row_ptr = nullptr;
-    int* d_col_idx = nullptr;
+    int* d_col_idx = nullptr;   // kernel order: tiles inside the grid first, border tiles last
+    int* d_n_plain = nullptr;
+    unsigned long long* d_mask_tbl = nullptr;
+    int mask_ry = 0, mask_rx = 0;
+    int num_cus = 256;
     // text-query workspace, grown on demand
     int ws_BH = 0;         // capacity in (batch*head) units
     int ws_max_splits = 0;  // splits the workspace is sized for
@@ -65,14 +70,28 @@ static int max_text_splits(long long N)
     return (int)s;
 }
 
-// Splits for a given batch*heads: enough workgroups to fill 256 CUs a few times over.
-static void choose_text_splits(long long N, int BH, int n_tq_tiles, int* n_splits, int* split_keys)
+// Splits for a given batch*heads: at least two workgroups per CU when the keys allow it, and a workgroup
+// count that fills whole rounds of the CUs (a partial last round idles most of the chip).
+static void choose_text_splits(long long N, int BH, int n_tq_tiles, int num_cus, int* n_splits, int* split_keys)
 {
     const int max_s = max_text_splits(N);
-    long long want = (1024 + (long long)BH * n_tq_tiles - 1) / ((long long)BH * n_tq_tiles);
-    if (want < 1) want = 1;
-    if (want > max_s) want = max_s;
-    long long keys = (N + want - 1) / want;
+    const long long units = (long long)BH * n_tq_tiles;
+    int best = 1;
+    double best_score = -1.0;
+    for (int s = 1; s <= max_s; ++s) {
+        long long keys = (N + s - 1) / s;
+        keys = ((keys + kKeyTileKeys - 1) / kKeyTileKeys) * kKeyTileKeys;
+        const long long real = (N + keys - 1) / keys;  // splits that actually hold keys
+        const long long wgs = units * real;
+        const long long rounds = (wgs + num_cus - 1) / num_cus;
+        double score = (double)wgs / (double)(rounds * num_cus);  // fraction of the rounds that is busy
+        if (wgs < 2LL * num_cus) score *= 0.5;                    // too few workgroups to hide a workgroup's start-up
+        if (score > best_score + 1e-9) {
+            best_score = score;
+            best = s;
+        }
+    }
+    long long keys = (N + best - 1) / best;
     keys = ((keys + kKeyTileKeys - 1) / kKeyTileKeys) * kKeyTileKeys;  // whole 64-key stages
     *split_keys = (int)keys;
     *n_splits = (int)((N + keys - 1) / keys);
@@ -153,12 +172,54 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
         delete ctx;
         return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
     }
+    // kernel-side tile lists: per query tile, key tiles that lie inside the grid first, border tiles last
+    std::vector<int> k_col(ctx->sched.col_idx.size()), n_plain(ctx->sched.row_ptr.size() - 1, 0);
+    {
+        const Schedule& sc = ctx->sched;
+        auto cut = [&](int id) {
+            const int ty = id / sc.n_ktx, tx = id % sc.n_ktx;
+            return (ty + 1) * sc.kth > gridH || (tx + 1) * sc.ktw > gridW;
+        };
+        for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt) {
+            int w = sc.row_ptr[qt];
+            for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                if (!cut(sc.col_idx[e])) k_col[w++] = sc.col_idx[e];
+            n_plain[qt] = w - sc.row_ptr[qt];
+            for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                if (cut(sc.col_idx[e])) k_col[w++] = sc.col_idx[e];
+        }
+    }
+    std::vector<unsigned long long> mask_tbl;
+    if (dtype == CLEAR_BF16) {
+        // relative block offsets that a non-empty (patch, block) pair can have
+        ctx->mask_ry = std::min((r + 2) / 4, (gridH + 3) / 4);
+        ctx->mask_rx = std::min((r + 6) / 8, (gridW + 7) / 8);
+        const size_t entries = (size_t)(2 * ctx->mask_ry + 1) * (2 * ctx->mask_rx + 1) + 2;
+        if (entries * 128 <= (64u << 20)) {  // beyond 64 MB the kernels fall back to arithmetic masks
+            try {
+                build_bf16_mask_table(r, ctx->mask_ry, ctx->mask_rx, &mask_tbl);
+            } catch (const std::bad_alloc&) {
+                delete ctx;
+                return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the mask table");
+            }
+        }
+    }
     hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, ctx->device);
+        if (e == hipSuccess && prop.multiProcessorCount > 0) ctx->num_cus = prop.multiProcessorCount;
+    }
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_row_ptr, ctx->sched.row_ptr.size() * sizeof(int));
-    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_col_idx, (ctx->sched.col_idx.size() + 1) * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_col_idx, (k_col.size() + 1) * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_n_plain, (n_plain.size() + 1) * sizeof(int));
     if (e == hipSuccess) e = hipMemcpy(ctx->d_row_ptr, ctx->sched.row_ptr.data(), ctx->sched.row_ptr.size() * sizeof(int), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !ctx->sched.col_idx.empty())
-        e = hipMemcpy(ctx->d_col_idx, ctx->sched.col_idx.data(), ctx->sched.col_idx.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !k_col.empty()) e = hipMemcpy(ctx->d_col_idx, k_col.data(), k_col.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !n_plain.empty()) e = hipMemcpy(ctx->d_n_plain, n_plain.data(), n_plain.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !mask_tbl.empty()) {
+        e = hipMalloc((void**)&ctx->d_mask_tbl, mask_tbl.size() * sizeof(unsigned long long));
+        if (e == hipSuccess) e = hipMemcpy(ctx->d_mask_tbl, mask_tbl.data(), mask_tbl.size() * sizeof(unsigned long long), hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         std::string msg = std::string("HIP error in create: ") + hipGetErrorString(e);
@@ -234,13 +295,17 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.n_ktx = s.n_ktx;
     p.row_ptr = ctx->d_row_ptr;
     p.col_idx = ctx->d_col_idx;
+    p.n_plain = ctx->d_n_plain;
+    p.mask_tbl = ctx->d_mask_tbl;
+    p.mask_ry = ctx->mask_ry;
+    p.mask_rx = ctx->mask_rx;
     p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     if (n_text > 0) {
         int rc = clear_attn_reserve(ctx, BH);
         if (rc != CLEAR_OK) return rc;
         const int per_block = ctx->dtype == CLEAR_BF16 ? bf16_text_queries_per_block() : f32_text_queries_per_block();
         p.n_tq_tiles = (n_text + per_block - 1) / per_block;
-        choose_text_splits(N, BH, p.n_tq_tiles, &p.n_splits, &p.split_keys);
+        choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
         if (p.n_splits > ctx->ws_max_splits) return fail(ctx, CLEAR_ERR_HIP, "internal: split count exceeds workspace");
         p.ws_o = ctx->d_ws_o;
         p.ws_ml = ctx->d_ws_ml;
@@ -299,6 +364,8 @@ void clear_attn_destroy(clear_attn_ctx* ctx)
     if (!ctx) return;
     if (ctx->d_row_ptr) (void)hipFree(ctx->d_row_ptr);
     if (ctx->d_col_idx) (void)hipFree(ctx->d_col_idx);
+    if (ctx->d_n_plain) (void)hipFree(ctx->d_n_plain);
+    if (ctx->d_mask_tbl) (void)hipFree(ctx->d_mask_tbl);
     if (ctx->d_ws_o) (void)hipFree(ctx->d_ws_o);
     if (ctx->d_ws_ml) (void)hipFree(ctx->d_ws_ml);
     delete ctx;

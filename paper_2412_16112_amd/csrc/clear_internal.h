@@ -48,7 +48,10 @@ struct FwdParams {
     int n_qtx;         // query tiles per tile row
     int n_ktx;         // key tiles per tile row
     const int* row_ptr;  // device CSR
-    const int* col_idx;
+    const int* col_idx;  // per query tile: key tiles inside the grid first (ascending), then the ones cut by the border
+    const int* n_plain;  // per query tile: how many of its key tiles lie inside the grid
+    const unsigned long long* mask_tbl;  // bf16 kernels: lane masks per relative block offset (may be null)
+    int mask_ry, mask_rx;
     float scale_log2e;  // log2(e) / sqrt(head_dim)
     // text-query pass: dense rows split along the keys, partial results merged afterwards
     int n_tq_tiles;   // text query tiles per head
@@ -64,6 +67,7 @@ enum Phase : int { kPhaseAll = -1, kPhaseImage = 0, kPhaseTextQuery = 1, kPhaseT
 hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
+void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl);
 int f32_text_queries_per_block();
 
 }  // namespace clear

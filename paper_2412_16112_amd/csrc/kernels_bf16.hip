@@ -86,11 +86,12 @@ struct LaneOffsets {
     unsigned v[4][2];  // V transpose reads, per 32-channel slice and per half of the 16-key contraction step
 };
 
-enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2 };
+enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2, kMaskTable = 3 };
 
 struct MaskArgs {
     int a, b;  // linear: first token of the tile, token limit; image: tile origin (row, col)
     int hh, qy, qx, gridH, gridW, r2;
+    const unsigned long long* row[2];  // kMaskTable: 16 lane masks per key block (one per score register)
 };
 
 // Sets the scores of inadmissible (query, key) pairs of key block kb to -inf.  Register r of this lane
@@ -98,7 +99,16 @@ struct MaskArgs {
 template <int MASK>
 __device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma)
 {
-    if (MASK == kMaskLinear) {
+    if (MASK == kMaskTable) {
+        // precomputed per relative block offset: bit l of row[r] says whether lane l keeps score register r
+        const unsigned long long* row = ma.row[kb & 1];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const unsigned long long w = row[r];  // wave-uniform; say so, so that it is read into scalar registers
+            const unsigned lo32 = __builtin_amdgcn_readfirstlane((unsigned)w), hi32 = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
+            s[r] = __builtin_amdgcn_inverse_ballot_w64(((unsigned long long)hi32 << 32) | lo32) ? s[r] : -INFINITY;
+        }
+    } else if (MASK == kMaskLinear) {
         const int base = ma.a + 32 * kb + 4 * ma.hh;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -240,36 +250,30 @@ __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char* kblk, unsi
 
 // Fast pass, one staged tile.  The reference maximum of a query never moves once set, so O is only
 // ever touched by the matrix pipeline and there is no data-dependent branch.
-// NB = 2 processes both 32-key blocks as one hand-ordered pipeline of 32 matrix instructions:
+// The tile's two 32-key blocks run as one hand-ordered pipeline of 32 matrix instructions:
 //   slots  0- 7  S of block 0
-//   slots  8-15  S of block 1          | mask, maximum, reference, P[0..7] of block 0
+//   slots  8-15  S of block 1                      | mask, maximum, reference, P[0..7] of block 0
 //   slots 16-19  P V of block 0, keys of P[0..7]   | P[8..15] of block 0
 //   slots 20-23  P V of block 0, keys of P[8..15]  | mask, maximum, reference, P[0..7] of block 1
 //   slots 24-27  P V of block 1, keys of P[0..7]   | P[8..15] of block 1
 //   slots 28-31  P V of block 1, keys of P[8..15]
 // LDS operands are read two slots ahead of the matrix instruction that consumes them.
-// NB = 1 processes block kb0 only.  Returns the lanes that ran out of headroom.
-template <int NB, int MASK>
+// A wave runs the whole tile or none of it: a block its disc cannot reach is masked out entirely (its
+// scores become -inf, its P zero), which keeps one code shape for every tile of a loop.
+// Returns the lanes that ran out of headroom.
+template <int MASK>
 __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo,
-                                                         const unsigned char* tileK, int kb0, const MaskArgs& ma)
+                                                         const unsigned char* tileK, const MaskArgs& ma)
 {
-    const unsigned char* const kbase = tileK + kb0 * 32 * ROW_BYTES;
+    constexpr int kb0 = 0;
+    constexpr bool has1 = true;
+    const unsigned char* const kbase = tileK;
     const unsigned char* const vbase = kbase + TILE_BYTES;
     const float c = ws.c;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 pf0[2], pf1[2];
-    unsigned long long bad;
+    unsigned long long bad = 0;
     float sum = 0.f;
-
-    if (NB == 1) {
-        f32x16 s0 = qk_block(kbase, lo, qf);
-        apply_mask<MASK>(s0, kb0, ma);
-        bad = adopt_reference(ws, wave_pair_max(max_block(s0)));
-        sum = exp_block(s0, c, ws.m_run * c, pf0);
-        pv_block(ws.oacc, vbase, lo, pf0);
-        ws.l_run += sum;
-        return bad;
-    }
 
     // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
     auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
@@ -277,6 +281,7 @@ __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf
         const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
         return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
     };
+    auto block1_slot = [](int slot) { return (slot >= 8 && slot < 16) || slot >= 24; };
     bf16x8 op[3];
     op[0] = k_operand(0);
     op[1] = k_operand(1);
@@ -285,18 +290,20 @@ __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf
 #pragma unroll
     for (int slot = 0; slot < 32; ++slot) {
         // prefetch the operand of slot + 2
-        if (slot + 2 < 16)
-            op[(slot + 2) % 3] = k_operand(slot + 2);
-        else if (slot + 2 < 32)
-            op[(slot + 2) % 3] = v_operand(slot + 2);
+        if (slot + 2 < 32 && (!block1_slot(slot + 2) || has1)) {
+            if (slot + 2 < 16)
+                op[(slot + 2) % 3] = k_operand(slot + 2);
+            else
+                op[(slot + 2) % 3] = v_operand(slot + 2);
+        }
         // matrix instruction of this slot
         if (slot < 8)
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot], s0, 0, 0, 0);
-        else if (slot < 16)
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot - 8], s1, 0, 0, 0);
-        else if (slot < 24)
+        else if (slot < 16) {
+            if (has1) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot - 8], s1, 0, 0, 0);
+        } else if (slot < 24)
             ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], pf0[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
-        else
+        else if (has1)
             ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], pf1[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
         // vector work riding along
         if (slot == 8) {
@@ -315,18 +322,20 @@ __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf
         if (slot == 17) exp_slice<10, 12>(s0, c, mc, sum, pf0);
         if (slot == 18) exp_slice<12, 14>(s0, c, mc, sum, pf0);
         if (slot == 19) exp_slice<14, 16>(s0, c, mc, sum, pf0);
-        if (slot == 20) {
-            apply_mask<MASK>(s1, kb0 + 1, ma);
-            bad |= adopt_reference(ws, wave_pair_max(max_block(s1)));
-            mc = ws.m_run * c;
+        if (has1) {
+            if (slot == 20) {
+                apply_mask<MASK>(s1, kb0 + 1, ma);
+                bad |= adopt_reference(ws, wave_pair_max(max_block(s1)));
+                mc = ws.m_run * c;
+            }
+            if (slot == 21) exp_slice<0, 2>(s1, c, mc, sum, pf1);
+            if (slot == 22) exp_slice<2, 5>(s1, c, mc, sum, pf1);
+            if (slot == 23) exp_slice<5, 8>(s1, c, mc, sum, pf1);
+            if (slot == 24) exp_slice<8, 10>(s1, c, mc, sum, pf1);
+            if (slot == 25) exp_slice<10, 12>(s1, c, mc, sum, pf1);
+            if (slot == 26) exp_slice<12, 14>(s1, c, mc, sum, pf1);
+            if (slot == 27) exp_slice<14, 16>(s1, c, mc, sum, pf1);
         }
-        if (slot == 21) exp_slice<0, 2>(s1, c, mc, sum, pf1);
-        if (slot == 22) exp_slice<2, 5>(s1, c, mc, sum, pf1);
-        if (slot == 23) exp_slice<5, 8>(s1, c, mc, sum, pf1);
-        if (slot == 24) exp_slice<8, 10>(s1, c, mc, sum, pf1);
-        if (slot == 25) exp_slice<10, 12>(s1, c, mc, sum, pf1);
-        if (slot == 26) exp_slice<12, 14>(s1, c, mc, sum, pf1);
-        if (slot == 27) exp_slice<14, 16>(s1, c, mc, sum, pf1);
         SCHED_FENCE();
     }
     ws.l_run += sum;
@@ -523,6 +532,19 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
         si.ma.qy = qy; si.ma.qx = qx; si.ma.gridH = p.gridH; si.ma.gridW = p.gridW; si.ma.r2 = p.r2;
+        si.ma.row[0] = si.ma.row[1] = p.mask_tbl;
+        if (!TEXTQ && !si.linear && p.mask_tbl) {
+            // lane masks of the two blocks: whole blocks use the all-ones entry, unreachable blocks the all-zeros
+            // entry at the end of the table
+            const int ncol = 2 * p.mask_rx + 1;
+            const int ones = (2 * p.mask_ry + 1) * ncol, zeros = ones + 1;
+            const int dbx = (tb - wx0) >> 3;
+            const int dby = (ta - wy0) >> 2;
+            const int i0 = (si.cls0 == kBlockPartial) ? (dby + p.mask_ry) * ncol + dbx + p.mask_rx : (si.cls0 == kBlockFull ? ones : zeros);
+            const int i1 = (si.cls1 == kBlockPartial) ? (dby + 1 + p.mask_ry) * ncol + dbx + p.mask_rx : (si.cls1 == kBlockFull ? ones : zeros);
+            si.ma.row[0] = p.mask_tbl + 16 * i0;
+            si.ma.row[1] = p.mask_tbl + 16 * i1;
+        }
         return si;
     };
 
@@ -553,22 +575,22 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
             int st = 0;
             for (; st < n_lin_whole; ++st) {
                 const StageInfo si = begin_stage(st);
-                if (wave_has_queries) bad |= fast_stage<2, kMaskNone>(ws, qf, lo, si.tileK, 0, si.ma);
+                if (wave_has_queries) bad |= fast_stage<kMaskNone>(ws, qf, lo, si.tileK, si.ma);
             }
             for (; st < n_lin_stages; ++st) {
                 const StageInfo si = begin_stage(st);
-                if (si.cls0 != kBlockSkip && si.cls1 != kBlockSkip)
-                    bad |= fast_stage<2, kMaskLinear>(ws, qf, lo, si.tileK, 0, si.ma);
-                else if (si.cls0 != kBlockSkip)
-                    bad |= fast_stage<1, kMaskLinear>(ws, qf, lo, si.tileK, 0, si.ma);
+                if (si.cls0 != kBlockSkip) bad |= fast_stage<kMaskLinear>(ws, qf, lo, si.tileK, si.ma);
             }
             if (!TEXTQ) {
+                // image tiles that lie inside the grid (masks from the table), then the ones cut by the border
+                const int n_plain_end = p.mask_tbl ? n_lin_stages + p.n_plain[qt] : n_lin_stages;
+                for (; st < n_plain_end; ++st) {
+                    const StageInfo si = begin_stage(st);
+                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) bad |= fast_stage<kMaskTable>(ws, qf, lo, si.tileK, si.ma);
+                }
                 for (; st < n_stages; ++st) {
                     const StageInfo si = begin_stage(st);
-                    if (si.cls0 != kBlockSkip && si.cls1 != kBlockSkip)
-                        bad |= fast_stage<2, kMaskImage>(ws, qf, lo, si.tileK, 0, si.ma);
-                    else if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip)
-                        bad |= fast_stage<1, kMaskImage>(ws, qf, lo, si.tileK, si.cls0 != kBlockSkip ? 0 : 1, si.ma);
+                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) bad |= fast_stage<kMaskImage>(ws, qf, lo, si.tileK, si.ma);
                 }
             }
         }
@@ -667,6 +689,30 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 }  // namespace
 
 int bf16_text_queries_per_block() { return kBf16NWY * kBf16NWX * kTextQueriesPerWave; }
+
+// Lane masks of the bf16 kernels for a (4 x 8 query patch, 4 x 8 key block) pair whose origins differ by
+// (4 dby, 8 dbx), |dby| <= ry, |dbx| <= rx: entry (dby + ry) * (2 rx + 1) + dbx + rx holds 16 words, one per
+// score register r; bit l is set iff lane l (query l % 32 of the patch, key slot 8 (r/4) + 4 (l/32) + r % 4
+// of the block) is admitted by Eq. 3, dx^2 + dy^2 < r^2.  Two more entries follow: all ones, all zeros.
+void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl)
+{
+    const long long r2 = (long long)r * r;
+    const int ncol = 2 * rx + 1;
+    tbl->assign((size_t)((2 * ry + 1) * ncol + 2) * 16, 0ull);
+    for (int dby = -ry; dby <= ry; ++dby)
+        for (int dbx = -rx; dbx <= rx; ++dbx) {
+            unsigned long long* e = tbl->data() + (size_t)((dby + ry) * ncol + dbx + rx) * 16;
+            for (int reg = 0; reg < 16; ++reg)
+                for (int l = 0; l < 64; ++l) {
+                    const int qi = l & 31, hh = l >> 5;
+                    const long long dy = 4 * dby + (reg >> 2) - (qi >> 3);
+                    const long long dx = 8 * dbx + 4 * hh + (reg & 3) - (qi & 7);
+                    if (dx * dx + dy * dy < r2) e[reg] |= 1ull << l;
+                }
+        }
+    unsigned long long* ones = tbl->data() + tbl->size() - 32;
+    for (int reg = 0; reg < 16; ++reg) ones[reg] = ~0ull;
+}
 
 hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase)
 {

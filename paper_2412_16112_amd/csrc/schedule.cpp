@@ -82,20 +82,22 @@ unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_s
                 for (int wx = 0; wx < nwx; ++wx) {
                     const int y0 = ty * s.qth + wy * kWaveQH, x0 = tx * s.qtw + wx * kWaveQW;
                     if (y0 >= s.gridH || x0 >= s.gridW) continue;  // wave has no query: it computes nothing
+                    // a wave runs both 32-key blocks of a staged tile, or skips the tile when neither is reachable
                     for (int t = 0; t < n_text_tiles; ++t)
-                        for (int kb = 0; kb < 2; ++kb)
-                            blocks += classify_linear_block((long long)t * kKeyTileKeys + 32 * kb, 32, n_text) != kBlockSkip;
+                        blocks += 2 * (classify_linear_block((long long)t * kKeyTileKeys, 32, n_text) != kBlockSkip);
                     for (int e = s.row_ptr[qt]; e < s.row_ptr[qt + 1]; ++e) {
                         const int ky0 = (s.col_idx[e] / s.n_ktx) * s.kth, kx0 = (s.col_idx[e] % s.n_ktx) * s.ktw;
+                        bool any = false;
                         for (int kb = 0; kb < 2; ++kb)
-                            blocks += classify_image_block(y0, x0, kWaveQH, kWaveQW, ky0 + kKeyBlockH * kb, kx0, kKeyBlockH,
-                                                           kKeyBlockW, s.gridH, s.gridW, s.r * s.r) != kBlockSkip;
+                            any |= classify_image_block(y0, x0, kWaveQH, kWaveQW, ky0 + kKeyBlockH * kb, kx0, kKeyBlockH,
+                                                        kKeyBlockW, s.gridH, s.gridW, s.r * s.r) != kBlockSkip;
+                        blocks += 2 * any;
                     }
                 }
         }
     // text-query pass: every wave that holds at least one text query visits every 32-key block of [0, N)
     const unsigned long long text_waves = (unsigned long long)ceil_div(n_text, kTextQueriesPerWave);
-    blocks += text_waves * (unsigned long long)((N + 31) / 32);
+    blocks += text_waves * 2ull * (unsigned long long)((N + kKeyTileKeys - 1) / kKeyTileKeys);
     return blocks * 1024ull;
 }
 
