@@ -35,8 +35,14 @@ constexpr int D = 128;               // head_dim
 constexpr int ROW_BYTES = D * 2;     // one token row of K or V
 constexpr int TILE_KEYS = kKeyTileKeys;
 constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
-constexpr int NSTAGE = 4;                          // ring of staged key tiles (K + V = 32 KB each)
-constexpr float FAST_HEADROOM_LOG2 = 60.0f;  // the fast pass lets 2^{(s - m_ref) c} grow up to 2^60 before it gives up
+#ifndef CLEAR_OPERAND_PREFETCH
+#define CLEAR_OPERAND_PREFETCH 2
+#endif
+#ifndef CLEAR_NSTAGE
+#define CLEAR_NSTAGE 4
+#endif
+constexpr int NSTAGE = CLEAR_NSTAGE;               // ring of staged key tiles (K + V = 32 KB each)
+constexpr float FAST_SUM_LIMIT = 1.0e30f;  // the fast pass is discarded when a query's sums leave [0, 1e30)
 constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)
 
 // LDS layout of a staged tile: 64 rows of 256 B, unpadded (the LDS-direct load writes 1 KB = 4 rows per
@@ -220,12 +226,12 @@ __device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[
 }
 
 // Reference maximum of the fast pass: a query adopts the maximum of the first block in which it sees an
-// admissible key (nothing has been accumulated for it before, so nothing needs rescaling) and keeps it.
-// Returns the lanes whose scores outgrow the headroom; the fast pass result is discarded if any does.
-__device__ __forceinline__ unsigned long long adopt_reference(WaveState& ws, float mx_pair)
+// admissible key (nothing has been accumulated for it before, so nothing needs rescaling) and keeps it:
+// all later exponentials are taken relative to it, 2^{(s - m_ref) c}, whatever their size.  Whether that
+// stayed within the range of fp32 is checked once, on the finished sums.
+__device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
 {
     ws.m_run = (ws.m_run == M_INIT) ? fmaxf(mx_pair, M_INIT) : ws.m_run;
-    return __builtin_amdgcn_ballot_w64((mx_pair - ws.m_run) * ws.c > FAST_HEADROOM_LOG2);
 }
 
 // Pins the instruction order: nothing is scheduled across this point.
@@ -260,10 +266,11 @@ __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char* kblk, unsi
 // LDS operands are read two slots ahead of the matrix instruction that consumes them.
 // A wave runs the whole tile or none of it: a block its disc cannot reach is masked out entirely (its
 // scores become -inf, its P zero), which keeps one code shape for every tile of a loop.
-// Returns the lanes that ran out of headroom.
-template <int MASK>
-__device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo,
-                                                         const unsigned char* tileK, const MaskArgs& ma)
+// ADOPT = true while some query of the wave still has no reference maximum (the first tiles): the block
+// maxima are formed and adopted.  ADOPT = false afterwards: no maximum is needed at all.
+template <int MASK, bool ADOPT>
+__device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo,
+                                           const unsigned char* tileK, const MaskArgs& ma)
 {
     constexpr int kb0 = 0;
     constexpr bool has1 = true;
@@ -272,44 +279,59 @@ __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf
     const float c = ws.c;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 pf0[2], pf1[2];
-    unsigned long long bad = 0;
     float sum = 0.f;
 
     // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
+#ifdef CLEAR_EXP_NO_LDSREAD
+    auto k_operand = [&](int slot) { return qf[slot & 7]; };
+    auto v_operand = [&](int slot) { return qf[slot & 7]; };
+#else
     auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
     auto v_operand = [&](int slot) {
         const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
         return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
     };
+#endif
     auto block1_slot = [](int slot) { return (slot >= 8 && slot < 16) || slot >= 24; };
-    bf16x8 op[3];
-    op[0] = k_operand(0);
-    op[1] = k_operand(1);
+    // operands are read PD slots ahead into a ring of PD + 2 (the extra entry keeps a read from landing on
+    // the registers the previous matrix instruction is still reading)
+    constexpr int PD = CLEAR_OPERAND_PREFETCH, RING = PD + 2;
+    bf16x8 op[RING];
+#pragma unroll
+    for (int i = 0; i < PD; ++i) op[i] = k_operand(i);
     f32x16 s0 = zero, s1 = zero;
-    float mc = 0.f;
+    float mc = ws.m_run * c;
 #pragma unroll
     for (int slot = 0; slot < 32; ++slot) {
-        // prefetch the operand of slot + 2
-        if (slot + 2 < 32 && (!block1_slot(slot + 2) || has1)) {
-            if (slot + 2 < 16)
-                op[(slot + 2) % 3] = k_operand(slot + 2);
+        // prefetch the operand of slot + PD
+        if (slot + PD < 32 && (!block1_slot(slot + PD) || has1)) {
+            if (slot + PD < 16)
+                op[(slot + PD) % RING] = k_operand(slot + PD);
             else
-                op[(slot + 2) % 3] = v_operand(slot + 2);
+                op[(slot + PD) % RING] = v_operand(slot + PD);
         }
         // matrix instruction of this slot
         if (slot < 8)
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot], s0, 0, 0, 0);
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], qf[slot], s0, 0, 0, 0);
         else if (slot < 16) {
-            if (has1) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], qf[slot - 8], s1, 0, 0, 0);
+            if (has1) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], qf[slot - 8], s1, 0, 0, 0);
         } else if (slot < 24)
-            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], pf0[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf0[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
         else if (has1)
-            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % 3], pf1[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf1[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+#ifdef CLEAR_EXP_NO_VALU
+        if (slot == 8) { for (int i = 0; i < 8; ++i) { pf0[0][i] = pf0[1][i] = (__bf16)s0[i]; } }
+        if (slot == 20) { for (int i = 0; i < 8; ++i) { pf1[0][i] = pf1[1][i] = (__bf16)s1[i]; } }
+        SCHED_FENCE();
+        continue;
+#endif
         // vector work riding along
         if (slot == 8) {
             apply_mask<MASK>(s0, kb0, ma);
-            bad = adopt_reference(ws, wave_pair_max(max_block(s0)));
-            mc = ws.m_run * c;
+            if (ADOPT) {
+                adopt_reference(ws, wave_pair_max(max_block(s0)));
+                mc = ws.m_run * c;
+            }
         }
         if (slot == 9) exp_slice<0, 1>(s0, c, mc, sum, pf0);
         if (slot == 10) exp_slice<1, 2>(s0, c, mc, sum, pf0);
@@ -325,8 +347,10 @@ __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf
         if (has1) {
             if (slot == 20) {
                 apply_mask<MASK>(s1, kb0 + 1, ma);
-                bad |= adopt_reference(ws, wave_pair_max(max_block(s1)));
-                mc = ws.m_run * c;
+                if (ADOPT) {
+                    adopt_reference(ws, wave_pair_max(max_block(s1)));
+                    mc = ws.m_run * c;
+                }
             }
             if (slot == 21) exp_slice<0, 2>(s1, c, mc, sum, pf1);
             if (slot == 22) exp_slice<2, 5>(s1, c, mc, sum, pf1);
@@ -339,7 +363,6 @@ __device__ __forceinline__ unsigned long long fast_stage(WaveState& ws, const bf
         SCHED_FENCE();
     }
     ws.l_run += sum;
-    return bad;
 }
 
 template <int NWY, int NWX, bool TEXTQ>
@@ -503,13 +526,21 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
     auto begin_stage = [&](int st) -> StageInfo {
         // tile st has landed once at most NSTAGE - 2 younger tiles are outstanding (all of them exist
         // only away from the tail)
+#ifdef CLEAR_EXP_NO_ISSUE
+        wait_vmcnt<0>();
+#else
         if (st + NSTAGE - 2 < n_stages)
             wait_vmcnt<(NSTAGE - 2) * LPT>();
         else
             wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();  // every wave's part of tile st is in LDS; every wave is done with tile st - 1
+#endif
+#ifndef CLEAR_EXP_NO_BARRIER
+        __builtin_amdgcn_s_barrier();
+#endif  // every wave's part of tile st is in LDS; every wave is done with tile st - 1
         asm volatile("" ::: "memory");
+#ifndef CLEAR_EXP_NO_ISSUE
         if (st + NSTAGE - 1 < n_stages) issue_stage(st + NSTAGE - 1);  // overwrites the buffer of tile st - 1
+#endif
 
         StageInfo si;
         int ta, tb;
@@ -569,30 +600,61 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
                 careful_stage(ws, qf, lo, si.tileK, si.cls0, si.cls1, si.linear, si.ma);
             }
         } else {
-            // Three consecutive ranges of the stage list, one loop each, so that every loop body has a
-            // single shape: whole 64-key linear tiles, the ragged linear tile (at most one), image tiles.
+            // Consecutive ranges of the stage list, one loop each, so that every loop body has a single
+            // shape: whole 64-key linear tiles, the ragged linear tile (at most one), image tiles inside the
+            // grid, image tiles cut by the border.  Each range starts in "adopt" mode and switches to the
+            // leaner loop once every query of the wave has its reference maximum.
             const int n_lin_whole = (lin_limit - lin_begin) / TILE_KEYS;
+            const int n_plain_end = TEXTQ ? n_lin_stages : (p.mask_tbl ? n_lin_stages + p.n_plain[qt] : n_lin_stages);
             int st = 0;
+            bool adopting = true;
+            auto still_adopting = [&]() { return __builtin_amdgcn_ballot_w64(ws.m_run == M_INIT) != 0; };
+
+            for (; st < n_lin_whole && adopting; ++st) {
+                const StageInfo si = begin_stage(st);
+                if (wave_has_queries) {
+                    fast_stage<kMaskNone, true>(ws, qf, lo, si.tileK, si.ma);
+                    adopting = still_adopting();
+                }
+            }
             for (; st < n_lin_whole; ++st) {
                 const StageInfo si = begin_stage(st);
-                if (wave_has_queries) bad |= fast_stage<kMaskNone>(ws, qf, lo, si.tileK, si.ma);
+                if (wave_has_queries) fast_stage<kMaskNone, false>(ws, qf, lo, si.tileK, si.ma);
             }
-            for (; st < n_lin_stages; ++st) {
+            for (; st < n_lin_stages; ++st) {  // ragged tile: at most one, keep it simple
                 const StageInfo si = begin_stage(st);
-                if (si.cls0 != kBlockSkip) bad |= fast_stage<kMaskLinear>(ws, qf, lo, si.tileK, si.ma);
+                if (si.cls0 != kBlockSkip) {
+                    fast_stage<kMaskLinear, true>(ws, qf, lo, si.tileK, si.ma);
+                    adopting = still_adopting();
+                }
             }
             if (!TEXTQ) {
-                // image tiles that lie inside the grid (masks from the table), then the ones cut by the border
-                const int n_plain_end = p.mask_tbl ? n_lin_stages + p.n_plain[qt] : n_lin_stages;
+                for (; st < n_plain_end && adopting; ++st) {
+                    const StageInfo si = begin_stage(st);
+                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) {
+                        fast_stage<kMaskTable, true>(ws, qf, lo, si.tileK, si.ma);
+                        adopting = still_adopting();
+                    }
+                }
                 for (; st < n_plain_end; ++st) {
                     const StageInfo si = begin_stage(st);
-                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) bad |= fast_stage<kMaskTable>(ws, qf, lo, si.tileK, si.ma);
+                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
                 }
-                for (; st < n_stages; ++st) {
+                for (; st < n_stages; ++st) {  // border tiles: few, keep them simple
                     const StageInfo si = begin_stage(st);
-                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) bad |= fast_stage<kMaskImage>(ws, qf, lo, si.tileK, si.ma);
+                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) {
+                        fast_stage<kMaskImage, true>(ws, qf, lo, si.tileK, si.ma);
+                        adopting = still_adopting();
+                    }
                 }
             }
+            // the fast pass stands only if every sum stayed finite and moderate
+            float chk = ws.l_run;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) chk += __builtin_fabsf(ws.oacc[db][r]);
+            bad = __builtin_amdgcn_ballot_w64(!(chk < FAST_SUM_LIMIT));
         }
         return bad;
     };

@@ -75,6 +75,27 @@ def test_bf16_sharp_logits():
     _run_full_compare(1, 2, 96, 32, 32, 128, 8, "bf16", seed=7, q_scale=4.0)
 
 
+@pytest.mark.parametrize("q_scale", [60.0, 400.0])
+def test_bf16_extreme_logits(q_scale):
+    """Logits spread over hundreds of powers of two: exponentials relative to the first tile's maximum leave
+    the fp32 range for some rows, so the kernel has to fall back to its exact-maximum pass."""
+    _run_full_compare(1, 2, 64, 24, 40, 128, 6, "bf16", seed=9, q_scale=q_scale)
+
+
+def test_bf16_first_tile_far_above_the_rest():
+    """Text keys with huge logits, image keys with ordinary ones: everything after the first tile underflows."""
+    B, H, n_text, gh, gw, d, r = 1, 1, 64, 16, 24, 128, 5
+    Q, K, V = make_qkv_shape(B, H, n_text, gh, gw, d, "bf16", seed=21, device="cpu")
+    K = K.float()
+    K[:, :, :n_text] *= 50.0
+    K = K.to(torch.bfloat16)
+    _announce("first tile dominates")
+    O = ca.clear_attn_forward_once(Q.to(DEV), K.to(DEV), V.to(DEV), n_text, gh, gw, r).float().cpu().numpy()
+    ref = orc.attention(Q, K, V, n_text, gh, gw, r)
+    max_abs, rel_rms = error_metrics(O, ref)
+    assert np.isfinite(O).all() and max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
+
+
 def test_schedule_from_context_equals_host_schedule_and_oracle():
     ctx = ca.ClearAttn(40, 20, 28, 128, 4, ca.CLEAR_BF16)
     try:
