@@ -13,7 +13,10 @@ constexpr int kWaveQH = 4, kWaveQW = 8;
 constexpr int kKeyBlockH = 4, kKeyBlockW = 8;
 constexpr int kKeyTileH = 8, kKeyTileW = 8;
 constexpr int kKeyTileKeys = kKeyTileH * kKeyTileW;  // 64 keys per staged tile
-constexpr int kBf16NWY = 4, kBf16NWX = 2;            // workgroup = 16 x 16 queries, 8 waves
+#ifndef CLEAR_NWY
+#define CLEAR_NWY 4
+#endif
+constexpr int kBf16NWY = CLEAR_NWY, kBf16NWX = 2;    // workgroup = (4 NWY) x 16 queries, 2 NWY waves
 constexpr int kBf16QTileH = kBf16NWY * kWaveQH, kBf16QTileW = kBf16NWX * kWaveQW;
 constexpr int kTextQueriesPerWave = 32;
 

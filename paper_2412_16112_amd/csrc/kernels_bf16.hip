@@ -38,10 +38,12 @@ constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
 #ifndef CLEAR_OPERAND_PREFETCH
 #define CLEAR_OPERAND_PREFETCH 2
 #endif
-#ifndef CLEAR_NSTAGE
-#define CLEAR_NSTAGE 4
+#ifndef CLEAR_TILES_PER_STAGE
+#define CLEAR_TILES_PER_STAGE 2
 #endif
-constexpr int NSTAGE = CLEAR_NSTAGE;               // ring of staged key tiles (K + V = 32 KB each)
+constexpr int TPS = CLEAR_TILES_PER_STAGE;           // key tiles (K + V = 32 KB each) staged per barrier
+constexpr int NBUF = 2;                             // stage buffers: one being computed on, one being filled
+constexpr int STAGE_BYTES = TPS * 2 * TILE_BYTES;
 constexpr float FAST_SUM_LIMIT = 1.0e30f;  // the fast pass is discarded when a query's sums leave [0, 1e30)
 constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)
 
@@ -282,9 +284,18 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
     float sum = 0.f;
 
     // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
-#ifdef CLEAR_EXP_NO_LDSREAD
+#if defined(CLEAR_EXP_NO_LDSREAD)
     auto k_operand = [&](int slot) { return qf[slot & 7]; };
     auto v_operand = [&](int slot) { return qf[slot & 7]; };
+#elif defined(CLEAR_EXP_NO_VREAD)
+    auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
+    auto v_operand = [&](int slot) { return qf[slot & 7]; };
+#elif defined(CLEAR_EXP_NO_KREAD)
+    auto k_operand = [&](int slot) { return qf[slot & 7]; };
+    auto v_operand = [&](int slot) {
+        const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
+        return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
+    };
 #else
     auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
     auto v_operand = [&](int slot) {
@@ -366,14 +377,13 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
 }
 
 template <int NWY, int NWX, bool TEXTQ>
-__global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const FwdParams p)
+__global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
 {
     constexpr int NW = NWY * NWX;
     constexpr int NI = 16 / NW;       // 1 KB load instructions per wave per tile, for K and for V each
-    constexpr int LPT = 2 * NI;       // loads per thread per stage
     static_assert(NI * NW == 16, "64 rows = 16 instructions of 4 rows");
 
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NSTAGE][K tile | V tile]
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][K tile | V tile]
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     const int tid = threadIdx.x;
@@ -439,28 +449,39 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
     }
 
-    // ---- stage list: tokens [lin_begin, lin_limit) in 64-key tiles, then (image mode) the CSR row
-    int n_stages, n_lin_stages, csr_begin = 0;
+    // ---- tile list: tokens [lin_begin, lin_limit) in 64-key tiles, then (image mode) the CSR row.
+    // Tiles fall into four consecutive categories, each with its own code shape:
+    //   [cb0, cb1) whole linear tiles   [cb1, cb2) the ragged linear tile (at most one)
+    //   [cb2, cb3) image tiles inside the grid (masks from the table)   [cb3, cb4) image tiles cut by the border
+    // A stage is up to TPS consecutive tiles of one category.
+    int n_tiles, n_lin_tiles, csr_begin = 0;
     int lin_begin = 0, lin_limit = 0;
     if (TEXTQ) {
         lin_begin = split * p.split_keys;
         lin_limit = (long long)lin_begin + p.split_keys < p.N ? lin_begin + p.split_keys : (int)p.N;
-        n_lin_stages = (lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS;
-        n_stages = n_lin_stages;
+        n_lin_tiles = (lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS;
+        n_tiles = n_lin_tiles;
     } else {
         lin_limit = p.n_text;
-        n_lin_stages = (p.n_text + TILE_KEYS - 1) / TILE_KEYS;
+        n_lin_tiles = (p.n_text + TILE_KEYS - 1) / TILE_KEYS;
         csr_begin = p.row_ptr[qt];
-        n_stages = n_lin_stages + (p.row_ptr[qt + 1] - csr_begin);
+        n_tiles = n_lin_tiles + (p.row_ptr[qt + 1] - csr_begin);
     }
+    const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
+    const int cb3 = TEXTQ ? n_lin_tiles : (p.mask_tbl ? n_lin_tiles + p.n_plain[qt] : n_lin_tiles);
+    const int cb4 = n_tiles;
+    auto stage_len = [&](int t) {  // tiles in the stage that starts at tile t
+        const int e = t < cb1 ? cb1 : (t < cb2 ? cb2 : (t < cb3 ? cb3 : cb4));
+        return imin(TPS, e - t);
+    };
 
-    // Tile origin of stage i: linear -> (first token, -1); image -> (row, col) of the 8 x 8 tile.
-    auto stage_origin = [&](int i, int& a, int& b) {
-        if (i < n_lin_stages) {
+    // Tile origin: linear -> (first token, -1); image -> (row, col) of the 8 x 8 tile.
+    auto tile_origin = [&](int i, int& a, int& b) {
+        if (i < n_lin_tiles) {
             a = lin_begin + i * TILE_KEYS;
             b = -1;
         } else {
-            const int id = p.col_idx[csr_begin + i - n_lin_stages];
+            const int id = p.col_idx[csr_begin + i - n_lin_tiles];
             a = (id / p.n_ktx) * kKeyTileH;
             b = (id % p.n_ktx) * kKeyTileW;
         }
@@ -469,10 +490,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
     // ---- LDS-direct staging.  Load instruction ii (0..15) of a tile covers rows 4 ii .. 4 ii + 3; lane i
     // writes slot i % 16 of row 4 ii + i / 16 and therefore fetches logical chunk (i % 16) ^ swz(row).
     // Addresses are clamped to valid tokens; slots beyond the range or the grid are masked in the compute.
-    auto issue_stage = [&](int i) {
+    auto issue_tile = [&](int i, unsigned lds_tile) {
         int a, b;
-        stage_origin(i, a, b);
-        const unsigned buf = lds_base + (unsigned)(i % NSTAGE) * (2 * TILE_BYTES);
+        tile_origin(i, a, b);
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
             const int ii = wave * NI + n;
@@ -486,9 +506,15 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
                 token = p.n_text + ky * p.gridW + kx;
             }
             const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
-            load_to_lds_16B(Kh, voff, buf + ii * 1024);
-            load_to_lds_16B(Vh, voff, buf + TILE_BYTES + ii * 1024);
+            load_to_lds_16B(Kh, voff, lds_tile + ii * 1024);
+            load_to_lds_16B(Vh, voff, lds_tile + TILE_BYTES + ii * 1024);
         }
+    };
+    auto issue_stage = [&](int t, int buf) {  // the stage that starts at tile t goes to stage buffer buf
+        const int len = stage_len(t);
+#pragma unroll
+        for (int j = 0; j < TPS; ++j)
+            if (j < len) issue_tile(t + j, lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
     };
 
     // ---- running softmax state: one query per lane (shared with lane ^ 32)
@@ -515,36 +541,35 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
             }
     }
 
-    // Per-stage bookkeeping shared by both paths: wait for tile st, publish it, refill the ring, and
-    // classify the tile's two key blocks against this wave's query patch.
-    struct StageInfo {
+    // Stage hand-over: this wave's loads of the stage about to be computed have landed; after the barrier
+    // so have everyone's, and every wave has left the other buffer, which is refilled with the next stage.
+    int pf_tile = 0;  // first tile of the next stage to load
+    auto begin_stage = [&](int buf) {
+        wait_vmcnt<0>();
+#ifndef CLEAR_EXP_NO_BARRIER
+        __builtin_amdgcn_s_barrier();
+#endif
+        asm volatile("" ::: "memory");
+#ifndef CLEAR_EXP_NO_ISSUE
+        if (pf_tile < n_tiles) {
+            issue_stage(pf_tile, buf ^ 1);
+            pf_tile += stage_len(pf_tile);
+        }
+#endif
+    };
+
+    // Classifies the two key blocks of tile t against this wave's query patch and gathers what the
+    // element masks need.
+    struct TileInfo {
         int cls0, cls1;
         bool linear;
         const unsigned char* tileK;
         MaskArgs ma;
     };
-    auto begin_stage = [&](int st) -> StageInfo {
-        // tile st has landed once at most NSTAGE - 2 younger tiles are outstanding (all of them exist
-        // only away from the tail)
-#ifdef CLEAR_EXP_NO_ISSUE
-        wait_vmcnt<0>();
-#else
-        if (st + NSTAGE - 2 < n_stages)
-            wait_vmcnt<(NSTAGE - 2) * LPT>();
-        else
-            wait_vmcnt<0>();
-#endif
-#ifndef CLEAR_EXP_NO_BARRIER
-        __builtin_amdgcn_s_barrier();
-#endif  // every wave's part of tile st is in LDS; every wave is done with tile st - 1
-        asm volatile("" ::: "memory");
-#ifndef CLEAR_EXP_NO_ISSUE
-        if (st + NSTAGE - 1 < n_stages) issue_stage(st + NSTAGE - 1);  // overwrites the buffer of tile st - 1
-#endif
-
-        StageInfo si;
+    auto tile_info = [&](int t, int buf, int j) -> TileInfo {
+        TileInfo si;
         int ta, tb;
-        stage_origin(st, ta, tb);
+        tile_origin(t, ta, tb);
         si.linear = tb < 0;
         if (!wave_has_queries) {
             si.cls0 = si.cls1 = kBlockSkip;
@@ -558,7 +583,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
             si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH,
                                            p.gridW, p.r2);
         }
-        si.tileK = smem + (st % NSTAGE) * (2 * TILE_BYTES);
+        si.tileK = smem + buf * STAGE_BYTES + j * (2 * TILE_BYTES);
         si.ma.hh = hh;
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
@@ -590,61 +615,88 @@ __global__ void __launch_bounds__(NWY* NWX * 64, 1) clear_fwd_bf16_kernel(const 
         ws.m_run = M_INIT;
         ws.l_run = 0.f;
         unsigned long long bad = 0;
-        // prologue: NSTAGE - 1 tiles in flight
-#pragma unroll
-        for (int i = 0; i < NSTAGE - 1; ++i)
-            if (i < n_stages) issue_stage(i);
+        // prologue: the first stage is in flight
+        pf_tile = 0;
+        if (n_tiles > 0) {
+            issue_stage(0, 0);
+            pf_tile = stage_len(0);
+        }
+        int buf = 0;
         if (CAREFUL) {
-            for (int st = 0; st < n_stages; ++st) {
-                const StageInfo si = begin_stage(st);
-                careful_stage(ws, qf, lo, si.tileK, si.cls0, si.cls1, si.linear, si.ma);
+            for (int t = 0; t < n_tiles;) {
+                begin_stage(buf);
+                const int len = stage_len(t);
+                for (int j = 0; j < len; ++j) {
+                    const TileInfo si = tile_info(t + j, buf, j);
+                    careful_stage(ws, qf, lo, si.tileK, si.cls0, si.cls1, si.linear, si.ma);
+                }
+                t += len;
+                buf ^= 1;
             }
         } else {
-            // Consecutive ranges of the stage list, one loop each, so that every loop body has a single
-            // shape: whole 64-key linear tiles, the ragged linear tile (at most one), image tiles inside the
-            // grid, image tiles cut by the border.  Each range starts in "adopt" mode and switches to the
-            // leaner loop once every query of the wave has its reference maximum.
-            const int n_lin_whole = (lin_limit - lin_begin) / TILE_KEYS;
-            const int n_plain_end = TEXTQ ? n_lin_stages : (p.mask_tbl ? n_lin_stages + p.n_plain[qt] : n_lin_stages);
-            int st = 0;
+            // One loop per tile category (and per mode), so that every loop body has a single shape.  Each
+            // category starts in "adopt" mode and switches to the leaner loop once every query of the wave
+            // has its reference maximum.
             bool adopting = true;
             auto still_adopting = [&]() { return __builtin_amdgcn_ballot_w64(ws.m_run == M_INIT) != 0; };
+            int t = 0;
 
-            for (; st < n_lin_whole && adopting; ++st) {
-                const StageInfo si = begin_stage(st);
-                if (wave_has_queries) {
-                    fast_stage<kMaskNone, true>(ws, qf, lo, si.tileK, si.ma);
-                    adopting = still_adopting();
+            // whole linear tiles
+            for (; t < cb1 && adopting; t += TPS, buf ^= 1) {
+                begin_stage(buf);
+#pragma unroll 1
+                for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
+                    const TileInfo si = tile_info(t + j, buf, j);
+                    if (wave_has_queries) fast_stage<kMaskNone, true>(ws, qf, lo, si.tileK, si.ma);
+                }
+                adopting = wave_has_queries && still_adopting();
+            }
+            for (; t < cb1; t += TPS, buf ^= 1) {
+                begin_stage(buf);
+#pragma unroll 1
+                for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
+                    const TileInfo si = tile_info(t + j, buf, j);
+                    if (wave_has_queries) fast_stage<kMaskNone, false>(ws, qf, lo, si.tileK, si.ma);
                 }
             }
-            for (; st < n_lin_whole; ++st) {
-                const StageInfo si = begin_stage(st);
-                if (wave_has_queries) fast_stage<kMaskNone, false>(ws, qf, lo, si.tileK, si.ma);
-            }
-            for (; st < n_lin_stages; ++st) {  // ragged tile: at most one, keep it simple
-                const StageInfo si = begin_stage(st);
+            t = cb1;
+            // the ragged linear tile: at most one, keep it simple
+            for (; t < cb2; t += TPS, buf ^= 1) {
+                begin_stage(buf);
+                const TileInfo si = tile_info(t, buf, 0);
                 if (si.cls0 != kBlockSkip) {
                     fast_stage<kMaskLinear, true>(ws, qf, lo, si.tileK, si.ma);
                     adopting = still_adopting();
                 }
             }
+            t = cb2;
             if (!TEXTQ) {
-                for (; st < n_plain_end && adopting; ++st) {
-                    const StageInfo si = begin_stage(st);
-                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) {
-                        fast_stage<kMaskTable, true>(ws, qf, lo, si.tileK, si.ma);
-                        adopting = still_adopting();
+                // image tiles inside the grid
+                for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
+                    begin_stage(buf);
+#pragma unroll 1
+                    for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
+                        const TileInfo si = tile_info(t + j, buf, j);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true>(ws, qf, lo, si.tileK, si.ma);
+                    }
+                    adopting = wave_has_queries && still_adopting();
+                }
+                for (; t < cb3; t += TPS, buf ^= 1) {
+                    begin_stage(buf);
+#pragma unroll 1
+                    for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
+                        const TileInfo si = tile_info(t + j, buf, j);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
                     }
                 }
-                for (; st < n_plain_end; ++st) {
-                    const StageInfo si = begin_stage(st);
-                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
-                }
-                for (; st < n_stages; ++st) {  // border tiles: few, keep them simple
-                    const StageInfo si = begin_stage(st);
-                    if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) {
-                        fast_stage<kMaskImage, true>(ws, qf, lo, si.tileK, si.ma);
-                        adopting = still_adopting();
+                t = cb3;
+                // image tiles cut by the border: few, keep them simple
+                for (; t < cb4; t += TPS, buf ^= 1) {
+                    begin_stage(buf);
+#pragma unroll 1
+                    for (int j = 0; j < imin(TPS, cb4 - t); ++j) {
+                        const TileInfo si = tile_info(t + j, buf, j);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true>(ws, qf, lo, si.tileK, si.ma);
                     }
                 }
             }
@@ -736,7 +788,7 @@ __global__ void __launch_bounds__(128) clear_text_merge_kernel(const FwdParams p
 template <int NWY, int NWX, bool TEXTQ>
 hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 {
-    const size_t smem = (size_t)NSTAGE * 2 * TILE_BYTES;
+    const size_t smem = (size_t)NBUF * STAGE_BYTES;
     auto kern = clear_fwd_bf16_kernel<NWY, NWX, TEXTQ>;
     static bool attr_set = false;  // the attribute is per function, set once per process
     if (!attr_set) {
