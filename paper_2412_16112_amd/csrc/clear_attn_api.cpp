@@ -46,6 +46,7 @@ static int check_shape(int n_text, int gridH, int gridW, int r, std::string* why
     if (gridH < 1 || gridW < 1) { *why = "gridH and gridW must be >= 1"; return CLEAR_ERR_INVALID_ARG; }
     if (r < 1) { *why = "r must be >= 1"; return CLEAR_ERR_INVALID_ARG; }
     if (r > 32768) { *why = "r must be <= 32768"; return CLEAR_ERR_INVALID_ARG; }
+    if (gridH > 32767 || gridW > 32767) { *why = "gridH and gridW must be <= 32767"; return CLEAR_ERR_INVALID_ARG; }
     if ((long long)gridH * gridW + n_text > 0x7fffffffLL) { *why = "n_text + gridH*gridW must fit in 31 bits"; return CLEAR_ERR_INVALID_ARG; }
     return CLEAR_OK;
 }
@@ -172,7 +173,8 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
         delete ctx;
         return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
     }
-    // kernel-side tile lists: per query tile, key tiles that lie inside the grid first, border tiles last
+    // kernel-side tile lists: per query tile, the origins (row << 16 | col) of its key tiles, those inside the
+    // grid first, border tiles last
     std::vector<int> k_col(ctx->sched.col_idx.size()), n_plain(ctx->sched.row_ptr.size() - 1, 0);
     {
         const Schedule& sc = ctx->sched;
@@ -180,13 +182,14 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
             const int ty = id / sc.n_ktx, tx = id % sc.n_ktx;
             return (ty + 1) * sc.kth > gridH || (tx + 1) * sc.ktw > gridW;
         };
+        auto origin = [&](int id) { return ((id / sc.n_ktx) * sc.kth) << 16 | ((id % sc.n_ktx) * sc.ktw); };
         for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt) {
             int w = sc.row_ptr[qt];
             for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
-                if (!cut(sc.col_idx[e])) k_col[w++] = sc.col_idx[e];
+                if (!cut(sc.col_idx[e])) k_col[w++] = origin(sc.col_idx[e]);
             n_plain[qt] = w - sc.row_ptr[qt];
             for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
-                if (cut(sc.col_idx[e])) k_col[w++] = sc.col_idx[e];
+                if (cut(sc.col_idx[e])) k_col[w++] = origin(sc.col_idx[e]);
         }
     }
     std::vector<unsigned long long> mask_tbl;

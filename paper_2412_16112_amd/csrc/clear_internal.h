@@ -51,7 +51,7 @@ struct FwdParams {
     int n_qtx;         // query tiles per tile row
     int n_ktx;         // key tiles per tile row
     const int* row_ptr;  // device CSR
-    const int* col_idx;  // per query tile: key tiles inside the grid first (ascending), then the ones cut by the border
+    const int* col_idx;  // per query tile: key tile origins (row << 16 | col), tiles inside the grid first (ascending), then the ones cut by the border
     const int* n_plain;  // per query tile: how many of its key tiles lie inside the grid
     const unsigned long long* mask_tbl;  // bf16 kernels: lane masks per relative block offset (may be null)
     int mask_ry, mask_rx;

@@ -96,10 +96,16 @@ struct LaneOffsets {
 
 enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2, kMaskTable = 3 };
 
+// Read-only tables (tile lists, lane masks) are addressed through the constant address space so that
+// they are fetched with scalar loads: wave-uniform, and not counted among the vector loads whose
+// completion the tile prefetch waits on.
+typedef const __attribute__((address_space(4))) int* const_int_ptr;
+typedef const __attribute__((address_space(4))) unsigned long long* const_u64_ptr;
+
 struct MaskArgs {
     int a, b;  // linear: first token of the tile, token limit; image: tile origin (row, col)
     int hh, qy, qx, gridH, gridW, r2;
-    const unsigned long long* row[2];  // kMaskTable: 16 lane masks per key block (one per score register)
+    const_u64_ptr row[2];  // kMaskTable: 16 lane masks per key block (one per score register)
 };
 
 // Sets the scores of inadmissible (query, key) pairs of key block kb to -inf.  Register r of this lane
@@ -109,13 +115,9 @@ __device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma
 {
     if (MASK == kMaskTable) {
         // precomputed per relative block offset: bit l of row[r] says whether lane l keeps score register r
-        const unsigned long long* row = ma.row[kb & 1];
+        const_u64_ptr row = ma.row[kb & 1];  // wave-uniform address: the words are read into scalar registers
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const unsigned long long w = row[r];  // wave-uniform; say so, so that it is read into scalar registers
-            const unsigned lo32 = __builtin_amdgcn_readfirstlane((unsigned)w), hi32 = __builtin_amdgcn_readfirstlane((unsigned)(w >> 32));
-            s[r] = __builtin_amdgcn_inverse_ballot_w64(((unsigned long long)hi32 << 32) | lo32) ? s[r] : -INFINITY;
-        }
+        for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_inverse_ballot_w64(row[r]) ? s[r] : -INFINITY;
     } else if (MASK == kMaskLinear) {
         const int base = ma.a + 32 * kb + 4 * ma.hh;
 #pragma unroll
@@ -449,6 +451,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
     }
 
+    const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
+    const const_u64_ptr mask_tbl = (const_u64_ptr)p.mask_tbl;
+
     // ---- tile list: tokens [lin_begin, lin_limit) in 64-key tiles, then (image mode) the CSR row.
     // Tiles fall into four consecutive categories, each with its own code shape:
     //   [cb0, cb1) whole linear tiles   [cb1, cb2) the ragged linear tile (at most one)
@@ -464,11 +469,11 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     } else {
         lin_limit = p.n_text;
         n_lin_tiles = (p.n_text + TILE_KEYS - 1) / TILE_KEYS;
-        csr_begin = p.row_ptr[qt];
-        n_tiles = n_lin_tiles + (p.row_ptr[qt + 1] - csr_begin);
+        csr_begin = row_ptr[qt];
+        n_tiles = n_lin_tiles + (row_ptr[qt + 1] - csr_begin);
     }
     const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
-    const int cb3 = TEXTQ ? n_lin_tiles : (p.mask_tbl ? n_lin_tiles + p.n_plain[qt] : n_lin_tiles);
+    const int cb3 = TEXTQ ? n_lin_tiles : (p.mask_tbl ? n_lin_tiles + n_plain[qt] : n_lin_tiles);
     const int cb4 = n_tiles;
     auto stage_len = [&](int t) {  // tiles in the stage that starts at tile t
         const int e = t < cb1 ? cb1 : (t < cb2 ? cb2 : (t < cb3 ? cb3 : cb4));
@@ -481,9 +486,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             a = lin_begin + i * TILE_KEYS;
             b = -1;
         } else {
-            const int id = p.col_idx[csr_begin + i - n_lin_tiles];
-            a = (id / p.n_ktx) * kKeyTileH;
-            b = (id % p.n_ktx) * kKeyTileW;
+            const int packed = col_idx[csr_begin + i - n_lin_tiles];  // tile origin, row << 16 | col
+            a = packed >> 16;
+            b = packed & 0xffff;
         }
     };
 
@@ -588,7 +593,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
         si.ma.qy = qy; si.ma.qx = qx; si.ma.gridH = p.gridH; si.ma.gridW = p.gridW; si.ma.r2 = p.r2;
-        si.ma.row[0] = si.ma.row[1] = p.mask_tbl;
+        si.ma.row[0] = si.ma.row[1] = mask_tbl;
         if (!TEXTQ && !si.linear && p.mask_tbl) {
             // lane masks of the two blocks: whole blocks use the all-ones entry, unreachable blocks the all-zeros
             // entry at the end of the table
@@ -598,8 +603,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             const int dby = (ta - wy0) >> 2;
             const int i0 = (si.cls0 == kBlockPartial) ? (dby + p.mask_ry) * ncol + dbx + p.mask_rx : (si.cls0 == kBlockFull ? ones : zeros);
             const int i1 = (si.cls1 == kBlockPartial) ? (dby + 1 + p.mask_ry) * ncol + dbx + p.mask_rx : (si.cls1 == kBlockFull ? ones : zeros);
-            si.ma.row[0] = p.mask_tbl + 16 * i0;
-            si.ma.row[1] = p.mask_tbl + 16 * i1;
+            si.ma.row[0] = mask_tbl + 16 * i0;
+            si.ma.row[1] = mask_tbl + 16 * i1;
         }
         return si;
     };

@@ -86,9 +86,9 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
             a = lin_begin + (long long)st * TILE_KEYS;
             b = lin_limit;
         } else {
-            const int id = p.col_idx[csr_begin + st - n_lin_stages];
-            a = (id / p.n_ktx) * kKeyTileH;
-            b = (id % p.n_ktx) * kKeyTileW;
+            const int packed = p.col_idx[csr_begin + st - n_lin_stages];  // tile origin, row << 16 | col
+            a = packed >> 16;
+            b = packed & 0xffff;
         }
         __syncthreads();  // previous tile fully consumed
         for (int ch = tid; ch < TILE_KEYS * D / 4; ch += NT) {
