@@ -314,6 +314,14 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
     for (int i = 0; i < PD; ++i) op[i] = k_operand(i);
     f32x16 s0 = zero, s1 = zero;
     float mc = ws.m_run * c;
+    // kMaskTable: the 16 lane masks of a block sit in scalar registers.  Block 0's are fetched before the
+    // pipeline starts (their latency overlaps that of the first LDS operands), block 1's as soon as block
+    // 0's have been used, a dozen slots before they are needed.
+    unsigned long long mw[16];
+    if (MASK == kMaskTable) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mw[r] = ma.row[kb0 & 1][r];
+    }
 #pragma unroll
     for (int slot = 0; slot < 32; ++slot) {
         // prefetch the operand of slot + PD
@@ -340,11 +348,20 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
 #endif
         // vector work riding along
         if (slot == 8) {
-            apply_mask<MASK>(s0, kb0, ma);
+            if (MASK == kMaskTable) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s0[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s0[r] : -INFINITY;
+            } else {
+                apply_mask<MASK>(s0, kb0, ma);
+            }
             if (ADOPT) {
                 adopt_reference(ws, wave_pair_max(max_block(s0)));
                 mc = ws.m_run * c;
             }
+        }
+        if (slot == 9 && MASK == kMaskTable) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mw[r] = ma.row[(kb0 + 1) & 1][r];
         }
         if (slot == 9) exp_slice<0, 1>(s0, c, mc, sum, pf0);
         if (slot == 10) exp_slice<1, 2>(s0, c, mc, sum, pf0);
@@ -359,7 +376,12 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
         if (slot == 19) exp_slice<14, 16>(s0, c, mc, sum, pf0);
         if (has1) {
             if (slot == 20) {
-                apply_mask<MASK>(s1, kb0 + 1, ma);
+                if (MASK == kMaskTable) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s1[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s1[r] : -INFINITY;
+                } else {
+                    apply_mask<MASK>(s1, kb0 + 1, ma);
+                }
                 if (ADOPT) {
                     adopt_reference(ws, wave_pair_max(max_block(s1)));
                     mc = ws.m_run * c;
