@@ -174,7 +174,7 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
         return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
     }
     // kernel-side tile lists: per query tile, the origins (row << 16 | col) of its key tiles, those inside the
-    // grid first, border tiles last
+    // grid first (mirror pairs adjacent), border tiles last
     std::vector<int> k_col(ctx->sched.col_idx.size()), n_plain(ctx->sched.row_ptr.size() - 1, 0);
     {
         const Schedule& sc = ctx->sched;
@@ -183,10 +183,38 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
             return (ty + 1) * sc.kth > gridH || (tx + 1) * sc.ktw > gridW;
         };
         auto origin = [&](int id) { return ((id / sc.n_ktx) * sc.kth) << 16 | ((id % sc.n_ktx) * sc.ktw); };
+        std::vector<int> plain, used;
         for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt) {
-            int w = sc.row_ptr[qt];
+            // Tiles inside the grid, reordered so that each stage (two consecutive tiles) holds a tile and its
+            // point mirror through the centre of the query tile: what one wave's disc misses of the pair,
+            // the wave sharing its SIMD tends to reach, which evens out the work between barriers.
+            plain.clear();
             for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
-                if (!cut(sc.col_idx[e])) k_col[w++] = origin(sc.col_idx[e]);
+                if (!cut(sc.col_idx[e])) plain.push_back(sc.col_idx[e]);
+            used.assign(plain.size(), 0);
+            const int qy0 = (int)(qt / sc.n_qtx) * sc.qth, qx0 = (int)(qt % sc.n_qtx) * sc.qtw;
+            int w = sc.row_ptr[qt];
+            std::vector<int> single;
+            for (size_t i = 0; i < plain.size(); ++i) {
+                if (used[i]) continue;
+                used[i] = 1;
+                const int ky = (plain[i] / sc.n_ktx) * sc.kth, kx = (plain[i] % sc.n_ktx) * sc.ktw;
+                const int my = 2 * qy0 + sc.qth - sc.kth - ky, mx = 2 * qx0 + sc.qtw - sc.ktw - kx;
+                int partner = -1;
+                if (my >= 0 && mx >= 0 && my % sc.kth == 0 && mx % sc.ktw == 0) {
+                    const int mid = (my / sc.kth) * sc.n_ktx + mx / sc.ktw;
+                    for (size_t j = i + 1; j < plain.size(); ++j)
+                        if (!used[j] && plain[j] == mid) { partner = (int)j; break; }
+                }
+                if (partner >= 0) {
+                    used[partner] = 1;
+                    k_col[w++] = origin(plain[i]);
+                    k_col[w++] = origin(plain[partner]);
+                } else {
+                    single.push_back(plain[i]);
+                }
+            }
+            for (int id : single) k_col[w++] = origin(id);
             n_plain[qt] = w - sc.row_ptr[qt];
             for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
                 if (cut(sc.col_idx[e])) k_col[w++] = origin(sc.col_idx[e]);
