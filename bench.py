@@ -28,9 +28,20 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="flux-8k-r16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-image-rows", type=int, default=1536)
-    ap.add_argument("--cpu-text-rows", type=int, default=24)
+    ap.add_argument("--cpu-image-rows", type=int, default=131072)
+    ap.add_argument("--cpu-text-rows", type=int, default=512)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": 1 << 30, "copies": 3}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported. "
               "Heads are independent, so N GPUs would each take H/N heads with no communication inside the op." % args.gpus,
