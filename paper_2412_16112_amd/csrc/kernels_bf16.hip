@@ -313,7 +313,7 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
 #pragma unroll
     for (int i = 0; i < PD; ++i) op[i] = k_operand(i);
     f32x16 s0 = zero, s1 = zero;
-    float mc = ws.m_run * c;
+    float mc = ws.m_run * c, mc1 = mc;
     // kMaskTable: the 16 lane masks of a block sit in scalar registers.  Block 0's are fetched before the
     // pipeline starts (their latency overlaps that of the first LDS operands), block 1's as soon as block
     // 0's have been used, a dozen slots before they are needed.
@@ -363,37 +363,52 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
 #pragma unroll
             for (int r = 0; r < 16; ++r) mw[r] = ma.row[(kb0 + 1) & 1][r];
         }
-        if (slot == 9) exp_slice<0, 1>(s0, c, mc, sum, pf0);
-        if (slot == 10) exp_slice<1, 2>(s0, c, mc, sum, pf0);
-        if (slot == 11) exp_slice<2, 3>(s0, c, mc, sum, pf0);
-        if (slot == 12) exp_slice<3, 4>(s0, c, mc, sum, pf0);
-        if (slot == 13) exp_slice<4, 5>(s0, c, mc, sum, pf0);
-        if (slot == 14) exp_slice<5, 6>(s0, c, mc, sum, pf0);
-        if (slot == 15) exp_slice<6, 8>(s0, c, mc, sum, pf0);
-        if (slot == 16) exp_slice<8, 10>(s0, c, mc, sum, pf0);
-        if (slot == 17) exp_slice<10, 12>(s0, c, mc, sum, pf0);
-        if (slot == 18) exp_slice<12, 14>(s0, c, mc, sum, pf0);
-        if (slot == 19) exp_slice<14, 16>(s0, c, mc, sum, pf0);
-        if (has1) {
-            if (slot == 20) {
-                if (MASK == kMaskTable) {
+        if (slot == 16 && has1) {
+            if (MASK == kMaskTable) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s1[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s1[r] : -INFINITY;
-                } else {
-                    apply_mask<MASK>(s1, kb0 + 1, ma);
+                for (int r = 0; r < 16; ++r) s1[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s1[r] : -INFINITY;
+            } else {
+                apply_mask<MASK>(s1, kb0 + 1, ma);
+            }
+            if (ADOPT) {
+                adopt_reference(ws, wave_pair_max(max_block(s1)));
+                mc1 = ws.m_run * c;
+            }
+        }
+        // Exponentials as a three-deep vector pipeline over pairs of scores, so that the instructions of
+        // one slot do not wait on each other: pair g of block 0 is scaled in slot 8 + g, exponentiated in
+        // slot 9 + g, summed and packed in slot 10 + g; block 1 runs the same eight slots later.  P[0..7]
+        // of a block is complete three slots before the matrix instruction that needs it.
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            if (slot == 8 + g) {
+                s0[2 * g] = __builtin_fmaf(s0[2 * g], c, -mc);
+                s0[2 * g + 1] = __builtin_fmaf(s0[2 * g + 1], c, -mc);
+            }
+            if (slot == 9 + g) {
+                s0[2 * g] = __builtin_amdgcn_exp2f(s0[2 * g]);
+                s0[2 * g + 1] = __builtin_amdgcn_exp2f(s0[2 * g + 1]);
+            }
+            if (slot == 10 + g) {
+                sum += s0[2 * g] + s0[2 * g + 1];
+                pf0[g >> 2][2 * (g & 3)] = (__bf16)s0[2 * g];
+                pf0[g >> 2][2 * (g & 3) + 1] = (__bf16)s0[2 * g + 1];
+            }
+            if (has1) {
+                if (slot == 16 + g) {
+                    s1[2 * g] = __builtin_fmaf(s1[2 * g], c, -mc1);
+                    s1[2 * g + 1] = __builtin_fmaf(s1[2 * g + 1], c, -mc1);
                 }
-                if (ADOPT) {
-                    adopt_reference(ws, wave_pair_max(max_block(s1)));
-                    mc = ws.m_run * c;
+                if (slot == 17 + g) {
+                    s1[2 * g] = __builtin_amdgcn_exp2f(s1[2 * g]);
+                    s1[2 * g + 1] = __builtin_amdgcn_exp2f(s1[2 * g + 1]);
+                }
+                if (slot == 18 + g) {
+                    sum += s1[2 * g] + s1[2 * g + 1];
+                    pf1[g >> 2][2 * (g & 3)] = (__bf16)s1[2 * g];
+                    pf1[g >> 2][2 * (g & 3) + 1] = (__bf16)s1[2 * g + 1];
                 }
             }
-            if (slot == 21) exp_slice<0, 2>(s1, c, mc, sum, pf1);
-            if (slot == 22) exp_slice<2, 5>(s1, c, mc, sum, pf1);
-            if (slot == 23) exp_slice<5, 8>(s1, c, mc, sum, pf1);
-            if (slot == 24) exp_slice<8, 10>(s1, c, mc, sum, pf1);
-            if (slot == 25) exp_slice<10, 12>(s1, c, mc, sum, pf1);
-            if (slot == 26) exp_slice<12, 14>(s1, c, mc, sum, pf1);
-            if (slot == 27) exp_slice<14, 16>(s1, c, mc, sum, pf1);
         }
         SCHED_FENCE();
     }
@@ -572,7 +587,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     // so have everyone's, and every wave has left the other buffer, which is refilled with the next stage.
     int pf_tile = 0;  // first tile of the next stage to load
     auto begin_stage = [&](int buf) {
+#ifndef CLEAR_EXP_NO_VMWAIT
         wait_vmcnt<0>();
+#endif
 #ifndef CLEAR_EXP_NO_BARRIER
         __builtin_amdgcn_s_barrier();
 #endif
@@ -610,7 +627,11 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH,
                                            p.gridW, p.r2);
         }
+#ifdef CLEAR_EXP_FIXED_TILE
+        si.tileK = smem;
+#else
         si.tileK = smem + buf * STAGE_BYTES + j * (2 * TILE_BYTES);
+#endif
         si.ma.hh = hh;
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
@@ -713,7 +734,11 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
+#ifdef CLEAR_EXP_NO_SKIP
+                        if (wave_has_queries) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
+#else
                         if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
+#endif
                     }
                 }
                 t = cb3;
