@@ -241,18 +241,6 @@ __device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
 // Pins the instruction order: nothing is scheduled across this point.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// p = 2^{s c - mc} for elements [R0, R1) of one block; adds them to sum; packs them as bf16.
-template <int R0, int R1>
-__device__ __forceinline__ void exp_slice(const f32x16& s, float c, float mc, float& sum, bf16x8 (&pf)[2])
-{
-#pragma unroll
-    for (int r = R0; r < R1; ++r) {
-        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -mc));
-        sum += pv;
-        pf[r >> 3][r & 7] = (__bf16)pv;
-    }
-}
-
 __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char* kblk, unsigned off)
 {
     return *(const bf16x8*)(kblk + off);
@@ -286,25 +274,11 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
     float sum = 0.f;
 
     // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
-#if defined(CLEAR_EXP_NO_LDSREAD)
-    auto k_operand = [&](int slot) { return qf[slot & 7]; };
-    auto v_operand = [&](int slot) { return qf[slot & 7]; };
-#elif defined(CLEAR_EXP_NO_VREAD)
-    auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
-    auto v_operand = [&](int slot) { return qf[slot & 7]; };
-#elif defined(CLEAR_EXP_NO_KREAD)
-    auto k_operand = [&](int slot) { return qf[slot & 7]; };
-    auto v_operand = [&](int slot) {
-        const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
-        return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
-    };
-#else
     auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
     auto v_operand = [&](int slot) {
         const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
         return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
     };
-#endif
     auto block1_slot = [](int slot) { return (slot >= 8 && slot < 16) || slot >= 24; };
     // operands are read PD slots ahead into a ring of PD + 2 (the extra entry keeps a read from landing on
     // the registers the previous matrix instruction is still reading)
@@ -340,12 +314,6 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
             ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf0[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
         else if (has1)
             ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf1[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
-#ifdef CLEAR_EXP_NO_VALU
-        if (slot == 8) { for (int i = 0; i < 8; ++i) { pf0[0][i] = pf0[1][i] = (__bf16)s0[i]; } }
-        if (slot == 20) { for (int i = 0; i < 8; ++i) { pf1[0][i] = pf1[1][i] = (__bf16)s1[i]; } }
-        SCHED_FENCE();
-        continue;
-#endif
         // vector work riding along
         if (slot == 8) {
             if (MASK == kMaskTable) {
@@ -587,19 +555,13 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     // so have everyone's, and every wave has left the other buffer, which is refilled with the next stage.
     int pf_tile = 0;  // first tile of the next stage to load
     auto begin_stage = [&](int buf) {
-#ifndef CLEAR_EXP_NO_VMWAIT
         wait_vmcnt<0>();
-#endif
-#ifndef CLEAR_EXP_NO_BARRIER
         __builtin_amdgcn_s_barrier();
-#endif
         asm volatile("" ::: "memory");
-#ifndef CLEAR_EXP_NO_ISSUE
         if (pf_tile < n_tiles) {
             issue_stage(pf_tile, buf ^ 1);
             pf_tile += stage_len(pf_tile);
         }
-#endif
     };
 
     // Classifies the two key blocks of tile t against this wave's query patch and gathers what the
@@ -627,11 +589,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH,
                                            p.gridW, p.r2);
         }
-#ifdef CLEAR_EXP_FIXED_TILE
-        si.tileK = smem;
-#else
         si.tileK = smem + buf * STAGE_BYTES + j * (2 * TILE_BYTES);
-#endif
         si.ma.hh = hh;
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
@@ -734,11 +692,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-#ifdef CLEAR_EXP_NO_SKIP
-                        if (wave_has_queries) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
-#else
                         if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
-#endif
                     }
                 }
                 t = cb3;
