@@ -99,6 +99,11 @@ def main():
         "kernel_ms": {"image_query": phase_ms[0], "text_query": phase_ms[1], "text_merge": phase_ms[2]},
     }
 
+    # what the matrix pipeline alone sustains on this device right now (data-sheet peak: 2.5 PFLOP/s at 2.4 GHz)
+    mfma_tflops, mfma_mhz = ca.clear_attn_measure_mfma_peak(0.5)
+    roofline["measured_mfma_only"] = {"tflops": mfma_tflops, "shader_mhz": mfma_mhz,
+                                      "executed_frac_of_measured": executed_tflops / mfma_tflops}
+
     result = {
         "metric": "local-attn useful TFLOP/s (4*sumM*d)", "value": useful_tflops, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

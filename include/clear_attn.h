@@ -122,6 +122,12 @@ int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_i
  * the matrix pipeline, masked and padding slots included ("executed" work; useful work is sumM). */
 int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head);
 
+/* Measurement aid (Sec. 1's FLOP accounting is quoted against the matrix peak): runs back-to-back
+ * v_mfma_f32_32x32x16_bf16 on every SIMD of the current device for about `seconds` (0 < seconds <= 5)
+ * and reports the sustained dense bf16 rate of the last launch in TFLOP/s and the shader clock it ran
+ * at in MHz (host pointers, both required).  Synchronises the device; allocates and frees a few bytes. */
+int clear_attn_measure_mfma_peak(double seconds, double* tflops, double* shader_mhz);
+
 /* Reason of the last failure on this context (or of the last failed create when ctx is NULL).
  * The string is owned by the library and valid until the next call on the same context/thread. */
 const char* clear_attn_last_error(const clear_attn_ctx* ctx);

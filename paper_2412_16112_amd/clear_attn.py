@@ -18,7 +18,7 @@ EXPORTS = [
     "clear_attn_destroy",
     "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
-    "clear_attn_last_error",
+    "clear_attn_measure_mfma_peak", "clear_attn_last_error",
 ]
 
 _lib = None
@@ -70,6 +70,13 @@ def clear_attn_mask_count(n_text, gridH, gridW, r):
     out = ctypes.c_ulonglong(0)
     _check(lib().clear_attn_mask_count(n_text, gridH, gridW, r, ctypes.byref(out)))
     return int(out.value)
+
+
+def clear_attn_measure_mfma_peak(seconds=0.5):
+    """(sustained dense bf16 MFMA TFLOP/s, shader clock in MHz) of the current device."""
+    tf, mhz = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().clear_attn_measure_mfma_peak(ctypes.c_double(seconds), ctypes.byref(tf), ctypes.byref(mhz)))
+    return float(tf.value), float(mhz.value)
 
 
 def clear_attn_tile_shape(head_dim, dtype):

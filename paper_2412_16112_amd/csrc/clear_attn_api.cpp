@@ -434,6 +434,19 @@ int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pai
     return CLEAR_OK;
 }
 
+int clear_attn_measure_mfma_peak(double seconds, double* tflops, double* shader_mhz)
+{
+    if (!tflops || !shader_mhz) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL argument");
+    if (!(seconds > 0.0) || seconds > 5.0) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "seconds must be in (0, 5]");
+    int dev = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e == hipSuccess) e = measure_mfma_peak(prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256, seconds, tflops, shader_mhz);
+    if (e != hipSuccess) return fail(nullptr, CLEAR_ERR_HIP, std::string("HIP error in measure_mfma_peak: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
 const char* clear_attn_last_error(const clear_attn_ctx* ctx)
 {
     return ctx ? ctx->err.c_str() : g_create_error.c_str();

@@ -72,5 +72,7 @@ hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
 void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl);
 int f32_text_queries_per_block();
+// mfma_peak.hip: sustained rate of back-to-back bf16 MFMAs on every SIMD, and the shader clock it ran at.
+hipError_t measure_mfma_peak(int num_cus, double seconds, double* tflops, double* shader_mhz);
 
 }  // namespace clear
