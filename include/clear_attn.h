@@ -122,6 +122,47 @@ int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_i
  * the matrix pipeline, masked and padding slots included ("executed" work; useful work is sumM). */
 int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head);
 
+/* ---- Row bands: patch-parallel inference, one band of image rows per GPU (multi-GPU section, Eq. 7) ----
+ *
+ * The gridH_total x gridW feature map is cut into n_bands bands of whole rows.  A band is processed
+ * with a context created for its LOCAL grid: halo_top + (y1 - y0) + halo_bottom rows by gridW columns,
+ * where the halo rows are copies of the r - 1 rows of K and V that the neighbouring bands hold next to the
+ * cut (the only exchange the image tokens need).  The local tensors are laid out like any other:
+ * [B, H, n_text + local_rows * gridW, head_dim], text tokens first.
+ *
+ * clear_attn_band_layout: rows [*y0, *y1) of band `band` of n_bands (as even as possible, larger bands
+ * first) and the halo rows it needs on either side.  CLEAR_ERR_UNSUPPORTED when a band would be narrower
+ * than its halo of r - 1 rows (the halo would have to come from beyond the adjacent band).  Host only. */
+int clear_attn_band_layout(int gridH_total, int r, int n_bands, int band, int* y0, int* y1, int* halo_top,
+                           int* halo_bottom);
+
+/* Forward pass of one band.  ctx, Q, K, V, O, B .. r, stream: as for clear_attn_forward, for the local grid.
+ * Image queries: only the rows [own_y0, own_y1) of the local grid are computed and written to O (exactly
+ * their output in the undivided problem when the halo holds the r - 1 neighbouring rows); halo rows of O
+ * are left untouched, and so are the text rows.
+ * Text queries: attend to the owned image rows and, if text_keys != 0, to the text keys; the softmax output
+ * over those keys goes to text_o (device, fp32, [B, H, n_text, head_dim]) and the natural logarithm of the
+ * softmax denominator sum_j exp(q.k_j / sqrt(head_dim)) to text_lse (device, fp32, [B, H, n_text]); both
+ * caller-owned, required when n_text > 0.  Combine the bands' results with clear_attn_merge_text.
+ * Never synchronises; allocates only if the text workspace has to grow (see clear_attn_reserve). */
+int clear_attn_forward_band(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B,
+                            int H, int n_text, int gridH, int gridW, int head_dim, int r, int own_y0,
+                            int own_y1, int text_keys, float* text_o, float* text_lse, void* stream);
+
+typedef enum {
+    CLEAR_MERGE_EXACT = 0,   /* weights exp(lse_p) / sum exp(lse_p): the softmax over the union of the bands' key
+                                sets, exact when those sets are disjoint (text keys counted in one band only) */
+    CLEAR_MERGE_AVERAGE = 1  /* Eq. 7: the plain mean of the per-band softmax outputs (each band: text keys and
+                                its own image keys) */
+} clear_merge_mode;
+
+/* Combines n_parts (1..64) band results for the text rows and writes them, converted to dtype, into rows
+ * 0 .. n_text-1 of every (batch, head) of O, a device [B, H, N, head_dim] tensor.  text_o, text_lse: HOST
+ * arrays of n_parts DEVICE pointers as filled by clear_attn_forward_band (on several GPUs: after an
+ * all-gather of these constant-size buffers).  Enqueues one kernel on stream; no allocation, no sync. */
+int clear_attn_merge_text(int n_parts, const float* const* text_o, const float* const* text_lse, int B, int H,
+                          int n_text, long long N, int head_dim, int mode, void* O, int dtype, void* stream);
+
 /* Measurement aid (Sec. 1's FLOP accounting is quoted against the matrix peak): runs back-to-back
  * v_mfma_f32_32x32x16_bf16 on every SIMD of the current device for about `seconds` (0 < seconds <= 5)
  * and reports the sustained dense bf16 rate of the last launch in TFLOP/s and the shader clock it ran

@@ -11,11 +11,12 @@ LIB_PATH = os.path.join(_HERE, "libclear_attn.so")
 
 CLEAR_OK, CLEAR_ERR_INVALID_ARG, CLEAR_ERR_UNSUPPORTED, CLEAR_ERR_ALLOC, CLEAR_ERR_HIP, CLEAR_ERR_MISMATCH = range(6)
 CLEAR_BF16, CLEAR_F32 = 0, 1
+CLEAR_MERGE_EXACT, CLEAR_MERGE_AVERAGE = 0, 1
 CLEAR_TILE_PARTIAL, CLEAR_TILE_FULL = 0, 1
 
 EXPORTS = [
     "clear_attn_create", "clear_attn_reserve", "clear_attn_forward", "clear_attn_forward_profile",
-    "clear_attn_destroy",
+    "clear_attn_destroy", "clear_attn_forward_band", "clear_attn_band_layout", "clear_attn_merge_text",
     "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
     "clear_attn_measure_mfma_peak", "clear_attn_last_error",
@@ -52,6 +53,10 @@ def lib():
         L.clear_attn_schedule_size.argtypes = [vp, ip, ip, ip, ip, ip, llp]
         L.clear_attn_schedule_copy.argtypes = [vp, vp, vp, vp]
         L.clear_attn_executed_pairs.argtypes = [vp, ullp]
+        L.clear_attn_forward_band.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp, vp, vp]
+        L.clear_attn_band_layout.argtypes = [i, i, i, i, ip, ip, ip, ip]
+        L.clear_attn_merge_text.argtypes = [i, vp, vp, i, i, i, ctypes.c_longlong, i, i, vp, i, vp]
+        L.clear_attn_measure_mfma_peak.argtypes = [ctypes.c_double, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.clear_attn_last_error.argtypes = [vp]
         L.clear_attn_last_error.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -138,6 +143,25 @@ class ClearAttn:
                                         n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
 
+    def forward_band(self, Q, K, V, O, own_y0, own_y1, text_keys, text_o=None, text_lse=None, stream=None):
+        """clear_attn_forward_band on the context's (local) grid.  Returns (O, text_o, text_lse)."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        if n_text > 0:
+            if text_o is None:
+                text_o = torch.empty((B, H, n_text, d), dtype=torch.float32, device=Q.device)
+            if text_lse is None:
+                text_lse = torch.empty((B, H, n_text), dtype=torch.float32, device=Q.device)
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        _check(lib().clear_attn_forward_band(
+            self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, n_text, gridH, gridW, head_dim, r,
+            own_y0, own_y1, int(bool(text_keys)), ctypes.c_void_p(text_o.data_ptr() if text_o is not None else None),
+            ctypes.c_void_p(text_lse.data_ptr() if text_lse is not None else None), ctypes.c_void_p(s)), self._ctx)
+        return O, text_o, text_lse
+
     def forward_profile(self, Q, K, V, O, reps=5, stream=None):
         """Average milliseconds per launch of (image-query, text-query, merge) kernels; synchronises."""
         import torch
@@ -178,6 +202,26 @@ class ClearAttn:
             self.destroy()
         except Exception:
             pass
+
+
+def clear_attn_band_layout(gridH_total, r, n_bands, band):
+    """(y0, y1, halo_top, halo_bottom) of one band."""
+    v = [ctypes.c_int(0) for _ in range(4)]
+    _check(lib().clear_attn_band_layout(gridH_total, r, n_bands, band, *[ctypes.byref(x) for x in v]))
+    return tuple(int(x.value) for x in v)
+
+
+def clear_attn_merge_text(text_o, text_lse, O, n_text, mode, stream=None):
+    """Combines per-band text results (lists of device tensors) into the text rows of O [B, H, N, d]."""
+    import torch
+    n = len(text_o)
+    B, H, N, d = O.shape
+    po = (ctypes.c_void_p * n)(*[t.data_ptr() for t in text_o])
+    pl = (ctypes.c_void_p * n)(*[t.data_ptr() for t in text_lse])
+    s = torch.cuda.current_stream(O.device).cuda_stream if stream is None else stream
+    _check(lib().clear_attn_merge_text(n, po, pl, B, H, n_text, ctypes.c_longlong(N), d, mode, ctypes.c_void_p(O.data_ptr()),
+                                       _dtype_code(O), ctypes.c_void_p(s)))
+    return O
 
 
 def clear_attn_forward_once(Q, K, V, n_text, gridH, gridW, r):

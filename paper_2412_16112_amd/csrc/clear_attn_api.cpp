@@ -290,8 +290,16 @@ int clear_attn_reserve(clear_attn_ctx* ctx, int BH)
 }
 
 // Validates the arguments of a forward call and fills the kernel parameters.
+// band == nullptr: the whole grid.
+struct BandArgs {
+    int own_y0, own_y1;  // image rows [own_y0, own_y1) of the context's grid carry queries; the rest is halo
+    int text_keys;       // whether the text queries see the text keys in this band
+    float* text_o;
+    float* text_lse;
+};
+
 static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
-                           int n_text, int gridH, int gridW, int head_dim, int r, FwdParams* out)
+                           int n_text, int gridH, int gridW, int head_dim, int r, const BandArgs* band, FwdParams* out)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (!Q || !K || !V || !O) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be non-NULL");
@@ -310,6 +318,12 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
             const uintptr_t i0 = (uintptr_t)in, i1 = i0 + bytes;
             if (o0 < i1 && i0 < o1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "O overlaps an input tensor");
         }
+    }
+    if (band) {
+        if (band->own_y0 < 0 || band->own_y0 >= band->own_y1 || band->own_y1 > gridH)
+            return fail(ctx, CLEAR_ERR_INVALID_ARG, "band rows must satisfy 0 <= own_y0 < own_y1 <= gridH");
+        if (n_text > 0 && (!band->text_o || !band->text_lse)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "text_o and text_lse must be non-NULL when n_text > 0");
+        if (n_text > 0 && (((uintptr_t)band->text_o | (uintptr_t)band->text_lse) & 3)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "text_o and text_lse must be 4-byte aligned");
     }
     const int BH = B * H;
     const Schedule& s = ctx->sched;
@@ -331,12 +345,32 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.mask_ry = ctx->mask_ry;
     p.mask_rx = ctx->mask_rx;
     p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
+    p.own_y0 = 0;
+    p.own_y1 = gridH;
+    p.qt_begin = 0;
+    p.n_q_tiles_launch = (int)n_q_tiles;
+    p.NV = N;
+    p.vkeys_text = 0x7fffffff;
+    p.vshift = 0;
+    if (band) {
+        p.own_y0 = band->own_y0;
+        p.own_y1 = band->own_y1;
+        const int ty0 = band->own_y0 / s.qth, ty1 = (band->own_y1 + s.qth - 1) / s.qth;  // tile rows that hold owned rows
+        p.qt_begin = ty0 * s.n_qtx;
+        p.n_q_tiles_launch = (ty1 - ty0) * s.n_qtx;
+        // keys of the text queries: [the text keys,] then the owned image rows
+        p.vkeys_text = band->text_keys ? n_text : 0;
+        p.NV = (long long)p.vkeys_text + (long long)(band->own_y1 - band->own_y0) * gridW;
+        p.vshift = (int)((long long)n_text + (long long)band->own_y0 * gridW - p.vkeys_text);
+        p.band_o = band->text_o;
+        p.band_lse = band->text_lse;
+    }
     if (n_text > 0) {
         int rc = clear_attn_reserve(ctx, BH);
         if (rc != CLEAR_OK) return rc;
         const int per_block = ctx->dtype == CLEAR_BF16 ? bf16_text_queries_per_block() : f32_text_queries_per_block();
         p.n_tq_tiles = (n_text + per_block - 1) / per_block;
-        choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
+        choose_text_splits(p.NV, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
         if (p.n_splits > ctx->ws_max_splits) return fail(ctx, CLEAR_ERR_HIP, "internal: split count exceeds workspace");
         p.ws_o = ctx->d_ws_o;
         p.ws_ml = ctx->d_ws_ml;
@@ -354,7 +388,7 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
                        int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
     if (rc != CLEAR_OK) return rc;
     hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
@@ -366,7 +400,7 @@ int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K
                                float* phase_ms)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
     if (rc != CLEAR_OK) return rc;
     if (!phase_ms || reps < 1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "phase_ms must be non-NULL and reps >= 1");
     hipStream_t st = (hipStream_t)stream;
@@ -387,6 +421,57 @@ int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K
     if (ev[0]) (void)hipEventDestroy(ev[0]);
     if (ev[1]) (void)hipEventDestroy(ev[1]);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("profile run failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+int clear_attn_forward_band(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
+                            int n_text, int gridH, int gridW, int head_dim, int r, int own_y0, int own_y1,
+                            int text_keys, float* text_o, float* text_lse, void* stream)
+{
+    const BandArgs band = {own_y0, own_y1, text_keys != 0, text_o, text_lse};
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &band, &p);
+    if (rc != CLEAR_OK) return rc;
+    hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+int clear_attn_band_layout(int gridH, int r, int n_bands, int band, int* y0, int* y1, int* halo_top, int* halo_bottom)
+{
+    if (gridH < 1 || r < 1 || n_bands < 1 || band < 0 || band >= n_bands) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "need gridH, r, n_bands >= 1 and 0 <= band < n_bands");
+    if (!y0 || !y1 || !halo_top || !halo_bottom) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL output pointer");
+    if (n_bands > gridH) return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "more bands than image rows");
+    const int base = gridH / n_bands, extra = gridH % n_bands;  // the first `extra` bands hold one row more
+    // a halo of r - 1 rows must come from the adjacent band alone (one exchange with each neighbour)
+    if (n_bands > 1 && base < r - 1) return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "bands narrower than the r - 1 halo rows are not supported");
+    const int b0 = band * base + std::min(band, extra);
+    const int b1 = b0 + base + (band < extra ? 1 : 0);
+    *y0 = b0;
+    *y1 = b1;
+    *halo_top = std::min(r - 1, b0);
+    *halo_bottom = std::min(r - 1, gridH - b1);
+    return CLEAR_OK;
+}
+
+int clear_attn_merge_text(int n_parts, const float* const* text_o, const float* const* text_lse, int B, int H, int n_text,
+                          long long N, int head_dim, int mode, void* O, int dtype, void* stream)
+{
+    if (n_parts < 1 || n_parts > kMaxMergeParts) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "n_parts must be in [1, 64]");
+    if (!text_o || !text_lse || !O) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL argument");
+    if (B < 1 || H < 1 || n_text < 1 || N < n_text || head_dim < 1 || head_dim > 1024) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "need B, H, n_text >= 1, N >= n_text, 1 <= head_dim <= 1024");
+    if (mode != CLEAR_MERGE_EXACT && mode != CLEAR_MERGE_AVERAGE) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "mode must be CLEAR_MERGE_EXACT or CLEAR_MERGE_AVERAGE");
+    if (dtype != CLEAR_BF16 && dtype != CLEAR_F32) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "dtype must be CLEAR_BF16 or CLEAR_F32");
+    if ((long long)B * H * n_text > 0x7fffffffLL) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "B*H*n_text must fit in 31 bits");
+    MergeParts parts;
+    parts.n = n_parts;
+    for (int i = 0; i < n_parts; ++i) {
+        if (!text_o[i] || !text_lse[i]) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL part pointer");
+        parts.o[i] = text_o[i];
+        parts.lse[i] = text_lse[i];
+    }
+    hipError_t e = launch_merge_text(parts, B * H, n_text, N, head_dim, mode, O, dtype, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(nullptr, CLEAR_ERR_HIP, std::string("merge launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }
 

@@ -62,6 +62,17 @@ struct FwdParams {
     int split_keys;   // keys per split, multiple of 64
     float* ws_o;      // [B*H][n_splits][n_text][head_dim] un-normalised partial outputs
     float* ws_ml;     // [B*H][n_splits][n_text][2]        running max (raw logit) and denominator
+    // Row-band mode (one band of image rows with its halo; Sec. 3.4).  Whole grid: own_y0 = 0, own_y1 = gridH,
+    // qt_begin = 0, n_q_tiles_launch = n_q_tiles, NV = N, vkeys_text = INT_MAX, vshift = 0, band_o = null.
+    int own_y0, own_y1;    // image rows whose queries are computed; the other rows are halo: keys only
+    int qt_begin;          // first query tile launched (tile rows covering the owned rows)
+    int n_q_tiles_launch;  // query tiles launched per (batch, head)
+    // key list of the text-query pass by "virtual" index v in [0, NV): token v for v < vkeys_text, else v + vshift
+    long long NV;
+    int vkeys_text;
+    int vshift;
+    float* band_o;    // when set, the text merge writes fp32 softmax outputs [B*H][n_text][head_dim] here ...
+    float* band_lse;  // ... and the natural log of the softmax denominators [B*H][n_text] here, not O's text rows
 };
 
 // Launchers (kernels_bf16.hip, kernels_f32.hip).  Each returns the first HIP error met.
@@ -72,6 +83,15 @@ hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
 void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl);
 int f32_text_queries_per_block();
+// band_merge.hip: combination of the text-query outputs of several row bands.
+constexpr int kMaxMergeParts = 64;
+struct MergeParts {
+    int n;
+    const float* o[kMaxMergeParts];    // [B*H][n_text][head_dim] softmax outputs
+    const float* lse[kMaxMergeParts];  // [B*H][n_text] natural log of the softmax denominators
+};
+hipError_t launch_merge_text(const MergeParts& parts, int BH, int n_text, long long N, int head_dim, int mode, void* O, int dtype,
+                             hipStream_t stream);
 // mfma_peak.hip: sustained rate of back-to-back bf16 MFMAs on every SIMD, and the shader clock it ran at.
 hipError_t measure_mfma_peak(int num_cus, double seconds, double* tflops, double* shader_mhz);
 

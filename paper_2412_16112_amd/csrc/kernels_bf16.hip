@@ -415,8 +415,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         qt = t % p.n_tq_tiles;
         bh = t / p.n_tq_tiles;
     } else {
-        qt = vid % p.n_q_tiles;
-        bh = vid / p.n_q_tiles;
+        qt = p.qt_begin + vid % p.n_q_tiles_launch;
+        bh = vid / p.n_q_tiles_launch;
     }
     const long long head_off = (long long)bh * p.N * D;  // elements
     const __bf16* const Qh = (const __bf16*)p.Q + head_off;
@@ -439,8 +439,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         wx0 = (qt % p.n_qtx) * (NWX * kWaveQW) + (wave % NWX) * kWaveQW;
         qy = wy0 + (qi >> 3);
         qx = wx0 + (qi & 7);
-        q_valid = qy < p.gridH && qx < p.gridW;
-        wave_has_queries = wy0 < p.gridH && wx0 < p.gridW;
+        // (row-band mode: only the rows [own_y0, own_y1) carry queries; the halo rows are keys only)
+        q_valid = qy < p.gridH && qx < p.gridW && qy >= p.own_y0 && qy < p.own_y1;
+        wave_has_queries = wy0 < p.gridH && wx0 < p.gridW && wy0 < p.own_y1 && wy0 + kWaveQH > p.own_y0;
         q_token = p.n_text + imin(qy, p.gridH - 1) * p.gridW + imin(qx, p.gridW - 1);
     }
 
@@ -468,7 +469,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     int lin_begin = 0, lin_limit = 0;
     if (TEXTQ) {
         lin_begin = split * p.split_keys;
-        lin_limit = (long long)lin_begin + p.split_keys < p.N ? lin_begin + p.split_keys : (int)p.N;
+        lin_limit = (long long)lin_begin + p.split_keys < p.NV ? lin_begin + p.split_keys : (int)p.NV;
         n_lin_tiles = (lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS;
         n_tiles = n_lin_tiles;
     } else {
@@ -510,6 +511,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             int token;
             if (b < 0) {
                 token = imin(a + row, lin_limit - 1);
+                if (TEXTQ && token >= p.vkeys_text) token += p.vshift;  // position in the key list -> token
             } else {
                 const int ky = imin(a + (row >> 3), p.gridH - 1);
                 const int kx = imin(b + (row & 7), p.gridW - 1);
@@ -788,7 +790,13 @@ __global__ void __launch_bounds__(128) clear_text_merge_kernel(const FwdParams p
         den += w * p.ws_ml[r * 2 + 1];
         num += w * p.ws_o[r * d + ch];
     }
-    ((OutT*)p.O)[((long long)bh * p.N + q) * d + ch] = (OutT)(num / den);
+    if (p.band_o) {
+        p.band_o[(long long)row * d + ch] = num / den;
+        // sum_j exp(s_j / sqrt(d)) = den * 2^{m c}
+        if (ch == 0) p.band_lse[row] = __logf(den) + m * p.scale_log2e * 0.6931471805599453f;
+    } else {
+        ((OutT*)p.O)[((long long)bh * p.N + q) * d + ch] = (OutT)(num / den);
+    }
 }
 
 template <int NWY, int NWX, bool TEXTQ>
@@ -839,7 +847,7 @@ hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase)
     const int BH = p.B * p.H;
     hipError_t e = hipSuccess;
     if (phase == kPhaseAll || phase == kPhaseImage) {
-        e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_q_tiles, stream);
+        e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_q_tiles_launch, stream);
         if (e != hipSuccess) return e;
     }
     if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextQuery)) {

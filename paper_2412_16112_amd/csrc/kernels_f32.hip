@@ -31,8 +31,8 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
             qt = t % p.n_tq_tiles;
             bh = t / p.n_tq_tiles;
         } else {
-            qt = vid % p.n_q_tiles;
-            bh = vid / p.n_q_tiles;
+            qt = p.qt_begin + vid % p.n_q_tiles_launch;
+            bh = vid / p.n_q_tiles_launch;
         }
     }
     const long long head_off = (long long)bh * p.N * D;
@@ -50,7 +50,7 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
     } else {
         qy = (qt / p.n_qtx) * kF32QTileH + tid / kF32QTileW;
         qx = (qt % p.n_qtx) * kF32QTileW + tid % kF32QTileW;
-        q_valid = qy < p.gridH && qx < p.gridW;
+        q_valid = qy < p.gridH && qx < p.gridW && qy >= p.own_y0 && qy < p.own_y1;  // (row-band mode: owned rows only)
         q_token = (long long)p.n_text + (long long)imin(qy, p.gridH - 1) * p.gridW + imin(qx, p.gridW - 1);
     }
 
@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
     long long lin_begin = 0, lin_limit = 0;
     if (TEXTQ) {
         lin_begin = (long long)split * p.split_keys;
-        lin_limit = lin_begin + p.split_keys < p.N ? lin_begin + p.split_keys : p.N;
+        lin_limit = lin_begin + p.split_keys < p.NV ? lin_begin + p.split_keys : p.NV;
         n_lin_stages = (int)((lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS);
         n_stages = n_lin_stages;
     } else {
@@ -97,6 +97,7 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
             if (linear) {
                 token = a + slot;
                 if (token > b - 1) token = b - 1;
+                if (TEXTQ && token >= p.vkeys_text) token += p.vshift;  // position in the key list -> token
             } else {
                 const int ky = imin((int)a + slot / kKeyTileW, p.gridH - 1);
                 const int kx = imin((int)b + slot % kKeyTileW, p.gridW - 1);
@@ -178,7 +179,12 @@ __global__ void __launch_bounds__(D) clear_text_merge_f32_kernel(const FwdParams
         den += w * p.ws_ml[r * 2 + 1];
         num += w * p.ws_o[r * D + ch];
     }
-    ((float*)p.O)[((long long)bh * p.N + q) * D + ch] = num / den;
+    if (p.band_o) {
+        p.band_o[(long long)row * D + ch] = num / den;
+        if (ch == 0) p.band_lse[row] = logf(den) + m * p.scale_log2e * 0.6931471805599453f;
+    } else {
+        ((float*)p.O)[((long long)bh * p.N + q) * D + ch] = num / den;
+    }
 }
 
 }  // namespace
@@ -190,7 +196,7 @@ hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase)
     const int BH = p.B * p.H;
     hipError_t e = hipSuccess;
     if (phase == kPhaseAll || phase == kPhaseImage) {
-        hipLaunchKernelGGL(clear_fwd_f32_kernel<false>, dim3(BH * p.n_q_tiles), dim3(NT), 0, stream, p);
+        hipLaunchKernelGGL(clear_fwd_f32_kernel<false>, dim3(BH * p.n_q_tiles_launch), dim3(NT), 0, stream, p);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

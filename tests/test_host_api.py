@@ -91,3 +91,26 @@ def test_schedule_bit_exact_large(name):
     for a, b in zip(got, ref):
         assert np.array_equal(a, b)
     assert got[2].any() == (w.r >= 32)
+
+
+def test_band_layout_partitions_and_halos():
+    from oracle import patch_parallel as pp
+    for gridH, r, n in [(512, 16, 8), (64, 16, 4), (50, 6, 7), (23, 3, 5), (16, 4, 3), (9, 1, 9), (12, 5, 1)]:
+        rows = [ca.clear_attn_band_layout(gridH, r, n, b) for b in range(n)]
+        assert [x[:2] for x in rows] == pp.band_rows(gridH, n)
+        for y0, y1, ht, hb in rows:
+            assert ht == min(r - 1, y0) and hb == min(r - 1, gridH - y1)
+
+
+def test_band_layout_rejects_bands_narrower_than_the_halo():
+    # 64 rows in 8 bands of 8 with r = 16: the 15 halo rows would reach across two neighbours
+    with pytest.raises(ca.ClearAttnError) as e:
+        ca.clear_attn_band_layout(64, 16, 8, 0)
+    assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+    with pytest.raises(ca.ClearAttnError) as e:
+        ca.clear_attn_band_layout(4, 2, 5, 0)
+    assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+    for bad in [(0, 4, 1, 0), (8, 0, 1, 0), (8, 4, 0, 0), (8, 4, 2, 2), (8, 4, 2, -1)]:
+        with pytest.raises(ca.ClearAttnError) as e:
+            ca.clear_attn_band_layout(*bad)
+        assert e.value.status == ca.CLEAR_ERR_INVALID_ARG
