@@ -30,6 +30,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-image-rows", type=int, default=131072)
     ap.add_argument("--cpu-text-rows", type=int, default=512)
+    ap.add_argument("--bands", type=int, default=0,
+                    help="row-band mode: time ONE band of the workload cut into this many bands (one GPU's share of a "
+                         "patch-parallel run; no second GPU is used)")
+    ap.add_argument("--band", type=int, default=-1, help="which band (default: a middle one, halo on both sides)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -56,6 +60,9 @@ def main():
     w = WORKLOADS[args.workload]
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.bands > 0:
+        bench_band(args, w, dev)
+        return
     Q, K, V = make_qkv(w, dev)
     O = torch.empty_like(Q)
     dtype_code = ca.CLEAR_BF16 if w.dtype == "bf16" else ca.CLEAR_F32
@@ -141,6 +148,69 @@ def main():
                                      "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
     ctx.destroy()
     print(json.dumps(result))
+
+
+def bench_band(args, w, dev):
+    """One band of a patch-parallel run: the band's image queries (with halo rows as extra keys) and the text
+    queries over the band's own keys, plus the merge of n_bands text partials.  Synthetic tensors of the band's
+    local shape; `value` is the useful TFLOP/s of this one GPU's share."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2412_16112_amd import clear_attn as ca
+    from paper_2412_16112_amd.inputs import make_qkv
+
+    band = args.band if args.band >= 0 else args.bands // 2
+    y0, y1, ht, hb = ca.clear_attn_band_layout(w.gridH, w.r, args.bands, band)
+    rows = ht + (y1 - y0) + hb
+    wl = dataclasses.replace(w, name="%s band %d/%d" % (w.name, band, args.bands), gridH=rows)
+    Q, K, V = make_qkv(wl, dev)
+    O = torch.empty_like(Q)
+    dtype_code = ca.CLEAR_BF16 if w.dtype == "bf16" else ca.CLEAR_F32
+    ctx = ca.ClearAttn(w.n_text, rows, w.gridW, w.head_dim, w.r, dtype_code)
+    ctx.reserve(w.B * w.H)
+    to = torch.empty((w.B, w.H, w.n_text, w.head_dim), dtype=torch.float32, device=dev)
+    tl = torch.empty((w.B, w.H, w.n_text), dtype=torch.float32, device=dev)
+    parts_o, parts_l = [to] * args.bands, [tl] * args.bands  # stand-ins for the gathered partials of the other bands
+
+    def step():
+        ctx.forward_band(Q, K, V, O, ht, ht + (y1 - y0), True, to, tl)
+        ca.clear_attn_merge_text(parts_o, parts_l, O, w.n_text, ca.CLEAR_MERGE_AVERAGE)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # useful pairs of this band: its image queries in the undivided problem + text queries over text and own image keys
+    BH = w.B * w.H
+    full = ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r)
+    img_rows_all = full - w.n_text * (w.n_text + w.gridH * w.gridW)
+    # image-query pairs of rows y0..y1-1: count by difference of two prefix problems is not exact near the cut, so count directly
+    r2 = w.r * w.r
+    offs = [(dy, dx) for dy in range(-w.r + 1, w.r) for dx in range(-w.r + 1, w.r) if dx * dx + dy * dy < r2]
+    dyc = np.bincount(np.array([dy for dy, _ in offs]) + w.r - 1, minlength=2 * w.r - 1)  # offsets per dy, dx unrestricted
+    pairs_img = 0
+    for dy in range(-w.r + 1, w.r):
+        n_y = sum(1 for y in range(y0, y1) if 0 <= y + dy < w.gridH)
+        for ddy, dx in offs:
+            if ddy == dy:
+                pairs_img += n_y * max(0, w.gridW - abs(dx))
+    del dyc, img_rows_all
+    pairs = pairs_img + (y1 - y0) * w.gridW * w.n_text + w.n_text * (w.n_text + (y1 - y0) * w.gridW)
+    useful = 4.0 * pairs * w.head_dim * BH
+    ctx.destroy()
+    print(json.dumps({
+        "metric": "local-attn useful TFLOP/s (4*sumM*d), one band of a patch-parallel run", "value": useful / (ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "strong", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text, "band_rows": [y0, y1],
+                   "halo_rows": [ht, hb], "gridW": w.gridW, "r": w.r, "n_bands": args.bands, "pairs_per_head": int(pairs),
+                   "text_merge": "average (Eq. 7) over %d partials" % args.bands},
+    }))
 
 
 if __name__ == "__main__":

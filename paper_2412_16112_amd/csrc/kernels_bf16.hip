@@ -451,10 +451,6 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         const __bf16* qrow = Qh + (long long)q_token * D + 8 * hh;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
-        // pin the fragments in registers now: otherwise the wait for these loads lands inside the key loop,
-        // where it would also drain the tile prefetches
-#pragma unroll
-        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
     }
 
     const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
@@ -629,6 +625,10 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             issue_stage(0, 0);
             pf_tile = stage_len(0);
         }
+        // The Q fragments are waited for here, once, with the first tiles already on their way: otherwise the
+        // wait lands inside the key loop, where it would also drain the tile prefetches.
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
         int buf = 0;
         if (CAREFUL) {
             for (int t = 0; t < n_tiles;) {
@@ -729,6 +729,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     if (s_redo != 0) {
         __syncthreads();  // every wave has read the flag and left the ring buffers
         run_pass(std::true_type{});
+        __syncthreads();  // the epilogue reuses the stage buffers
     }
 
     const float m_run = ws.m_run;
@@ -753,18 +754,31 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             }
         }
     } else {
-        if (q_valid) {
-            const float inv = 1.0f / l_tot;
-            __bf16* orow = (__bf16*)p.O + head_off + (long long)q_token * D;
+        // The wave's 32 x 128 output tile is turned round in LDS (the stage buffers are idle by now: every wave
+        // has passed the barrier above) so that it leaves as whole 256-byte rows: a lane owns a query, and
+        // storing from that layout would scatter 8-byte pieces over 32 rows per instruction.
+        constexpr int OROW = ROW_BYTES + 16;  // padded row pitch in LDS
+        unsigned char* const wbase = smem + wave * (32 * OROW);
+        const float inv = 1.0f / l_tot;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 v;
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 v;
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) v[t] = (__bf16)(oacc[db][4 * g + t] * inv);
-                    *(bf16x4*)(orow + 32 * db + 8 * g + 4 * hh) = v;
-                }
+                for (int t = 0; t < 4; ++t) v[t] = (__bf16)(oacc[db][4 * g + t] * inv);
+                *(bf16x4*)(wbase + qi * OROW + (32 * db + 8 * g + 4 * hh) * 2) = v;
+            }
+        // 16 lanes per row, 4 rows per store instruction
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + (lane >> 4);  // query slot of the patch
+            const int oy = wy0 + (row >> 3), ox = wx0 + (row & 7);
+            const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane & 15) * 16);
+            if (oy < p.gridH && ox < p.gridW && oy >= p.own_y0 && oy < p.own_y1) {
+                __bf16* orow = (__bf16*)p.O + head_off + ((long long)p.n_text + (long long)oy * p.gridW + ox) * D;
+                *(f32x4*)(orow + (lane & 15) * 8) = chunk;
+            }
         }
     }
 }
