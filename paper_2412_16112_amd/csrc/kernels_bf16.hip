@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "block_class.h"
 #include "clear_internal.h"
@@ -89,10 +90,29 @@ struct WaveState {
     float c;         // log2(e) / sqrt(head_dim)
 };
 
+// Per-lane LDS read offsets inside a staged tile.  All operand addresses of a tile derive from two
+// offsets by XOR with small constants and by adding multiples of 4 KB (ds_read immediates):
+//   K operand, block blk, contraction step ks:  ((tile + k0) ^ (ks << 5)) + blk * 8192
+//   V operand, block blk, step s2, slice db:    ((tile + TILE_BYTES + v0 [^ V_HI]) ^ (db << 6)) + blk * 8192 + s2 * 4096
+// (tile addresses are multiples of 1 KB, so the XORs stay inside the offsets' own bits).
 struct LaneOffsets {
-    unsigned k[8];     // K operand reads, one per contraction step
-    unsigned v[4][2];  // V transpose reads, per 32-channel slice and per half of the 16-key contraction step
+    unsigned k0;  // row qi, logical chunk hh:  qi * 256 + ((hh ^ swz(qi)) << 4)
+    unsigned v0;  // transpose read, slice 0, first half of the 16-key step
 };
+constexpr unsigned V_HI = (1u << 5) | (1u << 11);  // second half of the step: key rows + 8 (and their swizzle)
+
+// Lane addresses of one staged tile (LDS byte addresses).
+struct TileAddr {
+    unsigned kb, vb0, vb1;
+};
+__device__ __forceinline__ TileAddr tile_addr(unsigned tile_lds, const LaneOffsets& lo)
+{
+    TileAddr ta;
+    ta.kb = tile_lds + lo.k0;
+    ta.vb0 = tile_lds + TILE_BYTES + lo.v0;
+    ta.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
+    return ta;
+}
 
 enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2, kMaskTable = 3 };
 
@@ -167,48 +187,57 @@ __device__ __forceinline__ float max_block(const f32x16& s)
 // Classes (LLVM AMDGPU sched_group_barrier masks): 0x2 VALU, 0x8 MFMA, 0x100 LDS read.
 #define SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier((mask), (n), 0)
 
-__device__ __forceinline__ bf16x8 read_v_operand(const unsigned char* vb, int s2, unsigned off_lo, unsigned off_hi)
+typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+__device__ __forceinline__ bf16x8 read_k_operand(const TileAddr& ta, int blk, int ks)
 {
-    const short4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + off_lo));
-    const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(vb + 16 * s2 * ROW_BYTES + off_hi));
+    return *(lds_bf16x8_ptr)(size_t)((ta.kb ^ (unsigned)(ks << 5)) + (unsigned)(blk * 32 * ROW_BYTES));
+}
+
+// V^T fragment for the contraction over key slots 16 s2 + 4 hh + {0..3} and 16 s2 + 8 + 4 hh + {0..3} of
+// block blk, channels 32 db .. 32 db + 31: two 16-bit transpose reads.
+__device__ __forceinline__ bf16x8 read_v_operand(const TileAddr& ta, int blk, int s2, int db)
+{
+    const unsigned imm = (unsigned)(blk * 32 * ROW_BYTES + s2 * 16 * ROW_BYTES);
+    const short4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(size_t)((ta.vb0 ^ (unsigned)(db << 6)) + imm));
+    const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(size_t)((ta.vb1 ^ (unsigned)(db << 6)) + imm));
     union { struct { short4v lo, hi; } h; bf16x8 v; } u;
     u.h.lo = lo4;
     u.h.hi = hi4;
     return u.v;
 }
 
-__device__ __forceinline__ f32x16 qk_block(const unsigned char* kblk, const LaneOffsets& lo, const bf16x8 (&qf)[8])
+__device__ __forceinline__ f32x16 qk_block(const TileAddr& ta, int blk, const bf16x8 (&qf)[8])
 {
     f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *(const bf16x8*)(kblk + lo.k[ks]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
-    }
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(ta, blk, ks), qf[ks], s, 0, 0, 0);
     return s;
 }
 
 // O^T += V_blk^T P^T for one 32-key block.  The contraction step s2 pairs P registers 8*s2 .. 8*s2+7
 // with key slots 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}.
-__device__ __forceinline__ void pv_block(f32x16 (&oacc)[4], const unsigned char* vblk, const LaneOffsets& lo, const bf16x8 (&pf)[2])
+__device__ __forceinline__ void pv_block(f32x16 (&oacc)[4], const TileAddr& ta, int blk, const bf16x8 (&pf)[2])
 {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(vblk, s2, lo.v[db][0], lo.v[db][1]), pf[s2], oacc[db], 0, 0, 0);
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db), pf[s2], oacc[db], 0, 0, 0);
 }
 
 // Careful pass, one staged tile: block by block, exact running maximum, O and the denominator rescaled
 // at every block (Eq. 1 as a textbook online softmax).  Slow; only runs when the fast pass gave up.
-__device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo, const unsigned char* tileK,
+__device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo, unsigned tile_lds,
                                               int cls0, int cls1, bool linear, const MaskArgs& ma)
 {
+    const TileAddr ta = tile_addr(tile_lds, lo);
 #pragma unroll 1
     for (int kb = 0; kb < 2; ++kb) {
         const int cls = kb ? cls1 : cls0;
         if (cls == kBlockSkip) continue;
-        f32x16 s = qk_block(tileK + kb * 32 * ROW_BYTES, lo, qf);
+        f32x16 s = qk_block(ta, kb, qf);
         if (cls == kBlockPartial) {
             if (linear)
                 apply_mask<kMaskLinear>(s, kb, ma);
@@ -225,7 +254,7 @@ __device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[
         ws.m_run = m_new;
         bf16x8 pf[2];
         ws.l_run += exp_block(s, ws.c, m_new * ws.c, pf);
-        pv_block(ws.oacc, tileK + TILE_BYTES + kb * 32 * ROW_BYTES, lo, pf);
+        pv_block(ws.oacc, ta, kb, pf);
     }
 }
 
@@ -241,9 +270,41 @@ __device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
 // Pins the instruction order: nothing is scheduled across this point.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-__device__ __forceinline__ bf16x8 read_k_operand(const unsigned char* kblk, unsigned off)
+// This wave's share of the staging loads of one tile: 2 of the tile's 16 row groups (4 token rows = 1 KB
+// each), for K and for V.  Load k covers row group k / 2, K for even k and V for odd k.
+constexpr int kRowGroupsPerWave = 2;
+constexpr int kTileLoads = 2 * kRowGroupsPerWave;
+struct TileLoads {
+    const void* ksrc;                  // the head's K and V arrays
+    const void* vsrc;
+    unsigned voff[kRowGroupsPerWave];  // per lane: byte offset of its 16-byte chunk in the arrays
+    unsigned lds[kRowGroupsPerWave];   // LDS address of the row group in the tile's K half (V: + TILE_BYTES)
+};
+
+__device__ __forceinline__ void issue_tile_load(const TileLoads& tl, int k)
 {
-    return *(const bf16x8*)(kblk + off);
+    load_to_lds_16B((k & 1) ? tl.vsrc : tl.ksrc, tl.voff[k >> 1], tl.lds[k >> 1] + ((k & 1) ? TILE_BYTES : 0));
+}
+
+__device__ __forceinline__ void issue_tile_loads(const TileLoads& tl)
+{
+    static_assert(kTileLoads == 4, "written out: a loop around inline asm is not unrolled");
+    issue_tile_load(tl, 0);
+    issue_tile_load(tl, 1);
+    issue_tile_load(tl, 2);
+    issue_tile_load(tl, 3);
+}
+
+// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}), in order.
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 // Fast pass, one staged tile.  The reference maximum of a query never moves once set, so O is only
@@ -260,24 +321,27 @@ __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char* kblk, unsi
 // scores become -inf, its P zero), which keeps one code shape for every tile of a loop.
 // ADOPT = true while some query of the wave still has no reference maximum (the first tiles): the block
 // maxima are formed and adopted.  ADOPT = false afterwards: no maximum is needed at all.
-template <int MASK, bool ADOPT>
+// RIDE = true: the wave's staging loads for one tile of the next stage (tl) are issued from inside the
+// pipeline, one every other slot from slot 1 on, instead of in a burst right after the barrier, when every
+// wave of the workgroup would be issuing loads and no matrix instruction.  No branch inside the pipeline:
+// all four always go out.
+template <int MASK, bool ADOPT, bool RIDE>
 __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo,
-                                           const unsigned char* tileK, const MaskArgs& ma)
+                                           unsigned tile_lds, const MaskArgs& ma, const TileLoads& tl)
 {
     constexpr int kb0 = 0;
     constexpr bool has1 = true;
-    const unsigned char* const kbase = tileK;
-    const unsigned char* const vbase = kbase + TILE_BYTES;
+    const TileAddr ta = tile_addr(tile_lds, lo);
     const float c = ws.c;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 pf0[2], pf1[2];
     float sum = 0.f;
 
     // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
-    auto k_operand = [&](int slot) { return read_k_operand(kbase + (slot >> 3) * 32 * ROW_BYTES, lo.k[slot & 7]); };
+    auto k_operand = [&](int slot) { return read_k_operand(ta, slot >> 3, slot & 7); };
     auto v_operand = [&](int slot) {
-        const int i = slot - 16, blk = i >> 3, s2 = (i >> 2) & 1, db = i & 3;
-        return read_v_operand(vbase + blk * 32 * ROW_BYTES, s2, lo.v[db][0], lo.v[db][1]);
+        const int i = slot - 16;
+        return read_v_operand(ta, i >> 3, (i >> 2) & 1, i & 3);
     };
     auto block1_slot = [](int slot) { return (slot >= 8 && slot < 16) || slot >= 24; };
     // operands are read PD slots ahead into a ring of PD + 2 (the extra entry keeps a read from landing on
@@ -296,8 +360,8 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
 #pragma unroll
         for (int r = 0; r < 16; ++r) mw[r] = ma.row[kb0 & 1][r];
     }
-#pragma unroll
-    for (int slot = 0; slot < 32; ++slot) {
+    auto run_slot = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_tag)::value;
         // prefetch the operand of slot + PD
         if (slot + PD < 32 && (!block1_slot(slot + PD) || has1)) {
             if (slot + PD < 16)
@@ -305,6 +369,8 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
             else
                 op[(slot + PD) % RING] = v_operand(slot + PD);
         }
+        // a staging load for the next stage riding along (odd slots at the start)
+        if (RIDE && (slot & 1) && (slot >> 1) < kTileLoads) issue_tile_load(tl, slot >> 1);
         // matrix instruction of this slot
         if (slot < 8)
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], qf[slot], s0, 0, 0, 0);
@@ -379,7 +445,8 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
             }
         }
         SCHED_FENCE();
-    }
+    };
+    static_for<32>(run_slot);  // (not a loop: one that contains inline asm is not unrolled)
     ws.l_run += sum;
 }
 
@@ -387,7 +454,7 @@ template <int NWY, int NWX, bool TEXTQ>
 __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
 {
     constexpr int NW = NWY * NWX;
-    constexpr int NI = 16 / NW;       // 1 KB load instructions per wave per tile, for K and for V each
+    constexpr int NI = kRowGroupsPerWave;  // 1 KB load instructions per wave per tile, for K and for V each
     static_assert(NI * NW == 16, "64 rows = 16 instructions of 4 rows");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][K tile | V tile]
@@ -518,6 +585,31 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             load_to_lds_16B(Vh, voff, lds_tile + TILE_BYTES + ii * 1024);
         }
     };
+    // the same loads, not issued but written down (they ride in the compute pipeline of another tile)
+    auto plan_tile = [&](int i, unsigned lds_tile) {
+        TileLoads tl;
+        tl.ksrc = Kh;
+        tl.vsrc = Vh;
+        int a, b;
+        tile_origin(i, a, b);
+#pragma unroll
+        for (int n = 0; n < NI; ++n) {
+            const int ii = wave * NI + n;
+            const int row = 4 * ii + (lane >> 4);
+            int token;
+            if (b < 0) {
+                token = imin(a + row, lin_limit - 1);
+                if (TEXTQ && token >= p.vkeys_text) token += p.vshift;
+            } else {
+                const int ky = imin(a + (row >> 3), p.gridH - 1);
+                const int kx = imin(b + (row & 7), p.gridW - 1);
+                token = p.n_text + ky * p.gridW + kx;
+            }
+            tl.voff[n] = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
+            tl.lds[n] = lds_tile + ii * 1024;
+        }
+        return tl;
+    };
     auto issue_stage = [&](int t, int buf) {  // the stage that starts at tile t goes to stage buffer buf
         const int len = stage_len(t);
 #pragma unroll
@@ -529,45 +621,41 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     WaveState ws;
     ws.c = p.scale_log2e;
 
-    // ---- per-lane LDS read offsets inside a 32-key block (block and buffer offsets are added later)
-    // K operand: row qi, logical chunk 2 ks + hh
+    // ---- per-lane LDS read offsets inside a staged tile
     LaneOffsets lo;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) lo.k[ks] = (unsigned)(qi * ROW_BYTES + (((2 * ks + hh) ^ swz(qi)) << 4));
-    // V operand (transpose load): within each group of 16 lanes, lane j addresses key row j/4 and
-    // channels 4*(j%4)..+3 of the group's 16-channel slice; it receives channel (lane % 16) for 4 rows.
-    // Rows of the first load: 4 hh + j/4 (+ 16 s2); of the second: + 8.
+    // K operand: key row qi of the block, logical chunk 2 ks + hh (16 bytes = 8 channels)
+    lo.k0 = (unsigned)(qi * ROW_BYTES + ((hh ^ swz(qi)) << 4));
+    // V operand (transpose read): within each group of 16 lanes, lane j addresses key row j / 4 and channels
+    // 4 (j % 4) .. + 3 of the group's 16-channel slice; it receives channel lane % 16 for 4 rows.  Rows of
+    // the first read: 4 hh + j / 4 (+ 16 s2 + 32 blk), of the second: + 8.
     {
         const int j = lane & 15, g2 = (lane >> 4) & 1;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int hi = 0; hi < 2; ++hi) {
-                const int row = 4 * hh + (j >> 2) + 8 * hi;  // swz(row + 16 s2 + 32 kb) == swz(row)
-                const int chunk = 4 * db + 2 * g2 + ((j & 3) >> 1);
-                lo.v[db][hi] = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
-            }
+        const int row = 4 * hh + (j >> 2);
+        const int chunk = 2 * g2 + ((j & 3) >> 1);
+        lo.v0 = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
     }
 
     // Stage hand-over: this wave's loads of the stage about to be computed have landed; after the barrier
     // so have everyone's, and every wave has left the other buffer, which is refilled with the next stage.
     int pf_tile = 0;  // first tile of the next stage to load
-    auto begin_stage = [&](int buf) {
+    auto stage_sync = [&]() {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+    };
+    auto begin_stage = [&](int buf) {
+        stage_sync();
         if (pf_tile < n_tiles) {
             issue_stage(pf_tile, buf ^ 1);
             pf_tile += stage_len(pf_tile);
         }
     };
-
     // Classifies the two key blocks of tile t against this wave's query patch and gathers what the
     // element masks need.
     struct TileInfo {
         int cls0, cls1;
         bool linear;
-        const unsigned char* tileK;
+        unsigned tile_lds;  // LDS address of the staged tile (K half, then V half)
         MaskArgs ma;
     };
     auto tile_info = [&](int t, int buf, int j) -> TileInfo {
@@ -587,7 +675,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH,
                                            p.gridW, p.r2);
         }
-        si.tileK = smem + buf * STAGE_BYTES + j * (2 * TILE_BYTES);
+        si.tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
         si.ma.hh = hh;
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
@@ -608,6 +696,28 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         return si;
     };
 
+    // Lean stage whose tiles carry the next stage's loads: tile j of this stage issues, from inside its
+    // pipeline, this wave's loads for slot j of the next stage (or at once, if the wave skips the tile).
+    // Where the next stage has no slot j the loads fetch a valid tile into a slot nothing reads.
+    auto ride_stage = [&](auto mask_tag, int t, int len, int buf) {
+        constexpr int MASK = decltype(mask_tag)::value;
+        stage_sync();
+        const int nx = pf_tile;
+        const int nx_len = pf_tile < n_tiles ? stage_len(pf_tile) : 0;
+        pf_tile += nx_len;
+#pragma unroll 1
+        for (int j = 0; j < len; ++j) {
+            const TileInfo si = tile_info(t + j, buf, j);
+            const TileLoads tl = plan_tile(imin(nx + j, n_tiles - 1), lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
+            if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip)
+                fast_stage<MASK, false, true>(ws, qf, lo, si.tile_lds, si.ma, tl);
+            else
+                issue_tile_loads(tl);
+        }
+#pragma unroll 1
+        for (int j = len; j < nx_len; ++j) issue_tile(nx + j, lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
+    };
+
     // One pass over the stage list.  CAREFUL = false: fast pass (fixed reference maximum); returns the
     // lanes that ran out of headroom.  CAREFUL = true: exact online softmax, slow.
     auto run_pass = [&](auto careful_tag) -> unsigned long long {
@@ -619,6 +729,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         ws.m_run = M_INIT;
         ws.l_run = 0.f;
         unsigned long long bad = 0;
+        const TileLoads no_loads = {};
         // prologue: the first stage is in flight
         pf_tile = 0;
         if (n_tiles > 0) {
@@ -636,7 +747,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 const int len = stage_len(t);
                 for (int j = 0; j < len; ++j) {
                     const TileInfo si = tile_info(t + j, buf, j);
-                    careful_stage(ws, qf, lo, si.tileK, si.cls0, si.cls1, si.linear, si.ma);
+                    careful_stage(ws, qf, lo, si.tile_lds, si.cls0, si.cls1, si.linear, si.ma);
                 }
                 t += len;
                 buf ^= 1;
@@ -655,16 +766,22 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                 for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
                     const TileInfo si = tile_info(t + j, buf, j);
-                    if (wave_has_queries) fast_stage<kMaskNone, true>(ws, qf, lo, si.tileK, si.ma);
+                    if (wave_has_queries) fast_stage<kMaskNone, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                 }
                 adopting = wave_has_queries && still_adopting();
             }
-            for (; t < cb1; t += TPS, buf ^= 1) {
-                begin_stage(buf);
+            // (the long key walk of the text-query kernel gains from loads that ride in the pipeline; the
+            // image-query kernel, with its short lists and skipped tiles, is faster with the plain burst)
+            if (TEXTQ) {
+                for (; t < cb1; t += TPS, buf ^= 1) ride_stage(std::integral_constant<int, kMaskNone>{}, t, imin(TPS, cb1 - t), buf);
+            } else {
+                for (; t < cb1; t += TPS, buf ^= 1) {
+                    begin_stage(buf);
 #pragma unroll 1
-                for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
-                    const TileInfo si = tile_info(t + j, buf, j);
-                    if (wave_has_queries) fast_stage<kMaskNone, false>(ws, qf, lo, si.tileK, si.ma);
+                    for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
+                        const TileInfo si = tile_info(t + j, buf, j);
+                        if (wave_has_queries) fast_stage<kMaskNone, false, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    }
                 }
             }
             t = cb1;
@@ -673,7 +790,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 begin_stage(buf);
                 const TileInfo si = tile_info(t, buf, 0);
                 if (si.cls0 != kBlockSkip) {
-                    fast_stage<kMaskLinear, true>(ws, qf, lo, si.tileK, si.ma);
+                    fast_stage<kMaskLinear, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     adopting = still_adopting();
                 }
             }
@@ -685,7 +802,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true>(ws, qf, lo, si.tileK, si.ma);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
@@ -694,7 +811,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false>(ws, qf, lo, si.tileK, si.ma);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                 }
                 t = cb3;
@@ -704,7 +821,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb4 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true>(ws, qf, lo, si.tileK, si.ma);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                 }
             }
@@ -716,6 +833,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 for (int r = 0; r < 16; ++r) chk += __builtin_fabsf(ws.oacc[db][r]);
             bad = __builtin_amdgcn_ballot_w64(!(chk < FAST_SUM_LIMIT));
         }
+        wait_vmcnt<0>();  // loads into slots that nothing reads must not outlive the pass (or the workgroup's LDS)
         return bad;
     };
 
