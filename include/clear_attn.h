@@ -76,9 +76,9 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
                        void* stream);
 
 /*
- * Timing aid for benchmarks: same arguments and checks as clear_attn_forward, but runs the three
- * kernels of a forward pass one after the other, each `reps` times back to back between two HIP
- * events on `stream`, and SYNCHRONISES.  phase_ms[0..2] receive the average milliseconds per launch
+ * Timing aid for benchmarks: same arguments and checks as clear_attn_forward, but runs `reps`
+ * (1..256) forward passes back to back on `stream` with a HIP event between the kernels, and
+ * SYNCHRONISES.  phase_ms[0..2] receive the average milliseconds per launch, inside that sequence,
  * of (0) the image-query kernel (Eq. 3's windowed rows), (1) the text-query kernel (dense rows,
  * split along the keys) and (2) the merge of those splits.  O holds a valid result afterwards.
  */

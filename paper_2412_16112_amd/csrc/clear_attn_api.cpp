@@ -9,6 +9,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "clear_internal.h"
 
@@ -402,24 +403,34 @@ int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K
     FwdParams p;
     int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
     if (rc != CLEAR_OK) return rc;
-    if (!phase_ms || reps < 1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "phase_ms must be non-NULL and reps >= 1");
+    if (!phase_ms || reps < 1 || reps > 256) return fail(ctx, CLEAR_ERR_INVALID_ARG, "phase_ms must be non-NULL and 1 <= reps <= 256");
+    // The three kernels are timed inside the sequence they run in (image, text, merge, image, ...): timed
+    // one kind at a time they would each run at the clock that kind settles at, not at the one the mix gets.
     hipStream_t st = (hipStream_t)stream;
-    hipEvent_t ev[2] = {nullptr, nullptr};
-    hipError_t e = hipEventCreate(&ev[0]);
-    if (e == hipSuccess) e = hipEventCreate(&ev[1]);
-    for (int phase = 0; phase < 3 && e == hipSuccess; ++phase) {
-        phase_ms[phase] = 0.f;
-        if (phase != kPhaseImage && n_text == 0) continue;
-        e = hipEventRecord(ev[0], st);
-        for (int i = 0; i < reps && e == hipSuccess; ++i) e = launch(ctx, p, st, phase);
-        if (e == hipSuccess) e = hipEventRecord(ev[1], st);
-        if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
-        float ms = 0.f;
-        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
-        phase_ms[phase] = ms / (float)reps;
+    std::vector<hipEvent_t> ev((size_t)reps * 4, nullptr);
+    hipError_t e = hipSuccess;
+    for (size_t i = 0; i < ev.size() && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+    const bool text = n_text > 0;
+    for (int i = 0; i < reps && e == hipSuccess; ++i) {
+        hipEvent_t* v = &ev[(size_t)i * 4];
+        e = hipEventRecord(v[0], st);
+        if (e == hipSuccess) e = launch(ctx, p, st, kPhaseImage);
+        if (e == hipSuccess) e = hipEventRecord(v[1], st);
+        if (e == hipSuccess && text) e = launch(ctx, p, st, kPhaseTextQuery);
+        if (e == hipSuccess) e = hipEventRecord(v[2], st);
+        if (e == hipSuccess && text) e = launch(ctx, p, st, kPhaseTextMerge);
+        if (e == hipSuccess) e = hipEventRecord(v[3], st);
     }
-    if (ev[0]) (void)hipEventDestroy(ev[0]);
-    if (ev[1]) (void)hipEventDestroy(ev[1]);
+    if (e == hipSuccess) e = hipEventSynchronize(ev.back());
+    phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
+    for (int i = 0; i < reps && e == hipSuccess; ++i)
+        for (int ph = 0; ph < 3 && e == hipSuccess; ++ph) {
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, ev[(size_t)i * 4 + ph], ev[(size_t)i * 4 + ph + 1]);
+            phase_ms[ph] += ms / (float)reps;
+        }
+    for (hipEvent_t x : ev)
+        if (x) (void)hipEventDestroy(x);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("profile run failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }
