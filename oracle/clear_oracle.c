@@ -127,6 +127,137 @@ int oracle_attention_rows(const double* Q, const double* K, const double* V, con
 }
 
 /*
+ * Backward pass of the same operator (needed to train the attention layers, Sec. 3.3; the gradients of
+ * Eq. 1 under the mask of Eq. 3 are not printed in the paper: they follow from differentiating it).
+ * With s_ij = q_i.k_j / sqrt(d), p_ij = softmax_j(s_ij) over the keys with M_ij = 1, O_i = sum_j p_ij v_j
+ * and an upstream gradient dO:
+ *     dV_j = sum_i p_ij dO_i
+ *     dp_ij = dO_i . v_j,   delta_i = sum_j p_ij dp_ij  (= dO_i . O_i),   ds_ij = p_ij (dp_ij - delta_i)
+ *     dQ_i = sum_j ds_ij k_j / sqrt(d),      dK_j = sum_i ds_ij q_i / sqrt(d)
+ * Everything below is these sums written out in fp64, one (i, j) pair at a time, over ALL N columns
+ * (or rows) with the mask tested per pair.
+ *
+ * Per-row statistics of the forward pass for the given rows: m (max logit), l (sum of exp(s - m)) and
+ * delta (as defined above).  Returns 0 or -1.
+ */
+int oracle_row_stats(const double* Q, const double* K, const double* V, const double* dO, const int64_t* rows,
+                     int64_t n_rows, int n_text, int gridH, int gridW, int d, int r, double* m_out,
+                     double* l_out, double* delta_out)
+{
+    if (!Q || !K || !V || !dO || !rows || !m_out || !l_out || !delta_out || d < 1 || r < 1) return -1;
+    const int64_t N = (int64_t)n_text + (int64_t)gridH * gridW;
+    const double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const int64_t i = rows[t];
+        const double* q = Q + i * d;
+        const double* g = dO + i * d;
+        double m = -INFINITY;
+        for (int64_t j = 0; j < N; ++j) {
+            if (!oracle_mask(i, j, n_text, gridH, gridW, r)) continue;
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += q[c] * K[j * d + c];
+            if (acc * scale > m) m = acc * scale;
+        }
+        double l = 0.0, num = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            if (!oracle_mask(i, j, n_text, gridH, gridW, r)) continue;
+            double acc = 0.0, dp = 0.0;
+            for (int c = 0; c < d; ++c) { acc += q[c] * K[j * d + c]; dp += g[c] * V[j * d + c]; }
+            const double e = exp(acc * scale - m);
+            l += e;
+            num += e * dp;
+        }
+        m_out[t] = m;
+        l_out[t] = l;
+        delta_out[t] = num / l;
+    }
+    return 0;
+}
+
+/* dQ for the given query rows: [n_rows][d]. */
+int oracle_backward_dq_rows(const double* Q, const double* K, const double* V, const double* dO, const int64_t* rows,
+                            int64_t n_rows, int n_text, int gridH, int gridW, int d, int r, double* dQ)
+{
+    if (!dQ) return -1;
+    const int64_t N = (int64_t)n_text + (int64_t)gridH * gridW;
+    const double scale = 1.0 / sqrt((double)d);
+    double* m = (double*)malloc(sizeof(double) * (size_t)(3 * n_rows + 1));
+    if (!m) return -1;
+    double *l = m + n_rows, *delta = l + n_rows;
+    if (oracle_row_stats(Q, K, V, dO, rows, n_rows, n_text, gridH, gridW, d, r, m, l, delta) != 0) { free(m); return -1; }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const int64_t i = rows[t];
+        const double* q = Q + i * d;
+        const double* g = dO + i * d;
+        double* out = dQ + t * d;
+        for (int c = 0; c < d; ++c) out[c] = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            if (!oracle_mask(i, j, n_text, gridH, gridW, r)) continue;
+            double acc = 0.0, dp = 0.0;
+            for (int c = 0; c < d; ++c) { acc += q[c] * K[j * d + c]; dp += g[c] * V[j * d + c]; }
+            const double p = exp(acc * scale - m[t]) / l[t];
+            const double ds = p * (dp - delta[t]);
+            for (int c = 0; c < d; ++c) out[c] += ds * K[j * d + c] * scale;
+        }
+    }
+    free(m);
+    return 0;
+}
+
+/*
+ * dK and dV for the given key columns: [n_cols][d] each.  Every query row i is visited for every column
+ * (mask tested per pair); the statistics of the rows that attend to at least one of the columns are
+ * computed first.
+ */
+int oracle_backward_dkv_cols(const double* Q, const double* K, const double* V, const double* dO, const int64_t* cols,
+                             int64_t n_cols, int n_text, int gridH, int gridW, int d, int r, double* dK, double* dV)
+{
+    if (!Q || !K || !V || !dO || !cols || !dK || !dV || d < 1 || r < 1) return -1;
+    const int64_t N = (int64_t)n_text + (int64_t)gridH * gridW;
+    const double scale = 1.0 / sqrt((double)d);
+    /* rows that see any of the columns */
+    int64_t* need = (int64_t*)malloc(sizeof(int64_t) * (size_t)(N + 1));
+    int64_t* slot = (int64_t*)malloc(sizeof(int64_t) * (size_t)(N + 1));
+    if (!need || !slot) { free(need); free(slot); return -1; }
+    int64_t n_need = 0;
+    for (int64_t i = 0; i < N; ++i) {
+        int any = 0;
+        for (int64_t t = 0; t < n_cols && !any; ++t) any = oracle_mask(i, cols[t], n_text, gridH, gridW, r);
+        slot[i] = any ? n_need : -1;
+        if (any) need[n_need++] = i;
+    }
+    double* m = (double*)malloc(sizeof(double) * (size_t)(3 * n_need + 1));
+    if (!m) { free(need); free(slot); return -1; }
+    double *l = m + n_need, *delta = l + n_need;
+    int rc = oracle_row_stats(Q, K, V, dO, need, n_need, n_text, gridH, gridW, d, r, m, l, delta);
+    if (rc == 0) {
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t t = 0; t < n_cols; ++t) {
+            const int64_t j = cols[t];
+            double* ok = dK + t * d;
+            double* ov = dV + t * d;
+            for (int c = 0; c < d; ++c) { ok[c] = 0.0; ov[c] = 0.0; }
+            for (int64_t i = 0; i < N; ++i) {
+                if (!oracle_mask(i, j, n_text, gridH, gridW, r)) continue;
+                const int64_t u = slot[i];
+                double acc = 0.0, dp = 0.0;
+                for (int c = 0; c < d; ++c) { acc += Q[i * d + c] * K[j * d + c]; dp += dO[i * d + c] * V[j * d + c]; }
+                const double p = exp(acc * scale - m[u]) / l[u];
+                const double ds = p * (dp - delta[u]);
+                for (int c = 0; c < d; ++c) {
+                    ov[c] += p * dO[i * d + c];
+                    ok[c] += ds * Q[i * d + c] * scale;
+                }
+            }
+        }
+    }
+    free(m); free(need); free(slot);
+    return rc;
+}
+
+/*
  * Reference tile schedule by brute force over the element mask (image tokens only; text keys
  * are attended by every query and are not part of the schedule).
  * Query tiles are qth x qtw patches, key tiles kth x ktw patches, both aligned to the grid

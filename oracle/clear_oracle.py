@@ -36,6 +36,10 @@ def _load():
         lib.oracle_mask.argtypes = [i64, i64, i32, i32, i32, i32]
         lib.oracle_row_count.restype = i64
         lib.oracle_row_count.argtypes = [i64, i32, i32, i32, i32]
+        lib.oracle_backward_dq_rows.restype = i32
+        lib.oracle_backward_dq_rows.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        lib.oracle_backward_dkv_cols.restype = i32
+        lib.oracle_backward_dkv_cols.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp]
         lib.oracle_mask_count.restype = u64
         lib.oracle_mask_count.argtypes = [i32, i32, i32, i32]
         lib.oracle_mask_dense.restype = None
@@ -100,6 +104,43 @@ def attention_rows(Q, K, V, rows, n_text, gridH, gridW, r, return_stats=False):
         if rc != 0:
             raise RuntimeError("oracle_attention_rows failed")
     return (O, m, l, cnt) if return_stats else O
+
+
+def backward_dq_rows(Q, K, V, dO, rows, n_text, gridH, gridW, r):
+    """dQ of the given query rows of one [N, d] slice, for upstream gradient dO [N, d].  fp64 [len(rows), d]."""
+    lib = _load()
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    d = Q.shape[1]
+    out = np.zeros((len(rows), d), dtype=np.float64)
+    rc = lib.oracle_backward_dq_rows(Q.ctypes.data, K.ctypes.data, V.ctypes.data, dO.ctypes.data, rows.ctypes.data, len(rows),
+                                     n_text, gridH, gridW, d, r, out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("oracle_backward_dq_rows failed")
+    return out
+
+
+def backward_dkv_cols(Q, K, V, dO, cols, n_text, gridH, gridW, r):
+    """(dK, dV) of the given key columns of one [N, d] slice.  fp64 [len(cols), d] each."""
+    lib = _load()
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    cols = np.ascontiguousarray(cols, dtype=np.int64)
+    d = Q.shape[1]
+    dK = np.zeros((len(cols), d), dtype=np.float64)
+    dV = np.zeros((len(cols), d), dtype=np.float64)
+    rc = lib.oracle_backward_dkv_cols(Q.ctypes.data, K.ctypes.data, V.ctypes.data, dO.ctypes.data, cols.ctypes.data, len(cols),
+                                      n_text, gridH, gridW, d, r, dK.ctypes.data, dV.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("oracle_backward_dkv_cols failed")
+    return dK, dV
+
+
+def backward(Q, K, V, dO, n_text, gridH, gridW, r):
+    """(dQ, dK, dV) for every token of one [N, d] slice."""
+    N = Q.shape[0]
+    idx = np.arange(N, dtype=np.int64)
+    dK, dV = backward_dkv_cols(Q, K, V, dO, idx, n_text, gridH, gridW, r)
+    return backward_dq_rows(Q, K, V, dO, idx, n_text, gridH, gridW, r), dK, dV
 
 
 def attention(Q, K, V, n_text, gridH, gridW, r):
