@@ -122,6 +122,27 @@ int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_i
  * the matrix pipeline, masked and padding slots included ("executed" work; useful work is sumM). */
 int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head);
 
+/* ---- Training: forward with the softmax statistics, and the backward pass (the attention layers are the
+ * trained parameters of the distillation of Sec. 3.3; the gradients follow from differentiating Eq. 1
+ * under the mask of Eq. 3).  bf16 with head_dim 128 only.
+ *
+ * clear_attn_forward_lse: clear_attn_forward that also writes, for every row, the natural logarithm of its
+ * softmax denominator sum_j exp(q_i.k_j / sqrt(head_dim)) over the attended keys to lse (device, fp32,
+ * [B, H, N], caller-owned). */
+int clear_attn_forward_lse(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, float* lse,
+                           int B, int H, int n_text, int gridH, int gridW, int head_dim, int r, void* stream);
+
+/* Backward pass.  Q, K, V as given to the forward pass, O and lse as it returned them, dO the gradient with
+ * respect to O; writes dQ, dK, dV (device, [B, H, N, head_dim], the tensors' dtype; fp32 accumulation, one
+ * rounding on output).  All tensors 16-byte aligned; dQ, dK, dV must not overlap each other or an input.
+ * Enqueues on stream, never synchronises; allocates only if the context's backward workspace ([B*H][N] floats
+ * plus the split sums of the text rows) has to grow: call clear_attn_reserve_backward beforehand to avoid
+ * that.  Shape arguments as for clear_attn_forward (CLEAR_ERR_MISMATCH otherwise, nothing launched). */
+int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O,
+                        const void* dO, const float* lse, void* dQ, void* dK, void* dV, int B, int H, int n_text,
+                        int gridH, int gridW, int head_dim, int r, void* stream);
+int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH);
+
 /* ---- Row bands: patch-parallel inference, one band of image rows per GPU (multi-GPU section, Eq. 7) ----
  *
  * The gridH_total x gridW feature map is cut into n_bands bands of whole rows.  A band is processed

@@ -16,7 +16,8 @@ CLEAR_TILE_PARTIAL, CLEAR_TILE_FULL = 0, 1
 
 EXPORTS = [
     "clear_attn_create", "clear_attn_reserve", "clear_attn_forward", "clear_attn_forward_profile",
-    "clear_attn_destroy", "clear_attn_forward_band", "clear_attn_band_layout", "clear_attn_merge_text",
+    "clear_attn_destroy", "clear_attn_forward_lse", "clear_attn_backward", "clear_attn_reserve_backward",
+    "clear_attn_forward_band", "clear_attn_band_layout", "clear_attn_merge_text",
     "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
     "clear_attn_measure_mfma_peak", "clear_attn_last_error",
@@ -53,6 +54,9 @@ def lib():
         L.clear_attn_schedule_size.argtypes = [vp, ip, ip, ip, ip, ip, llp]
         L.clear_attn_schedule_copy.argtypes = [vp, vp, vp, vp]
         L.clear_attn_executed_pairs.argtypes = [vp, ullp]
+        L.clear_attn_forward_lse.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_reserve_backward.argtypes = [vp, i]
         L.clear_attn_forward_band.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp, vp, vp]
         L.clear_attn_band_layout.argtypes = [i, i, i, i, ip, ip, ip, ip]
         L.clear_attn_merge_text.argtypes = [i, vp, vp, i, i, i, ctypes.c_longlong, i, i, vp, i, vp]
@@ -142,6 +146,37 @@ class ClearAttn:
         _check(lib().clear_attn_forward(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H,
                                         n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
+
+    def forward_lse(self, Q, K, V, O=None, lse=None, stream=None):
+        """clear_attn_forward_lse: returns (O, lse) with lse fp32 [B, H, N]."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        if O is None:
+            O = torch.empty_like(Q)
+        if lse is None:
+            lse = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        _check(lib().clear_attn_forward_lse(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), lse.data_ptr(), B, H,
+                                            n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
+        return O, lse
+
+    def backward(self, Q, K, V, O, dO, lse, stream=None):
+        """clear_attn_backward: returns (dQ, dK, dV)."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        for t in (K, V, O, dO):
+            if not (t.is_cuda and t.is_contiguous() and t.shape == Q.shape and t.dtype == Q.dtype):
+                raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "K, V, O, dO must be contiguous device tensors shaped and typed like Q")
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        _check(lib().clear_attn_backward(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), lse.data_ptr(),
+                                         dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), B, H, n_text, gridH, gridW, head_dim, r,
+                                         ctypes.c_void_p(s)), self._ctx)
+        return dQ, dK, dV
 
     def forward_band(self, Q, K, V, O, own_y0, own_y1, text_keys, text_o=None, text_lse=None, stream=None):
         """clear_attn_forward_band on the context's (local) grid.  Returns (O, text_o, text_lse)."""

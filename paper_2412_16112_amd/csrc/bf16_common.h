@@ -1,0 +1,216 @@
+// Device-side building blocks shared by the bf16 kernels (forward and backward) for gfx950, head_dim 128:
+// vector types, the LDS layout of a staged 64-token tile and its swizzle, LDS-direct staging loads, MFMA
+// operand reads from a staged tile (row-wise and transposed), the element masks of Eq. 3, and the two
+// 32 x 32 block products every kernel is made of.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "block_class.h"
+#include "clear_internal.h"
+
+namespace clear {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int D = 128;               // head_dim
+constexpr int ROW_BYTES = D * 2;     // one token row of K or V
+constexpr int TILE_KEYS = kKeyTileKeys;
+constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
+#ifndef CLEAR_OPERAND_PREFETCH
+#define CLEAR_OPERAND_PREFETCH 2
+#endif
+#ifndef CLEAR_TILES_PER_STAGE
+#define CLEAR_TILES_PER_STAGE 2
+#endif
+constexpr int TPS = CLEAR_TILES_PER_STAGE;           // key tiles (K + V = 32 KB each) staged per barrier
+constexpr int NBUF = 2;                             // stage buffers: one being computed on, one being filled
+constexpr int STAGE_BYTES = TPS * 2 * TILE_BYTES;
+constexpr float FAST_SUM_LIMIT = 1.0e30f;  // the fast pass is discarded when a query's sums leave [0, 1e30)
+constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)
+
+// LDS layout of a staged tile: 64 rows of 256 B, unpadded (the LDS-direct load writes 1 KB = 4 rows per
+// wave instruction), with the 16-byte chunks of each row permuted: logical chunk c of row k sits in
+// slot c ^ swz(k).  swz is a bijection on 16 consecutive rows (the 32 key rows of a K read spread over
+// all banks) and sends 4 consecutive rows to 4 different 64-byte quads (so does the transposed V read).
+__host__ __device__ constexpr int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+__device__ __forceinline__ float wave_pair_max(float x)
+{
+    // lanes l and l ^ 32 hold the two halves of one query's scores
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float wave_pair_sum(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// One 16-byte-per-lane load from global memory straight into LDS: the wave writes 1 KB starting at
+// lds_addr (wave-uniform), lane i at lds_addr + 16 i; lane i reads gbase + voff.  Counted by vmcnt.
+// Written as asm so that the compiler does not serialise later LDS reads behind it; the kernel waits
+// with explicit s_waitcnt vmcnt before the barrier that publishes the tile.
+__device__ __forceinline__ void load_to_lds_16B(const void* gbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));  // expcnt, lgkmcnt unconstrained
+}
+
+struct WaveState {
+    f32x16 oacc[4];  // O^T tiles: channel 32*db + 8*(reg/4) + 4*hh + reg%4 of this lane's query
+    float m_run;     // running maximum, raw logits (may lag the true maximum by < 2^8 in the exponent)
+    float l_run;     // this lane's share of the denominator
+    float c;         // log2(e) / sqrt(head_dim)
+};
+
+// Per-lane LDS read offsets inside a staged tile.  All operand addresses of a tile derive from two
+// offsets by XOR with small constants and by adding multiples of 4 KB (ds_read immediates):
+//   K operand, block blk, contraction step ks:  ((tile + k0) ^ (ks << 5)) + blk * 8192
+//   V operand, block blk, step s2, slice db:    ((tile + TILE_BYTES + v0 [^ V_HI]) ^ (db << 6)) + blk * 8192 + s2 * 4096
+// (tile addresses are multiples of 1 KB, so the XORs stay inside the offsets' own bits).
+struct LaneOffsets {
+    unsigned k0;  // row qi, logical chunk hh:  qi * 256 + ((hh ^ swz(qi)) << 4)
+    unsigned v0;  // transpose read, slice 0, first half of the 16-key step
+};
+constexpr unsigned V_HI = (1u << 5) | (1u << 11);  // second half of the step: key rows + 8 (and their swizzle)
+
+// Lane addresses of one staged tile (LDS byte addresses).
+struct TileAddr {
+    unsigned kb, vb0, vb1;
+};
+__device__ __forceinline__ TileAddr tile_addr(unsigned tile_lds, const LaneOffsets& lo)
+{
+    TileAddr ta;
+    ta.kb = tile_lds + lo.k0;
+    ta.vb0 = tile_lds + TILE_BYTES + lo.v0;
+    ta.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
+    return ta;
+}
+
+enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2, kMaskTable = 3 };
+
+// Read-only tables (tile lists, lane masks) are addressed through the constant address space so that
+// they are fetched with scalar loads: wave-uniform, and not counted among the vector loads whose
+// completion the tile prefetch waits on.
+typedef const __attribute__((address_space(4))) int* const_int_ptr;
+typedef const __attribute__((address_space(4))) unsigned long long* const_u64_ptr;
+
+struct MaskArgs {
+    int a, b;  // linear: first token of the tile, token limit; image: tile origin (row, col)
+    int hh, qy, qx, gridH, gridW, r2;
+    const_u64_ptr row[2];  // kMaskTable: 16 lane masks per key block (one per score register)
+};
+
+// Sets the scores of inadmissible (query, key) pairs of key block kb to -inf.  Register r of this lane
+// is key slot 8*(r/4) + 4*hh + r%4 of the block (Eq. 3 for image keys; the token limit for linear tiles).
+template <int MASK>
+__device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma)
+{
+    if (MASK == kMaskTable) {
+        // precomputed per relative block offset: bit l of row[r] says whether lane l keeps score register r
+        const_u64_ptr row = ma.row[kb & 1];  // wave-uniform address: the words are read into scalar registers
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_inverse_ballot_w64(row[r]) ? s[r] : -INFINITY;
+    } else if (MASK == kMaskLinear) {
+        const int base = ma.a + 32 * kb + 4 * ma.hh;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (base + 8 * (r >> 2) + (r & 3) >= ma.b) s[r] = -INFINITY;
+    } else if (MASK == kMaskImage) {
+        const int ky0 = ma.a + kKeyBlockH * kb, kx0 = ma.b + 4 * ma.hh;
+        int dx2[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int dx = kx0 + t - ma.qx;
+            dx2[t] = (kx0 + t < ma.gridW) ? dx * dx : 0x7fffffff;  // columns beyond the grid never pass
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int dy = ky0 + g - ma.qy;
+            const int lim = (ky0 + g < ma.gridH) ? ma.r2 - dy * dy : 0;  // dx^2 must stay below lim
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (!(dx2[t] < lim)) s[4 * g + t] = -INFINITY;
+        }
+    }
+}
+
+// p = 2^{(s - m) c} for the 16 scores of one block; returns their sum; packs them as the B operand of P V.
+__device__ __forceinline__ float exp_block(const f32x16& s, float c, float mc, bf16x8 (&pf)[2])
+{
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -mc));
+        sum += pv;
+        pf[r >> 3][r & 7] = (__bf16)pv;
+    }
+    return sum;
+}
+
+__device__ __forceinline__ float max_block(const f32x16& s)
+{
+    float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    return mx;
+}
+
+// Scheduling hints: ask the backend to emit, in this order, `n` instructions of the given class.
+// Classes (LLVM AMDGPU sched_group_barrier masks): 0x2 VALU, 0x8 MFMA, 0x100 LDS read.
+#define SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier((mask), (n), 0)
+
+typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+__device__ __forceinline__ bf16x8 read_k_operand(const TileAddr& ta, int blk, int ks)
+{
+    return *(lds_bf16x8_ptr)(size_t)((ta.kb ^ (unsigned)(ks << 5)) + (unsigned)(blk * 32 * ROW_BYTES));
+}
+
+// V^T fragment for the contraction over key slots 16 s2 + 4 hh + {0..3} and 16 s2 + 8 + 4 hh + {0..3} of
+// block blk, channels 32 db .. 32 db + 31: two 16-bit transpose reads.
+__device__ __forceinline__ bf16x8 read_v_operand(const TileAddr& ta, int blk, int s2, int db)
+{
+    const unsigned imm = (unsigned)(blk * 32 * ROW_BYTES + s2 * 16 * ROW_BYTES);
+    const short4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(size_t)((ta.vb0 ^ (unsigned)(db << 6)) + imm));
+    const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(size_t)((ta.vb1 ^ (unsigned)(db << 6)) + imm));
+    union { struct { short4v lo, hi; } h; bf16x8 v; } u;
+    u.h.lo = lo4;
+    u.h.hi = hi4;
+    return u.v;
+}
+
+__device__ __forceinline__ f32x16 qk_block(const TileAddr& ta, int blk, const bf16x8 (&qf)[8])
+{
+    f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(ta, blk, ks), qf[ks], s, 0, 0, 0);
+    return s;
+}
+
+// O^T += V_blk^T P^T for one 32-key block.  The contraction step s2 pairs P registers 8*s2 .. 8*s2+7
+// with key slots 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}.
+__device__ __forceinline__ void pv_block(f32x16 (&oacc)[4], const TileAddr& ta, int blk, const bf16x8 (&pf)[2])
+{
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db), pf[s2], oacc[db], 0, 0, 0);
+}
+
+}  // namespace
+}  // namespace clear

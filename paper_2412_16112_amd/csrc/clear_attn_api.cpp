@@ -30,6 +30,10 @@ struct clear_attn_ctx {
     int ws_max_splits = 0;  // splits the workspace is sized for
     float* d_ws_o = nullptr;
     float* d_ws_ml = nullptr;
+    // backward workspace, grown on demand
+    int bwd_BH = 0;
+    float* d_bwd_delta = nullptr;  // [B*H][N]
+    float* d_bwd_ws = nullptr;     // [3][B*H][max splits][n_text][head_dim]
     std::string err;
 };
 
@@ -435,6 +439,94 @@ int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K
     return CLEAR_OK;
 }
 
+int clear_attn_forward_lse(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, float* lse, int B, int H,
+                           int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+{
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
+    if (rc != CLEAR_OK) return rc;
+    if (!lse || ((uintptr_t)lse & 3)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "lse must be non-NULL and 4-byte aligned");
+    p.lse = lse;
+    hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    if (BH < 1 || BH > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be in [1, 65535]");
+    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (BH <= ctx->bwd_BH) return CLEAR_OK;
+    if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
+    if (ctx->d_bwd_ws) (void)hipFree(ctx->d_bwd_ws);
+    ctx->d_bwd_delta = ctx->d_bwd_ws = nullptr;
+    ctx->bwd_BH = 0;
+    const long long N = (long long)ctx->n_text + (long long)ctx->gridH * ctx->gridW;
+    hipError_t e = hipMalloc((void**)&ctx->d_bwd_delta, (size_t)BH * N * sizeof(float));
+    if (e == hipSuccess && ctx->n_text > 0)
+        e = hipMalloc((void**)&ctx->d_bwd_ws, (size_t)3 * BH * max_text_splits(N) * ctx->n_text * ctx->head_dim * sizeof(float));
+    if (e != hipSuccess) {
+        if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
+        ctx->d_bwd_delta = nullptr;
+        (void)hipGetLastError();
+        return fail(ctx, e == hipErrorOutOfMemory ? CLEAR_ERR_ALLOC : CLEAR_ERR_HIP, std::string("backward workspace allocation failed: ") + hipGetErrorString(e));
+    }
+    ctx->bwd_BH = BH;
+    return CLEAR_OK;
+}
+
+int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* lse, void* dQ, void* dK, void* dV, int B, int H, int n_text, int gridH, int gridW,
+                        int head_dim, int r, void* stream)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV) return fail(ctx, CLEAR_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)dO | (uintptr_t)dQ | (uintptr_t)dK | (uintptr_t)dV) & 15)
+        return fail(ctx, CLEAR_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+    if ((uintptr_t)lse & 3) return fail(ctx, CLEAR_ERR_INVALID_ARG, "lse must be 4-byte aligned");
+    if (B < 1 || H < 1 || (long long)B * H > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "B, H must be >= 1 and B*H <= 65535");
+    if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
+        return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
+    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    const long long N = (long long)n_text + (long long)gridH * gridW;
+    {
+        // outputs must not overlap inputs or each other
+        const size_t bytes = (size_t)B * H * N * head_dim * 2;
+        const void* all[8] = {dQ, dK, dV, Q, K, V, O, dO};
+        for (int a = 0; a < 3; ++a)
+            for (int b = a + 1; b < 8; ++b) {
+                const uintptr_t a0 = (uintptr_t)all[a], b0 = (uintptr_t)all[b];
+                if (a0 < b0 + bytes && b0 < a0 + bytes) return fail(ctx, CLEAR_ERR_INVALID_ARG, "dQ, dK, dV must not overlap each other or an input");
+            }
+    }
+    const int BH = B * H;
+    int rc = clear_attn_reserve_backward(ctx, BH);
+    if (rc != CLEAR_OK) return rc;
+    const Schedule& s = ctx->sched;
+    BwdParams p;
+    memset(&p, 0, sizeof(p));
+    p.Q = Q; p.K = K; p.V = V; p.dO = dO; p.lse = lse; p.delta = ctx->d_bwd_delta;
+    p.dQ = dQ; p.dK = dK; p.dV = dV;
+    p.B = B; p.H = H; p.n_text = n_text; p.gridH = gridH; p.gridW = gridW; p.r2 = r * r;
+    p.N = N;
+    p.n_q_tiles = s.n_qty * s.n_qtx;
+    p.n_qtx = s.n_qtx;
+    p.row_ptr = ctx->d_row_ptr; p.col_idx = ctx->d_col_idx; p.n_plain = ctx->d_n_plain; p.mask_tbl = ctx->d_mask_tbl;
+    p.mask_ry = ctx->mask_ry; p.mask_rx = ctx->mask_rx;
+    p.scale = (float)(1.0 / std::sqrt((double)head_dim));
+    p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
+    if (n_text > 0) {
+        const int per_block = bf16_text_queries_per_block();
+        p.n_tq_tiles = (n_text + per_block - 1) / per_block;
+        choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
+        p.ws = ctx->d_bwd_ws;
+    }
+    hipError_t e = launch_bf16_d128_backward(p, O, ctx->d_bwd_delta, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("backward launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
 int clear_attn_forward_band(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
                             int n_text, int gridH, int gridW, int head_dim, int r, int own_y0, int own_y1,
                             int text_keys, float* text_o, float* text_lse, void* stream)
@@ -495,6 +587,8 @@ void clear_attn_destroy(clear_attn_ctx* ctx)
     if (ctx->d_mask_tbl) (void)hipFree(ctx->d_mask_tbl);
     if (ctx->d_ws_o) (void)hipFree(ctx->d_ws_o);
     if (ctx->d_ws_ml) (void)hipFree(ctx->d_ws_ml);
+    if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
+    if (ctx->d_bwd_ws) (void)hipFree(ctx->d_bwd_ws);
     delete ctx;
 }
 

@@ -73,6 +73,7 @@ struct FwdParams {
     int vshift;
     float* band_o;    // when set, the text merge writes fp32 softmax outputs [B*H][n_text][head_dim] here ...
     float* band_lse;  // ... and the natural log of the softmax denominators [B*H][n_text] here, not O's text rows
+    float* lse;       // optional [B*H][N]: natural log of every row's softmax denominator sum_j exp(q.k_j / sqrt(d))
 };
 
 // Launchers (kernels_bf16.hip, kernels_f32.hip).  Each returns the first HIP error met.
@@ -83,6 +84,33 @@ hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
 void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl);
 int f32_text_queries_per_block();
+// Backward pass (kernels_bf16_bwd.hip).
+struct BwdParams {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const void* dO;
+    const float* lse;    // [B*H][N] natural log of the softmax denominators (from the forward pass)
+    const float* delta;  // [B*H][N] dO_i . O_i (computed by the launcher into the context's workspace)
+    void* dQ;
+    void* dK;
+    void* dV;
+    int B, H, n_text, gridH, gridW, r2;
+    long long N;
+    int n_q_tiles, n_qtx;
+    const int* row_ptr;
+    const int* col_idx;
+    const int* n_plain;
+    const unsigned long long* mask_tbl;
+    int mask_ry, mask_rx;
+    float scale_log2e;  // log2(e) / sqrt(head_dim)
+    float scale;        // 1 / sqrt(head_dim)
+    // text rows: sums over every token, split along the columns, partial sums added up afterwards
+    int n_tq_tiles, n_splits, split_keys;
+    float* ws;  // [3 (dQ, dK, dV)][B*H][n_splits][n_text][head_dim]
+};
+hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream);
+
 // band_merge.hip: combination of the text-query outputs of several row bands.
 constexpr int kMaxMergeParts = 64;
 struct MergeParts {

@@ -1,0 +1,410 @@
+// Backward pass of the CLEAR local attention for gfx950 (bf16, head_dim 128): dQ, dK, dV of Eq. 1 under the
+// mask of Eq. 3, given dO and the per-row log-sum-exp the forward pass can return.  With
+//   s_ij = q_i.k_j / sqrt(d),  p_ij = exp(s_ij - lse_i) for M_ij = 1 (else 0),  delta_i = dO_i . O_i,
+//   dp_ij = dO_i . v_j,        ds_ij = p_ij (dp_ij - delta_i):
+//   dQ_i = sum_j ds_ij k_j / sqrt(d),   dK_j = sum_i ds_ij q_i / sqrt(d),   dV_j = sum_i p_ij dO_i.
+//
+// One kernel template computes any of the three.  Its "rows" are the tokens whose gradient a workgroup
+// produces (queries for dQ, keys for dK and dV), held one per lane as MFMA B operands like Q in the forward
+// kernel; its "columns" are the tokens summed over, staged in LDS tiles exactly like K and V in the forward
+// kernel, taken from the same tile schedule (the mask is symmetric, so the key tiles a query tile reaches
+// are also the query tiles that reach a key tile at its place):
+//   mode  rows      column tiles (C1 | C2)   S = C1 r1^T   dP = C2 r2^T   X    accumulator += T^T X
+//   dQ    queries   K | V                    K q^T         V dO^T         dS   K^T dS
+//   dK    keys      Q | dO                   Q k^T         dO v^T         dS   Q^T dS
+//   dV    keys      Q | dO                   Q k^T         -              P    dO^T P
+// lse and delta belong to the query: a per-lane scalar for dQ, a per-column vector (staged next to the tile)
+// for dK and dV.  Text rows sum over every token: they are split along the columns into partial sums that a
+// small kernel adds up, like the text-query rows of the forward pass.  Plain block-by-block code (no
+// hand-ordered pipeline): this is the first correct version of the backward pass, not a tuned one.
+#include <hip/hip_runtime.h>
+
+#include "bf16_common.h"
+#include "block_class.h"
+#include "clear_internal.h"
+
+namespace clear {
+namespace {
+
+enum BwdMode : int { kBwdQ = 0, kBwdK = 1, kBwdV = 2 };
+
+constexpr int STATS_BYTES = TILE_KEYS * 2 * 4;                           // per staged tile: lse2 and delta of its 64 columns
+constexpr int BWD_LDS_BYTES = NBUF * STAGE_BYTES + NBUF * TPS * STATS_BYTES;
+
+template <int MODE, bool LINROWS>
+__global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams p)
+{
+    constexpr int NWY = kBf16NWY, NWX = kBf16NWX, NW = NWY * NWX;
+    constexpr int NI = 16 / NW;
+    constexpr bool COLSTAT = MODE != kBwdQ;  // lse / delta indexed by column
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][C1 tile | C2 tile], then the column statistics
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    float* const stats = (float*)(smem + NBUF * STAGE_BYTES);  // [NBUF][TPS][2][64]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qi = lane & 31;
+    const int hh = lane >> 5;
+
+    // ---- workgroup -> (batch*head, row tile[, column split]); XCD-aware like the forward kernel
+    int vid;
+    {
+        const int nblk = gridDim.x, bid = blockIdx.x;
+        const int xcd = bid & 7, idx = bid >> 3;
+        const int q = nblk >> 3, rem = nblk & 7;
+        vid = xcd * q + imin(xcd, rem) + idx;
+    }
+    int bh, rt, split = 0;
+    if (LINROWS) {
+        split = vid % p.n_splits;
+        const int t = vid / p.n_splits;
+        rt = t % p.n_tq_tiles;
+        bh = t / p.n_tq_tiles;
+    } else {
+        rt = vid % p.n_q_tiles;
+        bh = vid / p.n_q_tiles;
+    }
+    const long long head_off = (long long)bh * p.N * D;  // elements
+    const __bf16* const R1 = (const __bf16*)(MODE == kBwdQ ? p.Q : p.K) + head_off;
+    const __bf16* const R2 = (const __bf16*)(MODE == kBwdQ ? p.dO : p.V) + head_off;
+    const unsigned char* const C1 = (const unsigned char*)((const __bf16*)(MODE == kBwdQ ? p.K : p.Q) + head_off);
+    const unsigned char* const C2 = (const unsigned char*)((const __bf16*)(MODE == kBwdQ ? p.V : p.dO) + head_off);
+    const float* const lse = p.lse + (long long)bh * p.N;
+    const float* const delta = p.delta + (long long)bh * p.N;
+
+    // ---- this lane's row
+    int wy0 = 0, wx0 = 0, ry = 0, rx = 0;
+    int r_token;
+    bool r_valid, wave_has_rows;
+    if (LINROWS) {
+        const int r0 = rt * (NW * 32) + wave * 32;
+        r_token = r0 + qi;
+        r_valid = r_token < p.n_text;
+        wave_has_rows = r0 < p.n_text;
+        if (!r_valid) r_token = p.n_text - 1;
+    } else {
+        wy0 = (rt / p.n_qtx) * (NWY * kWaveQH) + (wave / NWX) * kWaveQH;
+        wx0 = (rt % p.n_qtx) * (NWX * kWaveQW) + (wave % NWX) * kWaveQW;
+        ry = wy0 + (qi >> 3);
+        rx = wx0 + (qi & 7);
+        r_valid = ry < p.gridH && rx < p.gridW;
+        wave_has_rows = wy0 < p.gridH && wx0 < p.gridW;
+        r_token = p.n_text + imin(ry, p.gridH - 1) * p.gridW + imin(rx, p.gridW - 1);
+    }
+    // B operands: 8 contraction steps of 16 channels, this lane supplying channels 16 s + 8 hh .. + 7
+    bf16x8 r1f[8], r2f[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        r1f[s] = *(const bf16x8*)(R1 + (long long)r_token * D + 8 * hh + 16 * s);
+        if (MODE != kBwdV) r2f[s] = *(const bf16x8*)(R2 + (long long)r_token * D + 8 * hh + 16 * s);
+    }
+    // lse in units of log2 (the exponentials are 2^x); dQ: this lane's query
+    constexpr float LOG2E = 1.4426950408889634f;
+    float lse2_row = 0.f, delta_row = 0.f;
+    if (!COLSTAT) {
+        lse2_row = lse[r_token] * LOG2E;
+        delta_row = delta[r_token];
+    }
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        asm volatile("" : "+v"(r1f[s]));
+        if (MODE != kBwdV) asm volatile("" : "+v"(r2f[s]));
+    }
+    asm volatile("" : "+v"(lse2_row), "+v"(delta_row));
+
+    const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
+    const const_u64_ptr mask_tbl = (const_u64_ptr)p.mask_tbl;
+
+    // ---- column tile list: tokens [lin_begin, lin_limit) in 64-token tiles, then (image rows) the CSR row:
+    //   [0, cb1) whole linear tiles   [cb1, cb2) the ragged linear tile   [cb2, cb3) image tiles inside the grid
+    //   [cb3, cb4) image tiles cut by the border
+    int n_tiles, n_lin_tiles, csr_begin = 0;
+    int lin_begin = 0, lin_limit = 0;
+    if (LINROWS) {
+        lin_begin = split * p.split_keys;
+        lin_limit = (long long)lin_begin + p.split_keys < p.N ? lin_begin + p.split_keys : (int)p.N;
+        n_lin_tiles = (lin_limit - lin_begin + TILE_KEYS - 1) / TILE_KEYS;
+        n_tiles = n_lin_tiles;
+    } else {
+        lin_limit = p.n_text;
+        n_lin_tiles = (p.n_text + TILE_KEYS - 1) / TILE_KEYS;
+        csr_begin = row_ptr[rt];
+        n_tiles = n_lin_tiles + (row_ptr[rt + 1] - csr_begin);
+    }
+    const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
+    const int cb3 = LINROWS ? n_lin_tiles : (p.mask_tbl ? n_lin_tiles + n_plain[rt] : n_lin_tiles);
+    const int cb4 = n_tiles;
+    auto stage_len = [&](int t) {
+        const int e = t < cb1 ? cb1 : (t < cb2 ? cb2 : (t < cb3 ? cb3 : cb4));
+        return imin(TPS, e - t);
+    };
+    auto tile_origin = [&](int i, int& a, int& b) {  // linear -> (first token, -1); image -> (row, col) of the 8 x 8 tile
+        if (i < n_lin_tiles) {
+            a = lin_begin + i * TILE_KEYS;
+            b = -1;
+        } else {
+            const int packed = col_idx[csr_begin + i - n_lin_tiles];
+            a = packed >> 16;
+            b = packed & 0xffff;
+        }
+    };
+    auto slot_token = [&](int a, int b, int slot) {  // token staged in slot `slot` (0..63) of the tile with origin (a, b)
+        if (b < 0) return imin(a + slot, lin_limit - 1);
+        const int ky = imin(a + (slot >> 3), p.gridH - 1);
+        const int kx = imin(b + (slot & 7), p.gridW - 1);
+        return p.n_text + ky * p.gridW + kx;
+    };
+
+    // ---- staging: LDS-direct loads of the two column tiles (same layout and swizzle as K and V in the
+    // forward kernel), and for dK / dV the statistics of the tile's 64 queries (wave j of the first TPS waves
+    // fetches them for tile j of the stage and writes them to LDS before the next barrier)
+    auto issue_tile = [&](int i, unsigned lds_tile) {
+        int a, b;
+        tile_origin(i, a, b);
+#pragma unroll
+        for (int n = 0; n < NI; ++n) {
+            const int ii = wave * NI + n;
+            const int row = 4 * ii + (lane >> 4);
+            const int token = slot_token(a, b, row);
+            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
+            load_to_lds_16B(C1, voff, lds_tile + ii * 1024);
+            load_to_lds_16B(C2, voff, lds_tile + TILE_BYTES + ii * 1024);
+        }
+    };
+    float st_lse2 = 0.f, st_delta = 0.f;  // in flight: statistics of slot `lane` of tile `wave` of the next stage
+    auto issue_stage = [&](int t, int buf) {
+        const int len = stage_len(t);
+#pragma unroll
+        for (int j = 0; j < TPS; ++j)
+            if (j < len) issue_tile(t + j, lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
+        if (COLSTAT && wave < len) {
+            int a, b;
+            tile_origin(t + wave, a, b);
+            const int token = slot_token(a, b, lane);
+            st_lse2 = lse[token] * LOG2E;
+            st_delta = delta[token];
+        }
+    };
+    auto publish_stats = [&](int buf, int len) {  // called before the barrier that opens stage buffer buf
+        if (COLSTAT && wave < len) {
+            float* dst = stats + ((buf * TPS + wave) * 2) * TILE_KEYS;
+            dst[lane] = st_lse2;
+            dst[TILE_KEYS + lane] = st_delta;
+        }
+    };
+
+    LaneOffsets lo;
+    lo.k0 = (unsigned)(qi * ROW_BYTES + ((hh ^ swz(qi)) << 4));
+    {
+        const int j = lane & 15, g2 = (lane >> 4) & 1;
+        const int row = 4 * hh + (j >> 2);
+        const int chunk = 2 * g2 + ((j & 3) >> 1);
+        lo.v0 = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
+    }
+
+    f32x16 acc[4];  // gradient^T tiles: channel 32 db + 8 (reg / 4) + 4 hh + reg % 4 of this lane's row
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    const float c = p.scale_log2e;
+
+    // One 32-column block of a staged tile.
+    auto do_block = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma, const float* tile_stats) __attribute__((always_inline)) {
+        constexpr int MASK = decltype(mask_tag)::value;
+        TileAddr t1, t2, tt;
+        t1.kb = tile_lds + lo.k0;                                        // C1, row-wise
+        t2.kb = tile_lds + TILE_BYTES + lo.k0;                           // C2, row-wise
+        const unsigned tbase = tile_lds + (MODE == kBwdV ? TILE_BYTES : 0);  // tile read transposed for the accumulation
+        tt.vb0 = tbase + lo.v0;
+        tt.vb1 = tbase + (lo.v0 ^ V_HI);
+        t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = 0;
+        f32x16 s = qk_block(t1, blk, r1f);
+        apply_mask<MASK>(s, blk, ma);
+        bf16x8 xf[2];
+        if (MODE == kBwdV) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float l2 = COLSTAT ? tile_stats[32 * blk + 8 * (r >> 2) + 4 * hh + (r & 3)] : lse2_row;
+                xf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l2));
+            }
+        } else {
+            const f32x16 dp = qk_block(t2, blk, r2f);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int slot = 32 * blk + 8 * (r >> 2) + 4 * hh + (r & 3);
+                const float l2 = COLSTAT ? tile_stats[slot] : lse2_row;
+                const float dl = COLSTAT ? tile_stats[TILE_KEYS + slot] : delta_row;
+                const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l2));
+                xf[r >> 3][r & 7] = (__bf16)(pr * (dp[r] - dl));
+            }
+        }
+        pv_block(acc, tt, blk, xf);
+    };
+
+    int pf_tile = 0;
+    int pend_len = 0;  // tiles of the stage whose statistics are in flight
+    auto begin_stage = [&](int buf) {
+        publish_stats(buf, pend_len);
+        wait_vmcnt<0>();
+        __syncthreads();
+        pend_len = 0;
+        if (pf_tile < n_tiles) {
+            pend_len = stage_len(pf_tile);
+            issue_stage(pf_tile, buf ^ 1);
+            pf_tile += pend_len;
+        }
+    };
+    auto run_tile = [&](auto mask_tag, int t, int buf, int j) __attribute__((always_inline)) {
+        int ta, tb;
+        tile_origin(t, ta, tb);
+        const bool linear = tb < 0;
+        int cls0, cls1;
+        if (!wave_has_rows) {
+            cls0 = cls1 = kBlockSkip;
+        } else if (linear) {
+            cls0 = classify_linear_block(ta, 32, lin_limit);
+            cls1 = classify_linear_block(ta + 32, 32, lin_limit);
+        } else {
+            cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+            cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+        }
+        MaskArgs ma;
+        ma.hh = hh;
+        ma.a = ta;
+        ma.b = linear ? lin_limit : tb;
+        ma.qy = ry; ma.qx = rx; ma.gridH = p.gridH; ma.gridW = p.gridW; ma.r2 = p.r2;
+        ma.row[0] = ma.row[1] = mask_tbl;
+        if (!LINROWS && !linear && p.mask_tbl) {
+            const int ncol = 2 * p.mask_rx + 1;
+            const int ones = (2 * p.mask_ry + 1) * ncol, zeros = ones + 1;
+            const int dbx = (tb - wx0) >> 3, dby = (ta - wy0) >> 2;
+            const int i0 = (cls0 == kBlockPartial) ? (dby + p.mask_ry) * ncol + dbx + p.mask_rx : (cls0 == kBlockFull ? ones : zeros);
+            const int i1 = (cls1 == kBlockPartial) ? (dby + 1 + p.mask_ry) * ncol + dbx + p.mask_rx : (cls1 == kBlockFull ? ones : zeros);
+            ma.row[0] = mask_tbl + 16 * i0;
+            ma.row[1] = mask_tbl + 16 * i1;
+        }
+        const unsigned tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
+        const float* tile_stats = stats + ((buf * TPS + j) * 2) * TILE_KEYS;
+        if (cls0 != kBlockSkip) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
+        if (cls1 != kBlockSkip) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
+    };
+    auto run_category = [&](auto mask_tag, int& t, int end, int& buf) __attribute__((always_inline)) {
+        for (; t < end; t += TPS, buf ^= 1) {
+            begin_stage(buf);
+#pragma unroll 1
+            for (int j = 0; j < imin(TPS, end - t); ++j) run_tile(mask_tag, t + j, buf, j);
+        }
+        t = end;
+    };
+
+    // prologue: the first stage is in flight
+    if (n_tiles > 0) {
+        pend_len = stage_len(0);
+        issue_stage(0, 0);
+        pf_tile = pend_len;
+    }
+    int buf = 0, t = 0;
+    run_category(std::integral_constant<int, kMaskNone>{}, t, cb1, buf);
+    run_category(std::integral_constant<int, kMaskLinear>{}, t, cb2, buf);
+    if (!LINROWS) {
+        run_category(std::integral_constant<int, kMaskTable>{}, t, cb3, buf);
+        run_category(std::integral_constant<int, kMaskImage>{}, t, cb4, buf);
+    }
+
+    // ---- epilogue
+    if (!r_valid) return;
+    const float out_scale = MODE == kBwdV ? 1.0f : p.scale;  // dQ and dK carry the 1 / sqrt(d) of the logits
+    if (LINROWS) {
+        // partial sums of this column split: [mode][bh][split][row][d] fp32
+        float* wo = p.ws + ((((long long)MODE * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v = {acc[db][4 * g] * out_scale, acc[db][4 * g + 1] * out_scale, acc[db][4 * g + 2] * out_scale, acc[db][4 * g + 3] * out_scale};
+                *(f32x4*)(wo + 32 * db + 8 * g + 4 * hh) = v;
+            }
+    } else {
+        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdK ? p.dK : p.dV)) + head_off + (long long)r_token * D;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 v;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = (__bf16)(acc[db][4 * g + u] * out_scale);
+                *(bf16x4*)(orow + 32 * db + 8 * g + 4 * hh) = v;
+            }
+    }
+}
+
+// delta_i = dO_i . O_i for every row: one wave per row, two channels per lane.
+__global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, const __bf16* dO, float* delta, long long rows)
+{
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int lane = threadIdx.x & 63;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const bf16x2 o = *(const bf16x2*)(O + row * D + 2 * lane);
+    const bf16x2 g = *(const bf16x2*)(dO + row * D + 2 * lane);
+    float s = (float)o[0] * (float)g[0] + (float)o[1] * (float)g[1];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) delta[row] = s;
+}
+
+// Adds up the column-split partial sums of the text rows and stores them as bf16: one workgroup per
+// (mode, batch*head, text row), one thread per channel.
+__global__ void __launch_bounds__(D) clear_bwd_reduce_kernel(const BwdParams p)
+{
+    const int ch = threadIdx.x;
+    const long long BHn = (long long)p.B * p.H * p.n_text;
+    const int mode = (int)(blockIdx.x / BHn);
+    const long long row = blockIdx.x % BHn;
+    const int bh = (int)(row / p.n_text), q = (int)(row % p.n_text);
+    float s = 0.f;
+    for (int k = 0; k < p.n_splits; ++k)
+        s += p.ws[((((long long)mode * p.B * p.H + bh) * p.n_splits + k) * p.n_text + q) * D + ch];
+    __bf16* out = (__bf16*)(mode == kBwdQ ? p.dQ : (mode == kBwdK ? p.dK : p.dV));
+    out[((long long)bh * p.N + q) * D + ch] = (__bf16)s;
+}
+
+template <int MODE, bool LINROWS>
+hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
+{
+    auto kern = clear_bwd_bf16_kernel<MODE, LINROWS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(nblk), dim3(512), BWD_LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream)
+{
+    const int BH = p.B * p.H;
+    const long long rows = (long long)BH * p.N;
+    hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_bwd<kBwdQ, false>(p, BH * p.n_q_tiles, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdK, false>(p, BH * p.n_q_tiles, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdV, false>(p, BH * p.n_q_tiles, stream);
+    if (e != hipSuccess || p.n_text == 0) return e;
+    const int nlin = BH * p.n_tq_tiles * p.n_splits;
+    e = launch_bwd<kBwdQ, true>(p, nlin, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdK, true>(p, nlin, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdV, true>(p, nlin, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(clear_bwd_reduce_kernel, dim3((unsigned)(3LL * BH * p.n_text)), dim3(D), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace clear

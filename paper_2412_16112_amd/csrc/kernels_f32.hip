@@ -157,6 +157,7 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
         p.ws_ml[row * 2 + 1] = l;
     } else {
         const float inv = 1.0f / l;
+        if (p.lse) p.lse[(long long)bh * p.N + q_token] = logf(l) + m * p.scale_log2e * 0.6931471805599453f;
         float* orow = (float*)p.O + head_off + q_token * D;
 #pragma unroll
         for (int c4 = 0; c4 < D / 4; ++c4)
@@ -184,6 +185,7 @@ __global__ void __launch_bounds__(D) clear_text_merge_f32_kernel(const FwdParams
         if (ch == 0) p.band_lse[row] = logf(den) + m * p.scale_log2e * 0.6931471805599453f;
     } else {
         ((float*)p.O)[((long long)bh * p.N + q) * D + ch] = num / den;
+        if (p.lse && ch == 0) p.lse[(long long)bh * p.N + q] = logf(den) + m * p.scale_log2e * 0.6931471805599453f;
     }
 }
 

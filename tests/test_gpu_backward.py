@@ -1,0 +1,82 @@
+"""Backward pass through the C ABI against the fp64 oracle (oracle/clear_oracle.c, backward functions)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import clear_oracle as orc
+from paper_2412_16112_amd import clear_attn as ca
+from paper_2412_16112_amd.inputs import make_qkv_shape
+from tests.parity_util import TOL, error_metrics
+
+pytestmark = pytest.mark.gpu
+
+# Gradients are sums of products of bf16-rounded factors (P and dS are rounded to bf16 before the matrix
+# instruction, like P in the forward pass) accumulated in fp32 and rounded to bf16 once: the same error
+# model as the forward output, on values of a different size.  The bar is the forward bar made relative:
+# max-abs error <= 2e-2 of the largest reference magnitude, relative RMS <= 1e-2.
+def check_grad(name, got, ref):
+    max_abs, rel_rms = error_metrics(got, ref)
+    scale = float(np.abs(ref).max())
+    assert np.isfinite(got).all(), name
+    assert max_abs <= TOL["bf16"][0] * max(scale, 1e-30) and rel_rms <= TOL["bf16"][1], (name, max_abs, scale, rel_rms)
+
+
+def run_case(n_text, gridH, gridW, r, H, seed, q_scale=1.0):
+    d = 128
+    Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, "bf16", seed=seed, device="cuda:0", q_scale=q_scale)
+    g = torch.Generator(device="cuda:0").manual_seed(seed + 1000)
+    dO = torch.randn(Q.shape, generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        dQ, dK, dV = ctx.backward(Q, K, V, O, dO, lse)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    return Q, K, V, dO, O, lse, dQ, dK, dV
+
+
+CASES = [
+    # n_text, gridH, gridW, r, H
+    (37, 20, 24, 5, 2),      # ragged text tile, ragged grid tiles
+    (0, 17, 33, 4, 1),       # no text
+    (64, 16, 16, 1, 1),      # r = 1: an image token sees the text and itself
+    (16, 12, 12, 40, 1),     # r beyond the diagonal: full attention
+    (200, 48, 40, 16, 1),    # several tile rows and columns, r = 16
+]
+
+
+@pytest.mark.parametrize("n_text,gridH,gridW,r,H", CASES)
+def test_backward_all_rows(n_text, gridH, gridW, r, H):
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, H, seed=300 + r)
+    for h in range(H):
+        q, k, v, g = (t[0, h].float().cpu().numpy() for t in (Q, K, V, dO))
+        rQ, rK, rV = orc.backward(q, k, v, g, n_text, gridH, gridW, r)
+        check_grad("dQ", dQ[0, h].float().cpu().numpy(), rQ)
+        check_grad("dK", dK[0, h].float().cpu().numpy(), rK)
+        check_grad("dV", dV[0, h].float().cpu().numpy(), rV)
+
+
+def test_forward_lse_is_the_log_of_the_softmax_denominator():
+    n_text, gridH, gridW, r = 37, 20, 24, 5
+    Q, K, V, dO, O, lse, *_ = run_case(n_text, gridH, gridW, r, 1, seed=77, q_scale=2.0)
+    q, k, v = (t[0, 0].float().cpu().numpy() for t in (Q, K, V))
+    N = q.shape[0]
+    _, m, l, _ = orc.attention_rows(q, k, v, np.arange(N), n_text, gridH, gridW, r, return_stats=True)
+    np.testing.assert_allclose(lse[0, 0].cpu().numpy(), m + np.log(l), rtol=0, atol=2e-3)
+
+
+def test_backward_flux_1024_sampled():
+    """64 x 64 grid + 512 text tokens, r = 16 (the 1024^2 shape), one head: sampled rows and columns."""
+    n_text, gridH, gridW, r = 512, 64, 64, 16
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, 1, seed=9)
+    q, k, v, g = (t[0, 0].float().cpu().numpy() for t in (Q, K, V, dO))
+    rng = np.random.default_rng(3)
+    N = q.shape[0]
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 511, 512, 513, 512 + 63, 512 + 64, 512 + 15 * 64 + 15, 512 + 16 * 64 + 16, N - 1],
+                                     rng.integers(0, N, size=200)]))
+    check_grad("dQ", dQ[0, 0].float().cpu().numpy()[rows], orc.backward_dq_rows(q, k, v, g, rows, n_text, gridH, gridW, r))
+    cols = np.unique(np.concatenate([[0, 511, 512, 512 + 63, N - 1], rng.integers(0, n_text, size=6), rng.integers(n_text, N, size=60)]))
+    rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
+    check_grad("dK", dK[0, 0].float().cpu().numpy()[cols], rK)
+    check_grad("dV", dV[0, 0].float().cpu().numpy()[cols], rV)
