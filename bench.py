@@ -34,6 +34,8 @@ def main():
                     help="row-band mode: time ONE band of the workload cut into this many bands (one GPU's share of a "
                          "patch-parallel run; no second GPU is used)")
     ap.add_argument("--band", type=int, default=-1, help="which band (default: a middle one, halo on both sides)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (dQ, dK, dV from dO and the forward pass's log-sum-exp) instead of the forward pass")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -62,6 +64,9 @@ def main():
     torch.cuda.set_device(0)
     if args.bands > 0:
         bench_band(args, w, dev)
+        return
+    if args.backward:
+        bench_backward(args, w, dev)
         return
     Q, K, V = make_qkv(w, dev)
     O = torch.empty_like(Q)
@@ -145,6 +150,60 @@ def main():
             "us_per_query_row": (tc1 - tc0) * 1e6 / len(rows),
         }
         result["check_vs_oracle"] = {"rows": int(len(rows)), "max_abs": float(np.abs(diff).max()),
+                                     "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
+    ctx.destroy()
+    print(json.dumps(result))
+
+
+def bench_backward(args, w, dev):
+    """Backward pass on the workload's shape.  Useful work: the five matrix products of attention's backward
+    pass over the unmasked pairs, 10*sumM*d FLOP per head (the kernels execute seven: the scores are
+    recomputed once for dQ and once for dK/dV, and dV has its own pass)."""
+    import numpy as np
+    import torch
+    from paper_2412_16112_amd import clear_attn as ca
+    from paper_2412_16112_amd.inputs import make_qkv
+
+    Q, K, V = make_qkv(w, dev)
+    g = torch.Generator(device=dev).manual_seed(w.seed + 1000)
+    dO = torch.randn(Q.shape, generator=g, device=dev, dtype=torch.float32).to(Q.dtype)
+    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, ca.CLEAR_BF16)
+    ctx.reserve(w.B * w.H)
+    O, lse = ctx.forward_lse(Q, K, V)
+    for _ in range(args.warmup):
+        grads = ctx.backward(Q, K, V, O, dO, lse)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        grads = ctx.backward(Q, K, V, O, dO, lse)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    sum_m = ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r)
+    useful = 10.0 * sum_m * w.head_dim * w.B * w.H
+    result = {
+        "metric": "local-attn backward useful TFLOP/s (10*sumM*d)", "value": useful / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + " backward", "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text,
+                   "gridH": w.gridH, "gridW": w.gridW, "r": w.r, "sum_M_per_head": sum_m},
+        "roofline": {"bound": "mfma", "kernel": "clear_bwd_bf16_kernel (dQ, dK, dV passes)", "achieved": useful / (ms * 1e-3) / 1e12,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": useful / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import clear_oracle as orc
+        rng = np.random.default_rng(4321)
+        h = w.H // 2
+        q, k, v, go = (t[0, h].float().cpu().double().numpy() for t in (Q, K, V, dO))
+        rows = np.sort(rng.choice(w.N, size=min(w.N, 65536), replace=False)).astype(np.int64)
+        tc0 = time.perf_counter()
+        ref = orc.backward_dq_rows(q, k, v, go, rows, w.n_text, w.gridH, w.gridW, w.r)
+        tc1 = time.perf_counter()
+        got = grads[0][0, h][torch.from_numpy(rows).to(dev)].float().cpu().numpy()
+        diff = got - ref
+        result["cpu_baseline"] = {"value": (tc1 - tc0) * 1e6 / len(rows), "unit": "us per dQ row", "cores": orc.num_threads(), "kind": "oracle",
+                                  "sample": "dQ of %d random rows of head %d (fp64, two dense-masked passes over all %d keys per row), %.1f s"
+                                            % (len(rows), h, w.N, tc1 - tc0)}
+        result["check_vs_oracle"] = {"rows": int(len(rows)), "max_abs": float(np.abs(diff).max()), "ref_max_abs": float(np.abs(ref).max()),
                                      "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
     ctx.destroy()
     print(json.dumps(result))

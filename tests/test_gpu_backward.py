@@ -80,3 +80,53 @@ def test_backward_flux_1024_sampled():
     rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
     check_grad("dK", dK[0, 0].float().cpu().numpy()[cols], rK)
     check_grad("dV", dV[0, 0].float().cpu().numpy()[cols], rV)
+
+
+@pytest.mark.slow
+def test_backward_flux_2048_sampled():
+    """128 x 128 grid + 512 text tokens, r = 16 (the 2048^2 shape), one head: sampled query rows, image-key
+    columns at corners, borders and tile boundaries, and two text-key columns (every query row feeds those)."""
+    n_text, gridH, gridW, r = 512, 128, 128, 16
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, 1, seed=19, q_scale=1.5)
+    q, k, v, g = (t[0, 0].float().cpu().numpy() for t in (Q, K, V, dO))
+    rng = np.random.default_rng(5)
+    N = q.shape[0]
+    img = lambda y, x: n_text + y * gridW + x
+    rows = np.unique(np.concatenate([[0, 255, 256, 511, img(0, 0), img(0, 127), img(127, 0), img(127, 127), img(15, 15), img(16, 16), img(63, 64)],
+                                     rng.integers(0, N, size=300)]))
+    check_grad("dQ", dQ[0, 0].float().cpu().numpy()[rows], orc.backward_dq_rows(q, k, v, g, rows, n_text, gridH, gridW, r))
+    cols = np.unique(np.concatenate([[3, 500, img(0, 0), img(0, 127), img(127, 127), img(15, 16), img(16, 15), img(64, 63), img(112, 8)],
+                                     rng.integers(n_text, N, size=40)]))
+    rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
+    check_grad("dK", dK[0, 0].float().cpu().numpy()[cols], rK)
+    check_grad("dV", dV[0, 0].float().cpu().numpy()[cols], rV)
+
+
+def test_backward_rejects_bad_arguments():
+    n_text, gridH, gridW, r, d = 8, 16, 16, 4, 128
+    Q, K, V = make_qkv_shape(1, 1, n_text, gridH, gridW, d, "bf16", seed=1, device="cuda:0")
+    ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        L = ca.lib()
+        import ctypes
+        vp = ctypes.c_void_p
+        args = [ctx._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), O.data_ptr(), lse.data_ptr()]
+        # dQ aliasing an input
+        rc = L.clear_attn_backward(*args, Q.data_ptr(), torch.empty_like(Q).data_ptr(), torch.empty_like(Q).data_ptr(), 1, 1, n_text, gridH, gridW, d, r, vp(0))
+        assert rc == ca.CLEAR_ERR_INVALID_ARG
+        a, b, c = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+        rc = L.clear_attn_backward(*args, a.data_ptr(), b.data_ptr(), c.data_ptr(), 1, 1, n_text, gridH, gridW + 1, d, r, vp(0))
+        assert rc == ca.CLEAR_ERR_MISMATCH
+        rc = L.clear_attn_backward(*args[:6], None, a.data_ptr(), b.data_ptr(), c.data_ptr(), 1, 1, n_text, gridH, gridW, d, r, vp(0))
+        assert rc == ca.CLEAR_ERR_INVALID_ARG
+    finally:
+        ctx.destroy()
+    # fp32 contexts have no backward pass
+    ctx = ca.ClearAttn(8, 16, 16, 64, 4, ca.CLEAR_F32)
+    try:
+        with pytest.raises(ca.ClearAttnError) as e:
+            ca._check(ca.lib().clear_attn_reserve_backward(ctx._ctx, 1), ctx._ctx)
+        assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+    finally:
+        ctx.destroy()
