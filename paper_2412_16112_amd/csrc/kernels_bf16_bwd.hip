@@ -340,19 +340,21 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     }
 }
 
-// delta_i = dO_i . O_i for every row: one wave per row, two channels per lane.
+// delta_i = dO_i . O_i for every row: 16 lanes per row (8 channels = 16 bytes each), 16 rows per workgroup.
 __global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, const __bf16* dO, float* delta, long long rows)
 {
-    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
-    const int lane = threadIdx.x & 63;
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-    const bf16x2 o = *(const bf16x2*)(O + row * D + 2 * lane);
-    const bf16x2 g = *(const bf16x2*)(dO + row * D + 2 * lane);
-    float s = (float)o[0] * (float)g[0] + (float)o[1] * (float)g[1];
+    const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int part = threadIdx.x & 15;
+    float s = 0.f;
+    if (row < rows) {
+        const bf16x8 o = *(const bf16x8*)(O + row * D + 8 * part);
+        const bf16x8 g = *(const bf16x8*)(dO + row * D + 8 * part);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane == 0) delta[row] = s;
+        for (int j = 0; j < 8; ++j) s += (float)o[j] * (float)g[j];
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (row < rows && part == 0) delta[row] = s;
 }
 
 // Adds up the column-split partial sums of the text rows and stores them as bf16: one workgroup per
@@ -391,7 +393,7 @@ hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* d
 {
     const int BH = p.B * p.H;
     const long long rows = (long long)BH * p.N;
-    hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
+    hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = launch_bwd<kBwdQ, false>(p, BH * p.n_q_tiles, stream);
