@@ -1,0 +1,58 @@
+"""torch.autograd entry point for the CLEAR local attention (argument marshalling only: forward and backward
+both run in the HIP library).
+
+    from paper_2412_16112_amd.autograd import clear_attention
+    O = clear_attention(Q, K, V, n_text=512, gridH=64, gridW=64, r=16)   # [B, H, N, 128] bf16, differentiable
+
+Contexts (tile schedule, mask table, workspaces) are cached per (device, shape) and live until the process
+ends or `clear_context_cache()` is called.
+"""
+import torch
+
+from . import clear_attn as ca
+
+_contexts = {}
+
+
+def _context(device, n_text, gridH, gridW, head_dim, r, dtype_code):
+    key = (device.index, n_text, gridH, gridW, head_dim, r, dtype_code)
+    ctx = _contexts.get(key)
+    if ctx is None:
+        with torch.cuda.device(device):
+            ctx = ca.ClearAttn(n_text, gridH, gridW, head_dim, r, dtype_code)
+        _contexts[key] = ctx
+    return ctx
+
+
+def clear_context_cache():
+    for ctx in _contexts.values():
+        ctx.destroy()
+    _contexts.clear()
+
+
+class ClearAttentionFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(fctx, Q, K, V, n_text, gridH, gridW, r):
+        Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
+        ctx = _context(Q.device, n_text, gridH, gridW, Q.shape[-1], r, ca._dtype_code(Q))
+        needs_grad = any(fctx.needs_input_grad[:3])
+        with torch.cuda.device(Q.device):
+            if needs_grad:
+                O, lse = ctx.forward_lse(Q, K, V)
+                fctx.save_for_backward(Q, K, V, O, lse)
+                fctx.clear_ctx = ctx
+            else:
+                O = ctx.forward(Q, K, V)
+        return O
+
+    @staticmethod
+    def backward(fctx, dO):
+        Q, K, V, O, lse = fctx.saved_tensors
+        with torch.cuda.device(Q.device):
+            dQ, dK, dV = fctx.clear_ctx.backward(Q, K, V, O, dO.contiguous().to(Q.dtype), lse)
+        return dQ, dK, dV, None, None, None, None
+
+
+def clear_attention(Q, K, V, n_text, gridH, gridW, r):
+    """softmax(Q K^T / sqrt(d) under the CLEAR mask) V for [B, H, n_text + gridH*gridW, d] device tensors."""
+    return ClearAttentionFunction.apply(Q, K, V, n_text, gridH, gridW, r)

@@ -130,3 +130,27 @@ def test_backward_rejects_bad_arguments():
         assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
     finally:
         ctx.destroy()
+
+
+def test_autograd_function_matches_the_oracle():
+    from paper_2412_16112_amd.autograd import clear_attention, clear_context_cache
+    n_text, gridH, gridW, r, d = 20, 18, 21, 6, 128
+    Q, K, V = make_qkv_shape(1, 2, n_text, gridH, gridW, d, "bf16", seed=55, device="cuda:0")
+    Q.requires_grad_(True), K.requires_grad_(True), V.requires_grad_(True)
+    g = torch.Generator(device="cuda:0").manual_seed(56)
+    W = torch.randn(Q.shape, generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    try:
+        O = clear_attention(Q, K, V, n_text, gridH, gridW, r)
+        (O.float() * W.float()).sum().backward()
+        torch.cuda.synchronize()
+        with torch.no_grad():
+            O2 = clear_attention(Q.detach(), K.detach(), V.detach(), n_text, gridH, gridW, r)
+        assert torch.equal(O, O2)  # the forward with and without the statistics output gives the same bits
+    finally:
+        clear_context_cache()
+    for h in range(2):
+        q, k, v, w = (t[0, h].detach().float().cpu().numpy() for t in (Q, K, V, W))
+        rQ, rK, rV = orc.backward(q, k, v, w, n_text, gridH, gridW, r)
+        check_grad("dQ", Q.grad[0, h].float().cpu().numpy(), rQ)
+        check_grad("dK", K.grad[0, h].float().cpu().numpy(), rK)
+        check_grad("dV", V.grad[0, h].float().cpu().numpy(), rV)
