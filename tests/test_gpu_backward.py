@@ -21,9 +21,9 @@ def check_grad(name, got, ref):
     assert max_abs <= TOL["bf16"][0] * max(scale, 1e-30) and rel_rms <= TOL["bf16"][1], (name, max_abs, scale, rel_rms)
 
 
-def run_case(n_text, gridH, gridW, r, H, seed, q_scale=1.0):
+def run_case(n_text, gridH, gridW, r, H, seed, q_scale=1.0, B=1):
     d = 128
-    Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, "bf16", seed=seed, device="cuda:0", q_scale=q_scale)
+    Q, K, V = make_qkv_shape(B, H, n_text, gridH, gridW, d, "bf16", seed=seed, device="cuda:0", q_scale=q_scale)
     g = torch.Generator(device="cuda:0").manual_seed(seed + 1000)
     dO = torch.randn(Q.shape, generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
     ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16)
@@ -55,6 +55,17 @@ def test_backward_all_rows(n_text, gridH, gridW, r, H):
         check_grad("dQ", dQ[0, h].float().cpu().numpy(), rQ)
         check_grad("dK", dK[0, h].float().cpu().numpy(), rK)
         check_grad("dV", dV[0, h].float().cpu().numpy(), rV)
+
+
+def test_backward_batch_of_two():
+    n_text, gridH, gridW, r, H = 40, 20, 28, 4, 3
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, H, seed=71, B=2)
+    for b, h in ((0, 0), (1, 2)):
+        q, k, v, g = (t[b, h].float().cpu().numpy() for t in (Q, K, V, dO))
+        rQ, rK, rV = orc.backward(q, k, v, g, n_text, gridH, gridW, r)
+        check_grad("dQ", dQ[b, h].float().cpu().numpy(), rQ)
+        check_grad("dK", dK[b, h].float().cpu().numpy(), rK)
+        check_grad("dV", dV[b, h].float().cpu().numpy(), rV)
 
 
 def test_forward_lse_is_the_log_of_the_softmax_denominator():
