@@ -122,6 +122,26 @@ int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_i
  * the matrix pipeline, masked and padding slots included ("executed" work; useful work is sumM). */
 int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head);
 
+/* ---- Other local masks through the same scheduler (the sparse-attention variants the paper compares CLEAR
+ * with; the text rule of Eq. 3 - text rows and columns all ones - is kept for every kind):
+ *   CLEAR_MASK_DISC    dx^2 + dy^2 < r^2 (Eq. 3; what clear_attn_create builds)
+ *   CLEAR_MASK_SQUARE  |dx| < r and |dy| < r: a (2r-1) x (2r-1) window centred on the query, cut off at the border
+ *   CLEAR_MASK_SWIN    both tokens in the same r x r window of the partition whose origin is moved up and left
+ *                      by `shift` (0 <= shift < r; the windows cut by the border are smaller); shift 0 and r/2
+ *                      on alternate layers give the shifted-window scheme
+ * Every other entry point takes such a context unchanged (forward, forward_band, backward, ...); the executed
+ * work differs: only the disc has precomputed lane masks, the other kinds use the arithmetic element mask. */
+typedef enum { CLEAR_MASK_DISC = 0, CLEAR_MASK_SQUARE = 1, CLEAR_MASK_SWIN = 2 } clear_mask_kind;
+int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r,
+                             int dtype, int mask_kind, int shift);
+/* clear_attn_schedule_host for a mask kind. */
+int clear_attn_schedule_host_masked(int gridH, int gridW, int r, int mask_kind, int shift, int q_tile_h, int q_tile_w,
+                                    int k_tile_h, int k_tile_w, int* n_q_tiles, long long* n_pairs, int* row_ptr,
+                                    int* col_idx, unsigned char* flags);
+/* sumM for a mask kind (clear_attn_mask_count is the disc). */
+int clear_attn_mask_count_masked(int n_text, int gridH, int gridW, int r, int mask_kind, int shift,
+                                 unsigned long long* sumM);
+
 /* ---- Training: forward with the softmax statistics, and the backward pass (the attention layers are the
  * trained parameters of the distillation of Sec. 3.3; the gradients follow from differentiating Eq. 1
  * under the mask of Eq. 3).  bf16 with head_dim 128 only.

@@ -29,7 +29,18 @@
 #include <omp.h>
 #endif
 
-/* Eq. 3, 0-based.  Returns 1 when query row i may attend to key column j. */
+/*
+ * Which local mask the image-image pairs follow.  0: the disc of Eq. 3 (CLEAR; the default).  The other two
+ * are the sparse-attention variants the paper compares with, kept under the same text rule:
+ * 1: square window, |dx| < r and |dy| < r (neighbourhood attention, window cut off at the border);
+ * 2: Swin windows: both tokens in the same r x r cell of the partition whose origin is moved up and left
+ *    by `shift` tokens.
+ * A process-wide setting (set it, call the oracle, set it back): every function below goes through oracle_mask.
+ */
+static int g_mask_kind = 0, g_mask_shift = 0;
+void oracle_set_mask(int kind, int shift) { g_mask_kind = kind; g_mask_shift = shift; }
+
+/* Eq. 3 (or the variant selected above), 0-based.  Returns 1 when query row i may attend to key column j. */
 int oracle_mask(int64_t i, int64_t j, int n_text, int gridH, int gridW, int r)
 {
     (void)gridH;
@@ -38,6 +49,9 @@ int oracle_mask(int64_t i, int64_t j, int n_text, int gridH, int gridW, int r)
     int yi = pi / gridW, xi = pi % gridW;
     int yj = pj / gridW, xj = pj % gridW;
     int64_t dx = xi - xj, dy = yi - yj;
+    if (g_mask_kind == 1) return (llabs(dx) < r && llabs(dy) < r) ? 1 : 0;
+    if (g_mask_kind == 2)
+        return ((yi + g_mask_shift) / r == (yj + g_mask_shift) / r && (xi + g_mask_shift) / r == (xj + g_mask_shift) / r) ? 1 : 0;
     return (dx * dx + dy * dy < (int64_t)r * r) ? 1 : 0;
 }
 

@@ -40,6 +40,8 @@ def _load():
         lib.oracle_backward_dq_rows.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         lib.oracle_backward_dkv_cols.restype = i32
         lib.oracle_backward_dkv_cols.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp]
+        lib.oracle_set_mask.restype = None
+        lib.oracle_set_mask.argtypes = [i32, i32]
         lib.oracle_mask_count.restype = u64
         lib.oracle_mask_count.argtypes = [i32, i32, i32, i32]
         lib.oracle_mask_dense.restype = None
@@ -51,6 +53,23 @@ def _load():
         lib.oracle_num_threads.restype = i32
         _lib = lib
     return _lib
+
+
+MASK_DISC, MASK_SQUARE, MASK_SWIN = 0, 1, 2
+
+
+class mask_kind:
+    """Context manager: `with mask_kind(MASK_SQUARE): ...` makes every oracle call inside use that local mask
+    for the image-image pairs (process-wide setting of the C library; the disc of Eq. 3 outside)."""
+
+    def __init__(self, kind, shift=0):
+        self.kind, self.shift = kind, shift
+
+    def __enter__(self):
+        _load().oracle_set_mask(self.kind, self.shift)
+
+    def __exit__(self, *exc):
+        _load().oracle_set_mask(MASK_DISC, 0)
 
 
 def num_threads():

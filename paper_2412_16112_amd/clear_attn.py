@@ -12,10 +12,11 @@ LIB_PATH = os.path.join(_HERE, "libclear_attn.so")
 CLEAR_OK, CLEAR_ERR_INVALID_ARG, CLEAR_ERR_UNSUPPORTED, CLEAR_ERR_ALLOC, CLEAR_ERR_HIP, CLEAR_ERR_MISMATCH = range(6)
 CLEAR_BF16, CLEAR_F32 = 0, 1
 CLEAR_MERGE_EXACT, CLEAR_MERGE_AVERAGE = 0, 1
+CLEAR_MASK_DISC, CLEAR_MASK_SQUARE, CLEAR_MASK_SWIN = 0, 1, 2
 CLEAR_TILE_PARTIAL, CLEAR_TILE_FULL = 0, 1
 
 EXPORTS = [
-    "clear_attn_create", "clear_attn_reserve", "clear_attn_forward", "clear_attn_forward_profile",
+    "clear_attn_create", "clear_attn_create_masked", "clear_attn_mask_count_masked", "clear_attn_schedule_host_masked", "clear_attn_reserve", "clear_attn_forward", "clear_attn_forward_profile",
     "clear_attn_destroy", "clear_attn_forward_lse", "clear_attn_backward", "clear_attn_reserve_backward",
     "clear_attn_forward_band", "clear_attn_band_layout", "clear_attn_merge_text",
     "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
@@ -43,6 +44,8 @@ def lib():
         i, vp, ip = ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)
         ullp, llp = ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(ctypes.c_longlong)
         L.clear_attn_create.argtypes = [ctypes.POINTER(vp), i, i, i, i, i, i]
+        L.clear_attn_create_masked.argtypes = [ctypes.POINTER(vp), i, i, i, i, i, i, i, i]
+        L.clear_attn_mask_count_masked.argtypes = [i, i, i, i, i, i, ullp]
         L.clear_attn_reserve.argtypes = [vp, i]
         L.clear_attn_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.clear_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp, i, ctypes.POINTER(ctypes.c_float)]
@@ -51,6 +54,7 @@ def lib():
         L.clear_attn_mask_count.argtypes = [i, i, i, i, ullp]
         L.clear_attn_tile_shape.argtypes = [i, i, ip, ip, ip, ip]
         L.clear_attn_schedule_host.argtypes = [i, i, i, i, i, i, i, ip, llp, vp, vp, vp]
+        L.clear_attn_schedule_host_masked.argtypes = [i, i, i, i, i, i, i, i, i, ip, llp, vp, vp, vp]
         L.clear_attn_schedule_size.argtypes = [vp, ip, ip, ip, ip, ip, llp]
         L.clear_attn_schedule_copy.argtypes = [vp, vp, vp, vp]
         L.clear_attn_executed_pairs.argtypes = [vp, ullp]
@@ -88,6 +92,12 @@ def clear_attn_measure_mfma_peak(seconds=0.5):
     return float(tf.value), float(mhz.value)
 
 
+def clear_attn_mask_count_masked(n_text, gridH, gridW, r, mask_kind, shift=0):
+    out = ctypes.c_ulonglong(0)
+    _check(lib().clear_attn_mask_count_masked(n_text, gridH, gridW, r, mask_kind, shift, ctypes.byref(out)))
+    return int(out.value)
+
+
 def clear_attn_tile_shape(head_dim, dtype):
     v = [ctypes.c_int(0) for _ in range(4)]
     _check(lib().clear_attn_tile_shape(head_dim, dtype, *[ctypes.byref(x) for x in v]))
@@ -107,6 +117,19 @@ def clear_attn_schedule_host(gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_ti
     return row_ptr, col_idx[:npairs.value], flags[:npairs.value]
 
 
+def clear_attn_schedule_host_masked(gridH, gridW, r, mask_kind, shift, q_tile_h, q_tile_w, k_tile_h, k_tile_w):
+    """clear_attn_schedule_host for a mask kind."""
+    nq, npairs = ctypes.c_int(0), ctypes.c_longlong(0)
+    args = (gridH, gridW, r, mask_kind, shift, q_tile_h, q_tile_w, k_tile_h, k_tile_w)
+    _check(lib().clear_attn_schedule_host_masked(*args, ctypes.byref(nq), ctypes.byref(npairs), None, None, None))
+    row_ptr = np.zeros(nq.value + 1, dtype=np.int32)
+    col_idx = np.zeros(max(1, npairs.value), dtype=np.int32)
+    flags = np.zeros(max(1, npairs.value), dtype=np.uint8)
+    _check(lib().clear_attn_schedule_host_masked(*args, ctypes.byref(nq), ctypes.byref(npairs), row_ptr.ctypes.data,
+                                                 col_idx.ctypes.data, flags.ctypes.data))
+    return row_ptr, col_idx[:npairs.value], flags[:npairs.value]
+
+
 def _dtype_code(t):
     import torch
     if t.dtype == torch.bfloat16:
@@ -119,11 +142,15 @@ def _dtype_code(t):
 class ClearAttn:
     """Owns one clear_attn_ctx (clear_attn_create / clear_attn_forward / clear_attn_destroy)."""
 
-    def __init__(self, n_text, gridH, gridW, head_dim, r, dtype):
+    def __init__(self, n_text, gridH, gridW, head_dim, r, dtype, mask_kind=CLEAR_MASK_DISC, shift=0):
         self._ctx = ctypes.c_void_p(None)
         self.shape = (n_text, gridH, gridW, head_dim, r)
         self.dtype = dtype
-        _check(lib().clear_attn_create(ctypes.byref(self._ctx), n_text, gridH, gridW, head_dim, r, dtype))
+        self.mask = (mask_kind, shift)
+        if mask_kind == CLEAR_MASK_DISC and shift == 0:
+            _check(lib().clear_attn_create(ctypes.byref(self._ctx), n_text, gridH, gridW, head_dim, r, dtype))
+        else:
+            _check(lib().clear_attn_create_masked(ctypes.byref(self._ctx), n_text, gridH, gridW, head_dim, r, dtype, mask_kind, shift))
 
     def reserve(self, BH):
         _check(lib().clear_attn_reserve(self._ctx, BH), self._ctx)

@@ -110,6 +110,7 @@ typedef const __attribute__((address_space(4))) unsigned long long* const_u64_pt
 struct MaskArgs {
     int a, b;  // linear: first token of the tile, token limit; image: tile origin (row, col)
     int hh, qy, qx, gridH, gridW, r2;
+    int kind, r, shift;    // MaskKind; for kinds other than the disc: radius / window size and Swin shift
     const_u64_ptr row[2];  // kMaskTable: 16 lane masks per key block (one per score register)
 };
 
@@ -128,6 +129,16 @@ __device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             if (base + 8 * (r >> 2) + (r & 3) >= ma.b) s[r] = -INFINITY;
+    } else if (MASK == kMaskImage && ma.kind != kMaskDisc) {
+        // the other local masks, element by element
+        const MaskSpec spec = {ma.kind, ma.r, ma.shift};
+        const int ky0 = ma.a + kKeyBlockH * kb, kx0 = ma.b + 4 * ma.hh;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int ky = ky0 + (e >> 2), kx = kx0 + (e & 3);
+            const bool keep = ky < ma.gridH && kx < ma.gridW && mask_admits(spec, ma.qy, ma.qx, ky, kx);
+            s[e] = keep ? s[e] : -INFINITY;
+        }
     } else if (MASK == kMaskImage) {
         const int ky0 = ma.a + kKeyBlockH * kb, kx0 = ma.b + 4 * ma.hh;
         int dx2[4];

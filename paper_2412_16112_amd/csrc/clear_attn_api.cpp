@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <algorithm>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <string>
 #include <vector>
@@ -17,6 +18,7 @@ using namespace clear;
 
 struct clear_attn_ctx {
     int n_text = 0, gridH = 0, gridW = 0, head_dim = 0, r = 0, dtype = 0;
+    int mask_kind = 0, mask_shift = 0;
     int device = 0;
     Schedule sched;
     int* d_row_ptr = nullptr;
@@ -128,11 +130,21 @@ int clear_attn_tile_shape(int head_dim, int dtype, int* q_tile_h, int* q_tile_w,
     return CLEAR_OK;
 }
 
+static int check_mask(int mask_kind, int r, int shift, std::string* why);
+
 int clear_attn_schedule_host(int gridH, int gridW, int r, int q_tile_h, int q_tile_w, int k_tile_h, int k_tile_w,
                              int* n_q_tiles, long long* n_pairs, int* row_ptr, int* col_idx, unsigned char* flags)
 {
+    return clear_attn_schedule_host_masked(gridH, gridW, r, CLEAR_MASK_DISC, 0, q_tile_h, q_tile_w, k_tile_h, k_tile_w, n_q_tiles, n_pairs,
+                                           row_ptr, col_idx, flags);
+}
+
+int clear_attn_schedule_host_masked(int gridH, int gridW, int r, int mask_kind, int shift, int q_tile_h, int q_tile_w, int k_tile_h,
+                                    int k_tile_w, int* n_q_tiles, long long* n_pairs, int* row_ptr, int* col_idx, unsigned char* flags)
+{
     std::string why;
     int rc = check_shape(0, gridH, gridW, r, &why);
+    if (rc == CLEAR_OK) rc = check_mask(mask_kind, r, shift, &why);
     if (rc != CLEAR_OK) return fail(nullptr, rc, why);
     if (q_tile_h < 1 || q_tile_w < 1 || k_tile_h < 1 || k_tile_w < 1) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "tile sizes must be >= 1");
     if (!n_q_tiles || !n_pairs) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "n_q_tiles / n_pairs is NULL");
@@ -140,7 +152,7 @@ int clear_attn_schedule_host(int gridH, int gridW, int r, int q_tile_h, int q_ti
     if (!sizes_only && (!row_ptr || !col_idx || !flags)) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "row_ptr, col_idx and flags must be all NULL or all set");
     Schedule s;
     try {
-        build_schedule(gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_tile_w, &s);
+        build_schedule(gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_tile_w, &s, mask_kind, shift);
     } catch (const std::bad_alloc&) {
         return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
     }
@@ -154,13 +166,39 @@ int clear_attn_schedule_host(int gridH, int gridW, int r, int q_tile_h, int q_ti
     return CLEAR_OK;
 }
 
+static int check_mask(int mask_kind, int r, int shift, std::string* why)
+{
+    if (mask_kind != CLEAR_MASK_DISC && mask_kind != CLEAR_MASK_SQUARE && mask_kind != CLEAR_MASK_SWIN) { *why = "mask_kind must be CLEAR_MASK_DISC, CLEAR_MASK_SQUARE or CLEAR_MASK_SWIN"; return CLEAR_ERR_INVALID_ARG; }
+    if (mask_kind == CLEAR_MASK_SWIN ? (shift < 0 || shift >= r) : shift != 0) { *why = "shift must be 0, or in [0, r) for CLEAR_MASK_SWIN"; return CLEAR_ERR_INVALID_ARG; }
+    return CLEAR_OK;
+}
+
 int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r, int dtype)
+{
+    return clear_attn_create_masked(out, n_text, gridH, gridW, head_dim, r, dtype, CLEAR_MASK_DISC, 0);
+}
+
+int clear_attn_mask_count_masked(int n_text, int gridH, int gridW, int r, int mask_kind, int shift, unsigned long long* sumM)
+{
+    std::string why;
+    if (!sumM) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "sumM is NULL");
+    int rc = check_shape(n_text, gridH, gridW, r, &why);
+    if (rc == CLEAR_OK) rc = check_mask(mask_kind, r, shift, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+    *sumM = mask_count(n_text, gridH, gridW, r, mask_kind, shift);
+    return CLEAR_OK;
+}
+
+int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r, int dtype,
+                             int mask_kind, int shift)
 {
     std::string why;
     if (!out) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "out is NULL");
     int rc = check_shape(n_text, gridH, gridW, r, &why);
     if (rc != CLEAR_OK) return fail(nullptr, rc, why);
     rc = check_kernel(head_dim, dtype, &why);
+    if (rc != CLEAR_OK) return fail(nullptr, rc, why);
+    rc = check_mask(mask_kind, r, shift, &why);
     if (rc != CLEAR_OK) return fail(nullptr, rc, why);
 
     if (dtype == CLEAR_BF16 && (long long)n_text + (long long)gridH * gridW > (1LL << 24) - 1)
@@ -170,10 +208,11 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
     if (!ctx) return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory");
     ctx->n_text = n_text; ctx->gridH = gridH; ctx->gridW = gridW;
     ctx->head_dim = head_dim; ctx->r = r; ctx->dtype = dtype;
+    ctx->mask_kind = mask_kind; ctx->mask_shift = shift;
     int qth, qtw, kth, ktw;
     clear_attn_tile_shape(head_dim, dtype, &qth, &qtw, &kth, &ktw);
     try {
-        build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &ctx->sched);
+        build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &ctx->sched, mask_kind, shift);
     } catch (const std::bad_alloc&) {
         delete ctx;
         return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
@@ -226,7 +265,7 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
         }
     }
     std::vector<unsigned long long> mask_tbl;
-    if (dtype == CLEAR_BF16) {
+    if (dtype == CLEAR_BF16 && mask_kind == CLEAR_MASK_DISC) {  // (other masks take the arithmetic element mask)
         // relative block offsets that a non-empty (patch, block) pair can have
         ctx->mask_ry = std::min((r + 2) / 4, (gridH + 3) / 4);
         ctx->mask_rx = std::min((r + 6) / 8, (gridW + 7) / 8);
@@ -349,6 +388,7 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.mask_tbl = ctx->d_mask_tbl;
     p.mask_ry = ctx->mask_ry;
     p.mask_rx = ctx->mask_rx;
+    p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
     p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     p.own_y0 = 0;
     p.own_y1 = gridH;
@@ -514,6 +554,7 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     p.n_qtx = s.n_qtx;
     p.row_ptr = ctx->d_row_ptr; p.col_idx = ctx->d_col_idx; p.n_plain = ctx->d_n_plain; p.mask_tbl = ctx->d_mask_tbl;
     p.mask_ry = ctx->mask_ry; p.mask_rx = ctx->mask_rx;
+    p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
     p.scale = (float)(1.0 / std::sqrt((double)head_dim));
     p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     if (n_text > 0) {

@@ -25,6 +25,7 @@ constexpr int kF32QTileH = 16, kF32QTileW = 16;
 
 struct Schedule {
     int gridH = 0, gridW = 0, r = 0;
+    int mask_kind = 0, mask_shift = 0;  // MaskKind of block_class.h; shift: Swin windows only
     int qth = 0, qtw = 0, kth = 0, ktw = 0;
     int n_qty = 0, n_qtx = 0, n_kty = 0, n_ktx = 0;
     std::vector<int> row_ptr;        // n_q_tiles + 1
@@ -33,8 +34,8 @@ struct Schedule {
 };
 
 // Host-side integer geometry (schedule.cpp)
-void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s);
-unsigned long long mask_count(int n_text, int gridH, int gridW, int r);
+void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s, int mask_kind = 0, int mask_shift = 0);
+unsigned long long mask_count(int n_text, int gridH, int gridW, int r, int mask_kind = 0, int mask_shift = 0);
 // Pairs fed to the matrix pipeline per (batch, head) by the bf16 kernels (image pass + text-query pass).
 unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys);
 // Pairs visited by the fp32 path (it tests every slot of every staged tile).
@@ -73,6 +74,7 @@ struct FwdParams {
     int vshift;
     float* band_o;    // when set, the text merge writes fp32 softmax outputs [B*H][n_text][head_dim] here ...
     float* band_lse;  // ... and the natural log of the softmax denominators [B*H][n_text] here, not O's text rows
+    int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift
     float* lse;       // optional [B*H][N]: natural log of every row's softmax denominator sum_j exp(q.k_j / sqrt(d))
 };
 
@@ -103,6 +105,7 @@ struct BwdParams {
     const int* n_plain;
     const unsigned long long* mask_tbl;
     int mask_ry, mask_rx;
+    int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift
     float scale_log2e;  // log2(e) / sqrt(head_dim)
     float scale;        // 1 / sqrt(head_dim)
     // text rows: sums over every token, split along the columns, partial sums added up afterwards

@@ -471,15 +471,16 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         } else if (TEXTQ) {
             si.cls0 = si.cls1 = kBlockSkip;
         } else {
-            si.cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
-            si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH,
-                                           p.gridW, p.r2);
+            const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
+            si.cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
+            si.cls1 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
         }
         si.tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
         si.ma.hh = hh;
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
         si.ma.qy = qy; si.ma.qx = qx; si.ma.gridH = p.gridH; si.ma.gridW = p.gridW; si.ma.r2 = p.r2;
+        si.ma.kind = p.mask_kind; si.ma.r = p.mask_r; si.ma.shift = p.mask_shift;
         si.ma.row[0] = si.ma.row[1] = mask_tbl;
         if (!TEXTQ && !si.linear && p.mask_tbl) {
             // lane masks of the two blocks: whole blocks use the all-ones entry, unreachable blocks the all-zeros

@@ -267,14 +267,16 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
             cls0 = classify_linear_block(ta, 32, lin_limit);
             cls1 = classify_linear_block(ta + 32, 32, lin_limit);
         } else {
-            cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
-            cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+            const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
+            cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
+            cls1 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
         }
         MaskArgs ma;
         ma.hh = hh;
         ma.a = ta;
         ma.b = linear ? lin_limit : tb;
         ma.qy = ry; ma.qx = rx; ma.gridH = p.gridH; ma.gridW = p.gridW; ma.r2 = p.r2;
+        ma.kind = p.mask_kind; ma.r = p.mask_r; ma.shift = p.mask_shift;
         ma.row[0] = ma.row[1] = mask_tbl;
         if (!LINROWS && !linear && p.mask_tbl) {
             const int ncol = 2 * p.mask_rx + 1;

@@ -115,7 +115,8 @@ __global__ void __launch_bounds__(NT) clear_fwd_f32_kernel(const FwdParams p)
             } else {
                 const int ky = (int)a + slot / kKeyTileW, kx = (int)b + slot % kKeyTileW;
                 const int dy = ky - qy, dx = kx - qx;
-                ok = !TEXTQ && ky < p.gridH && kx < p.gridW && dx * dx + dy * dy < p.r2;
+                const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
+                ok = !TEXTQ && ky < p.gridH && kx < p.gridW && (p.mask_kind == kMaskDisc ? dx * dx + dy * dy < p.r2 : mask_admits(spec, qy, qx, ky, kx));
             }
             if (!ok) continue;
             float s = 0.f;

@@ -15,9 +15,10 @@ static inline int interval_gap(int a0, int a1, int b0, int b1)
     return 0;
 }
 
-void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s)
+void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s, int mask_kind, int mask_shift)
 {
     s->gridH = gridH; s->gridW = gridW; s->r = r;
+    s->mask_kind = mask_kind; s->mask_shift = mask_shift;
     s->qth = qth; s->qtw = qtw; s->kth = kth; s->ktw = ktw;
     s->n_qty = ceil_div(gridH, qth); s->n_qtx = ceil_div(gridW, qtw);
     s->n_kty = ceil_div(gridH, kth); s->n_ktx = ceil_div(gridW, ktw);
@@ -39,10 +40,22 @@ void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int 
                     const int ky0 = ky * kth, ky1 = imin(ky0 + kth, gridH) - 1;
                     const int kx0 = kx * ktw, kx1 = imin(kx0 + ktw, gridW) - 1;
                     const long long dy = interval_gap(qy0, qy1, ky0, ky1), dx = interval_gap(qx0, qx1, kx0, kx1);
-                    if (dy * dy + dx * dx >= r2) continue;  // no pair closer than r: not listed
                     const bool k_inside = (ky0 + kth <= gridH) && (kx0 + ktw <= gridW);
                     const long long fy = imax(qy1 - ky0, ky1 - qy0), fx = imax(qx1 - kx0, kx1 - qx0);
-                    const bool full = q_inside && k_inside && fy * fy + fx * fx < r2;
+                    bool full;
+                    if (mask_kind == kMaskSquare) {
+                        if (dy >= r || dx >= r) continue;  // no pair inside the square window: not listed
+                        full = q_inside && k_inside && fy < r && fx < r;
+                    } else if (mask_kind == kMaskSwin) {
+                        // windows (per axis) that the two tiles touch: listed iff they share one
+                        const int wq0 = (qy0 + mask_shift) / r, wq1 = (qy1 + mask_shift) / r, wk0 = (ky0 + mask_shift) / r, wk1 = (ky1 + mask_shift) / r;
+                        const int vq0 = (qx0 + mask_shift) / r, vq1 = (qx1 + mask_shift) / r, vk0 = (kx0 + mask_shift) / r, vk1 = (kx1 + mask_shift) / r;
+                        if (wq1 < wk0 || wk1 < wq0 || vq1 < vk0 || vk1 < vq0) continue;
+                        full = q_inside && k_inside && wq0 == wq1 && wk0 == wk1 && wq0 == wk0 && vq0 == vq1 && vk0 == vk1 && vq0 == vk0;
+                    } else {
+                        if (dy * dy + dx * dx >= r2) continue;  // no pair closer than r: not listed
+                        full = q_inside && k_inside && fy * fy + fx * fx < r2;
+                    }
                     s->col_idx.push_back(ky * s->n_ktx + kx);
                     s->flags.push_back(full ? 1 : 0);
                 }
@@ -50,8 +63,26 @@ void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int 
         }
 }
 
-unsigned long long mask_count(int n_text, int gridH, int gridW, int r)
+unsigned long long mask_count(int n_text, int gridH, int gridW, int r, int mask_kind, int mask_shift)
 {
+    if (mask_kind == kMaskSwin) {
+        // every window of h x w tokens contributes (h w)^2 pairs; windows are the cells of the shifted partition
+        const unsigned long long n_img = (unsigned long long)gridH * gridW, N = n_img + n_text;
+        unsigned long long sy = 0, sx = 0, img = 0;
+        // sum over window rows of h^2 ... the count factorises: sum_{wy, wx} (h_wy w_wx)^2 = (sum h^2)(sum w^2)
+        for (int y = 0; y < gridH;) {
+            const int end = imin(gridH, ((y + mask_shift) / r + 1) * r - mask_shift);
+            sy += (unsigned long long)(end - y) * (end - y);
+            y = end;
+        }
+        for (int x = 0; x < gridW;) {
+            const int end = imin(gridW, ((x + mask_shift) / r + 1) * r - mask_shift);
+            sx += (unsigned long long)(end - x) * (end - x);
+            x = end;
+        }
+        img = sy * sx;
+        return (unsigned long long)n_text * N + n_img * n_text + img;
+    }
     // Each offset (dy, dx) of the open disc occurs (gridH - |dy|)(gridW - |dx|) times on the raster.
     const unsigned long long n_img = (unsigned long long)gridH * gridW, N = n_img + n_text;
     unsigned long long img = 0;
@@ -61,7 +92,7 @@ unsigned long long mask_count(int n_text, int gridH, int gridW, int r)
         if (ady >= gridH) continue;
         for (long long dx = -(r - 1); dx <= r - 1; ++dx) {
             const long long adx = dx < 0 ? -dx : dx;
-            if (adx >= gridW || dx * dx + dy * dy >= r2) continue;
+            if (adx >= gridW || (mask_kind == kMaskDisc && dx * dx + dy * dy >= r2)) continue;  // (square: every |dx|, |dy| < r)
             img += (unsigned long long)(gridH - ady) * (unsigned long long)(gridW - adx);
         }
     }
@@ -75,6 +106,7 @@ unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_s
     unsigned long long blocks = 0;  // executed (32 query x 32 key) blocks
     const int n_text_tiles = ceil_div(n_text, kKeyTileKeys);
     const int nwy = s.qth / kWaveQH, nwx = s.qtw / kWaveQW;
+    const MaskSpec spec = {s.mask_kind, s.r, s.mask_shift};
     for (int ty = 0; ty < s.n_qty; ++ty)
         for (int tx = 0; tx < s.n_qtx; ++tx) {
             const int qt = ty * s.n_qtx + tx;
@@ -89,8 +121,8 @@ unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_s
                         const int ky0 = (s.col_idx[e] / s.n_ktx) * s.kth, kx0 = (s.col_idx[e] % s.n_ktx) * s.ktw;
                         bool any = false;
                         for (int kb = 0; kb < 2; ++kb)
-                            any |= classify_image_block(y0, x0, kWaveQH, kWaveQW, ky0 + kKeyBlockH * kb, kx0, kKeyBlockH,
-                                                        kKeyBlockW, s.gridH, s.gridW, s.r * s.r) != kBlockSkip;
+                            any |= classify_image_block_spec(spec, y0, x0, kWaveQH, kWaveQW, ky0 + kKeyBlockH * kb, kx0, kKeyBlockH,
+                                                             kKeyBlockW, s.gridH, s.gridW) != kBlockSkip;
                         blocks += 2 * any;
                     }
                 }
