@@ -79,3 +79,35 @@ def make_qkv_shape(B, H, n_text, gridH, gridW, head_dim, dtype, seed, device="cp
     if q_scale != 1.0:
         Q = (Q.float() * q_scale).to(Q.dtype)
     return Q, K, V
+
+
+def make_prologue_inputs(gridH, gridW, head_dim, seed, ntk_factor=1.0, theta=10000.0, device="cpu"):
+    """Inputs of the query/key prologue for a FLUX-style block: per-channel RMS-norm gains for Q and K
+    (1 + 0.1 N(0,1), fp32) and the rotary tables of the two image axes, fp32 [grid, head_dim/2, 2] = (cos, sin).
+
+    The channel pairs are split over three position axes in the proportion 1 : 3.5 : 3.5 (16 / 56 / 56
+    channels at head_dim 128); the first axis is constant over the sequence, so its pairs hold (1, 0) in
+    both tables; the second follows the row, the third the column.  Pair j of an axis with n pairs has the
+    frequency (theta * ntk_factor) ** (-j / n) (ntk_factor 1: the native setting; 10: the resolution-
+    extrapolation setting of Sec. 4.3)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    half = head_dim // 2
+    n_row = n_col = (half * 7) // 16
+    n_const = half - n_row - n_col
+    gain_q = (1.0 + 0.1 * torch.randn(head_dim, generator=g, dtype=torch.float32))
+    gain_k = (1.0 + 0.1 * torch.randn(head_dim, generator=g, dtype=torch.float32))
+
+    def table(n_pos, first, n):
+        t = torch.zeros(n_pos, half, 2, dtype=torch.float64)
+        t[:, :, 0] = 1.0
+        freq = (theta * ntk_factor) ** (-torch.arange(n, dtype=torch.float64) / n)
+        ang = torch.arange(n_pos, dtype=torch.float64)[:, None] * freq[None, :]
+        t[:, first:first + n, 0] = torch.cos(ang)
+        t[:, first:first + n, 1] = torch.sin(ang)
+        return t.float()
+
+    table_y = table(gridH, n_const, n_row)
+    table_x = table(gridW, n_const + n_row, n_col)
+    dev = torch.device(device)
+    return gain_q.to(dev), gain_k.to(dev), table_y.to(dev), table_x.to(dev)
