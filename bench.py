@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--band", type=int, default=-1, help="which band (default: a middle one, halo on both sides)")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (dQ, dK, dV from dO and the forward pass's log-sum-exp) instead of the forward pass")
+    ap.add_argument("--prologue", action="store_true",
+                    help="time the forward pass with the query/key prologue (RMS norm, rotary embedding, logit scale) fused in, "
+                         "against the plain forward pass and against the prologue as two passes of their own")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -67,6 +70,9 @@ def main():
         return
     if args.backward:
         bench_backward(args, w, dev)
+        return
+    if args.prologue:
+        bench_prologue(args, w, dev)
         return
     Q, K, V = make_qkv(w, dev)
     O = torch.empty_like(Q)
@@ -149,6 +155,88 @@ def main():
                       % (len(rows_t), len(rows_i), h, w.N, tc1 - tc0),
             "us_per_query_row": (tc1 - tc0) * 1e6 / len(rows),
         }
+        result["check_vs_oracle"] = {"rows": int(len(rows)), "max_abs": float(np.abs(diff).max()),
+                                     "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
+    ctx.destroy()
+    print(json.dumps(result))
+
+
+def bench_prologue(args, w, dev):
+    """Forward pass with the query/key prologue.  Three routes over the same raw Q, K: (a) the plain forward pass
+    on them (no prologue; the floor), (b) fused: Q transformed as it is loaded, K by one pass into the context's
+    buffer, (c) a prologue pass over Q and one over K, then the plain forward pass.  `value` is route (b)."""
+    import numpy as np
+    import torch
+    from paper_2412_16112_amd import clear_attn as ca
+    from paper_2412_16112_amd.inputs import make_prologue_inputs, make_qkv
+
+    Q, K, V = make_qkv(w, dev)
+    O = torch.empty_like(Q)
+    gq, gk, ty, tx = make_prologue_inputs(w.gridH, w.gridW, w.head_dim, w.seed + 2000, ntk_factor=10.0, device=dev)
+    logit_scale = 1.1
+    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, ca.CLEAR_BF16)
+    ctx.reserve(w.B * w.H)
+    Qp, Kp = torch.empty_like(Q), torch.empty_like(K)
+
+    def plain():
+        ctx.forward(Q, K, V, O)
+
+    def fused():
+        ctx.forward_prologue(Q, K, V, O, q_gain=gq, k_gain=gk, rope_y=ty, rope_x=tx, logit_scale=logit_scale)
+
+    def two_pass():
+        ca.clear_attn_qk_prologue(Q, w.n_text, w.gridH, w.gridW, gain=gq, rope_y=ty, rope_x=tx, out=Qp)
+        ca.clear_attn_qk_prologue(K, w.n_text, w.gridH, w.gridW, gain=gk, rope_y=ty, rope_x=tx, out=Kp)
+        ctx.forward(Qp, Kp, V, O)
+
+    def one_pass_only():
+        ca.clear_attn_qk_prologue(K, w.n_text, w.gridH, w.gridW, gain=gk, rope_y=ty, rope_x=tx, out=Kp)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_plain, ms_fused, ms_two, ms_pass = timed(plain), timed(fused), timed(two_pass), timed(one_pass_only)
+    sum_m = ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r)
+    useful = 4.0 * sum_m * w.head_dim * w.B * w.H
+    tensor_bytes = Q.numel() * 2
+    result = {
+        "metric": "local-attn forward with fused q/k prologue, useful TFLOP/s (4*sumM*d)", "value": useful / (ms_fused * 1e-3) / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_fused, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + " + prologue", "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text, "gridH": w.gridH,
+                   "gridW": w.gridW, "r": w.r, "logit_scale": logit_scale},
+        "routes_ms": {"plain_forward_no_prologue": ms_plain, "fused": ms_fused, "two_prologue_passes_then_forward": ms_two,
+                      "one_prologue_pass": ms_pass},
+        # the pass of its own is the HBM-bound kernel here: one tensor read, one written
+        "roofline": {"bound": "hbm", "kernel": "qk_prologue_kernel<128>", "achieved": 2 * tensor_bytes / (ms_pass * 1e-3) / 1e9, "peak": 8000.0,
+                     "unit": "GB/s", "frac": 2 * tensor_bytes / (ms_pass * 1e-3) / 1e9 / 8000.0, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import clear_oracle as orc
+        from oracle import prologue as pro
+        fused()
+        torch.cuda.synchronize()
+        h = w.H // 2
+        f64 = lambda t: None if t is None else t.detach().cpu().double().numpy()
+        rng = np.random.default_rng(777)
+        rows = np.sort(np.concatenate([rng.choice(w.n_text, size=min(w.n_text, 64), replace=False),
+                                       w.n_text + rng.choice(w.gridH * w.gridW, size=4096, replace=False)])).astype(np.int64)
+        tc0 = time.perf_counter()
+        qp = pro.qk_prologue(f64(Q[0, h]), f64(gq), 1e-6, w.n_text, w.gridH, w.gridW, f64(ty), f64(tx))
+        kp = pro.qk_prologue(f64(K[0, h]), f64(gk), 1e-6, w.n_text, w.gridH, w.gridW, f64(ty), f64(tx))
+        tc1 = time.perf_counter()
+        ref = orc.attention_rows(qp * logit_scale, kp, f64(V[0, h]), rows, w.n_text, w.gridH, w.gridW, w.r)
+        got = O[0, h][torch.from_numpy(rows).to(dev)].float().cpu().numpy()
+        diff = got - ref
+        result["cpu_baseline"] = {"value": (tc1 - tc0) * 1e6 / (2 * w.N), "unit": "us per prologue row", "cores": 1, "kind": "oracle",
+                                  "sample": "prologue of Q and K of head %d (%d rows each, numpy fp64), %.1f s" % (h, w.N, tc1 - tc0)}
         result["check_vs_oracle"] = {"rows": int(len(rows)), "max_abs": float(np.abs(diff).max()),
                                      "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
     ctx.destroy()

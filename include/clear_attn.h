@@ -142,6 +142,36 @@ int clear_attn_schedule_host_masked(int gridH, int gridW, int r, int mask_kind, 
 int clear_attn_mask_count_masked(int n_text, int gridH, int gridW, int r, int mask_kind, int shift,
                                  unsigned long long* sumM);
 
+/* ---- The block's query/key prologue fused into the forward pass (Sec. 3.1: the backbone perceives the two
+ * image axes through a rotary position embedding; Sec. 4.3: its frequencies and a scale on the attention
+ * logits are changed for resolution extrapolation).  bf16 only.
+ *
+ * Q and K are the raw projections; each token row x of a head goes through
+ *   1. RMS normalisation, if its gain is non-NULL:  x_c * gain_c / sqrt(mean_c x_c^2 + norm_eps);
+ *   2. rotary embedding, if rope_y and rope_x are non-NULL (both or neither): channels (2i, 2i+1) of the image
+ *      token at (y, x) are turned by the sum of two angles given as (cos, sin) pairs, rope_y[y][i] and
+ *      rope_x[x][i] (fp32, [gridH or gridW][head_dim/2][2]; a pair that an axis does not act on holds (1, 0)):
+ *      (e, o) -> (cos e - sin o, sin e + cos o); text tokens are not turned;
+ *   3. rounding to bf16,
+ * and the softmax runs on logit_scale * q.k / sqrt(head_dim) (logit_scale > 0).  Gains are fp32 [head_dim];
+ * all four tables are device pointers, 16-byte aligned, read-only, caller-owned.
+ *
+ * The query rows are transformed in registers as each workgroup loads them (no extra pass over Q); the key
+ * rows, which many workgroups stage, are transformed once into a buffer the context owns (B*H*N*head_dim
+ * bf16, allocated on first use or by clear_attn_reserve_prologue; K itself is not modified).  Errors as for
+ * clear_attn_forward, plus CLEAR_ERR_UNSUPPORTED for an fp32 context. */
+int clear_attn_forward_prologue(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B,
+                                int H, int n_text, int gridH, int gridW, int head_dim, int r, const float* q_gain,
+                                const float* k_gain, float norm_eps, const float* rope_y, const float* rope_x,
+                                float logit_scale, void* stream);
+int clear_attn_reserve_prologue(clear_attn_ctx* ctx, int BH);
+/* Steps 1-3 on a whole tensor as a pass of its own: X, Y device bf16 [B, H, N, head_dim] (head_dim 64 or 128),
+ * Y == X allowed, otherwise they must not overlap.  No context: errors are reported through the status and
+ * clear_attn_last_error(NULL). */
+int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int gridH, int gridW, int head_dim,
+                           const float* gain, float norm_eps, const float* rope_y, const float* rope_x,
+                           void* stream);
+
 /* ---- Training: forward with the softmax statistics, and the backward pass (the attention layers are the
  * trained parameters of the distillation of Sec. 3.3; the gradients follow from differentiating Eq. 1
  * under the mask of Eq. 3).  bf16 with head_dim 128 only.

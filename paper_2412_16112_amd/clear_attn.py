@@ -22,6 +22,7 @@ EXPORTS = [
     "clear_attn_mask_count", "clear_attn_tile_shape", "clear_attn_schedule_host",
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
     "clear_attn_measure_mfma_peak", "clear_attn_last_error",
+    "clear_attn_forward_prologue", "clear_attn_reserve_prologue", "clear_attn_qk_prologue",
 ]
 
 _lib = None
@@ -65,6 +66,10 @@ def lib():
         L.clear_attn_band_layout.argtypes = [i, i, i, i, ip, ip, ip, ip]
         L.clear_attn_merge_text.argtypes = [i, vp, vp, i, i, i, ctypes.c_longlong, i, i, vp, i, vp]
         L.clear_attn_measure_mfma_peak.argtypes = [ctypes.c_double, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        f = ctypes.c_float
+        L.clear_attn_forward_prologue.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp, vp, f, vp, vp, f, vp]
+        L.clear_attn_reserve_prologue.argtypes = [vp, i]
+        L.clear_attn_qk_prologue.argtypes = [vp, vp, i, i, i, i, i, i, vp, f, vp, vp, vp]
         L.clear_attn_last_error.argtypes = [vp]
         L.clear_attn_last_error.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -174,6 +179,24 @@ class ClearAttn:
                                         n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
 
+    def forward_prologue(self, Q, K, V, O=None, q_gain=None, k_gain=None, norm_eps=1e-6, rope_y=None, rope_x=None, logit_scale=1.0,
+                         stream=None):
+        """clear_attn_forward_prologue: Q, K raw; gains fp32 [head_dim]; rope tables fp32 [grid, head_dim/2, 2]."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        _check_prologue_tables(Q.device, head_dim, gridH, gridW, (q_gain, k_gain), rope_y, rope_x)
+        if O is None:
+            O = torch.empty_like(Q)
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        ptr = lambda t: None if t is None else t.data_ptr()
+        _check(lib().clear_attn_forward_prologue(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, n_text, gridH, gridW,
+                                                 head_dim, r, ptr(q_gain), ptr(k_gain), norm_eps, ptr(rope_y), ptr(rope_x), logit_scale,
+                                                 ctypes.c_void_p(s)), self._ctx)
+        return O
+
     def forward_lse(self, Q, K, V, O=None, lse=None, stream=None):
         """clear_attn_forward_lse: returns (O, lse) with lse fp32 [B, H, N]."""
         import torch
@@ -264,6 +287,33 @@ class ClearAttn:
             self.destroy()
         except Exception:
             pass
+
+
+def _check_prologue_tables(device, head_dim, gridH, gridW, gains, rope_y, rope_x):
+    import torch
+    for g in gains:
+        if g is not None and not (g.is_cuda and g.device == device and g.dtype == torch.float32 and g.is_contiguous() and g.shape == (head_dim,)):
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "gains must be contiguous fp32 device tensors [head_dim]")
+    for t, n in ((rope_y, gridH), (rope_x, gridW)):
+        if t is not None and not (t.is_cuda and t.device == device and t.dtype == torch.float32 and t.is_contiguous()
+                                  and t.shape == (n, head_dim // 2, 2)):
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "rotary tables must be contiguous fp32 device tensors [grid, head_dim/2, 2]")
+
+
+def clear_attn_qk_prologue(X, n_text, gridH, gridW, gain=None, norm_eps=1e-6, rope_y=None, rope_x=None, out=None, stream=None):
+    """clear_attn_qk_prologue on a bf16 device tensor [B, H, N, head_dim]; out may be X itself."""
+    import torch
+    B, H, N, d = X.shape
+    if not (X.is_cuda and X.is_contiguous() and X.dtype == torch.bfloat16 and N == n_text + gridH * gridW):
+        raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "X must be a contiguous bf16 device tensor [B, H, n_text + gridH*gridW, head_dim]")
+    _check_prologue_tables(X.device, d, gridH, gridW, (gain,), rope_y, rope_x)
+    if out is None:
+        out = torch.empty_like(X)
+    s = torch.cuda.current_stream(X.device).cuda_stream if stream is None else stream
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib().clear_attn_qk_prologue(X.data_ptr(), out.data_ptr(), B, H, n_text, gridH, gridW, d, ptr(gain), norm_eps, ptr(rope_y),
+                                        ptr(rope_x), ctypes.c_void_p(s)))
+    return out
 
 
 def clear_attn_band_layout(gridH_total, r, n_bands, band):

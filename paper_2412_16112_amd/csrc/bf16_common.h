@@ -68,6 +68,35 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));  // expcnt, lgkmcnt unconstrained
 }
 
+// Query/key prologue on 8 consecutive channels (4 rotary pairs) of one token, in fp32: RMS-norm gain, then
+// the rotation by the sum of the row angle and the column angle (tables hold (cos, sin) per pair).
+// gain8 / ry8 / rx8 point at this chunk's 8 floats of the gain vector and of the token's two table rows.
+__device__ __forceinline__ void prologue_chunk(float (&x)[8], float inv_rms, const float* gain8, const float* ry8, const float* rx8)
+{
+    if (gain8) {
+        const f32x4 g0 = *(const f32x4*)gain8, g1 = *(const f32x4*)(gain8 + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x[j] = x[j] * inv_rms * g0[j];
+            x[4 + j] = x[4 + j] * inv_rms * g1[j];
+        }
+    }
+    if (ry8) {
+        const f32x4 a0 = *(const f32x4*)ry8, a1 = *(const f32x4*)(ry8 + 4);
+        const f32x4 b0 = *(const f32x4*)rx8, b1 = *(const f32x4*)(rx8 + 4);
+        const float cy[4] = {a0[0], a0[2], a1[0], a1[2]}, sy[4] = {a0[1], a0[3], a1[1], a1[3]};
+        const float cx[4] = {b0[0], b0[2], b1[0], b1[2]}, sx[4] = {b0[1], b0[3], b1[1], b1[3]};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float c = cy[t] * cx[t] - sy[t] * sx[t];
+            const float s = sy[t] * cx[t] + cy[t] * sx[t];
+            const float e = x[2 * t], o = x[2 * t + 1];
+            x[2 * t] = c * e - s * o;
+            x[2 * t + 1] = s * e + c * o;
+        }
+    }
+}
+
 struct WaveState {
     f32x16 oacc[4];  // O^T tiles: channel 32*db + 8*(reg/4) + 4*hh + reg%4 of this lane's query
     float m_run;     // running maximum, raw logits (may lag the true maximum by < 2^8 in the exponent)

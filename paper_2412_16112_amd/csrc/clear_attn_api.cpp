@@ -36,6 +36,9 @@ struct clear_attn_ctx {
     int bwd_BH = 0;
     float* d_bwd_delta = nullptr;  // [B*H][N]
     float* d_bwd_ws = nullptr;     // [3][B*H][max splits][n_text][head_dim]
+    // keys after the prologue (clear_attn_forward_prologue), grown on demand
+    int kpro_BH = 0;
+    void* d_kpro = nullptr;        // [B*H][N][head_dim] bf16
     std::string err;
 };
 
@@ -492,6 +495,90 @@ int clear_attn_forward_lse(clear_attn_ctx* ctx, const void* Q, const void* K, co
     return CLEAR_OK;
 }
 
+// Arguments of the query/key prologue shared by the two entry points below.
+static int check_prologue(clear_attn_ctx* ctx, int head_dim, const float* gain_a, const float* gain_b, float eps, const float* rope_y,
+                          const float* rope_x)
+{
+    if (head_dim % 8 != 0) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the prologue needs head_dim to be a multiple of 8");
+    if ((rope_y == nullptr) != (rope_x == nullptr)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "rope_y and rope_x must be given together");
+    if (((uintptr_t)gain_a | (uintptr_t)gain_b | (uintptr_t)rope_y | (uintptr_t)rope_x) & 15)
+        return fail(ctx, CLEAR_ERR_INVALID_ARG, "gains and rotary tables must be 16-byte aligned");
+    if ((gain_a || gain_b) && !(eps >= 0.f)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "norm_eps must be >= 0");
+    return CLEAR_OK;
+}
+
+int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int gridH, int gridW, int head_dim, const float* gain,
+                           float norm_eps, const float* rope_y, const float* rope_x, void* stream)
+{
+    if (!X || !Y) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "X and Y must be non-NULL");
+    if (((uintptr_t)X | (uintptr_t)Y) & 15) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "X and Y must be 16-byte aligned");
+    if (B < 1 || H < 1) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "B and H must be >= 1");
+    if (n_text < 0 || gridH < 0 || gridW < 0) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "n_text, gridH, gridW must be >= 0");
+    if (head_dim != 64 && head_dim != 128) return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the prologue is built for head_dim 64 and 128");
+    int rc = check_prologue(nullptr, head_dim, gain, nullptr, norm_eps, rope_y, rope_x);
+    if (rc != CLEAR_OK) return rc;
+    const long long N = (long long)n_text + (long long)gridH * gridW;
+    if (X != Y) {
+        const size_t bytes = (size_t)B * H * N * head_dim * 2;
+        const uintptr_t x0 = (uintptr_t)X, y0 = (uintptr_t)Y;
+        if (x0 < y0 + bytes && y0 < x0 + bytes) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "X and Y must be the same tensor or must not overlap");
+    }
+    hipError_t e = launch_qk_prologue(X, Y, (long long)B * H, n_text, gridH, gridW, head_dim, gain, norm_eps, rope_y, rope_x, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(nullptr, CLEAR_ERR_HIP, std::string("prologue launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+int clear_attn_reserve_prologue(clear_attn_ctx* ctx, int BH)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    if (BH < 1 || BH > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be in [1, 65535]");
+    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the fused prologue is built for bf16 only");
+    if (BH <= ctx->kpro_BH) return CLEAR_OK;
+    hipError_t e = hipDeviceSynchronize();  // a running forward may still read the old buffer
+    if (e == hipSuccess && ctx->d_kpro) e = hipFree(ctx->d_kpro);
+    ctx->d_kpro = nullptr;
+    ctx->kpro_BH = 0;
+    const long long N = (long long)ctx->n_text + (long long)ctx->gridH * ctx->gridW;
+    if (e == hipSuccess) e = hipMalloc(&ctx->d_kpro, (size_t)BH * N * ctx->head_dim * 2);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, e == hipErrorOutOfMemory ? CLEAR_ERR_ALLOC : CLEAR_ERR_HIP, std::string("prologue workspace allocation failed: ") + hipGetErrorString(e));
+    }
+    ctx->kpro_BH = BH;
+    return CLEAR_OK;
+}
+
+int clear_attn_forward_prologue(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H, int n_text,
+                                int gridH, int gridW, int head_dim, int r, const float* q_gain, const float* k_gain, float norm_eps,
+                                const float* rope_y, const float* rope_x, float logit_scale, void* stream)
+{
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
+    if (rc != CLEAR_OK) return rc;
+    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the fused prologue is built for bf16 only");
+    rc = check_prologue(ctx, head_dim, q_gain, k_gain, norm_eps, rope_y, rope_x);
+    if (rc != CLEAR_OK) return rc;
+    if (!(logit_scale > 0.f) || !std::isfinite(logit_scale)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "logit_scale must be positive and finite");
+    p.scale_log2e *= logit_scale;
+    p.q_gain = q_gain;
+    p.rope_y = rope_y;
+    p.rope_x = rope_x;
+    p.norm_eps = norm_eps;
+    if (k_gain || rope_y) {
+        // Every key row is staged by up to 36 workgroups, so its prologue runs once, ahead of the attention
+        // kernels, into the context's buffer; the query rows are handled as each workgroup loads its own.
+        rc = clear_attn_reserve_prologue(ctx, B * H);
+        if (rc != CLEAR_OK) return rc;
+        hipError_t e = launch_qk_prologue(K, ctx->d_kpro, (long long)B * H, n_text, gridH, gridW, head_dim, k_gain, norm_eps, rope_y, rope_x,
+                                          (hipStream_t)stream);
+        if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("prologue launch failed: ") + hipGetErrorString(e));
+        p.K = ctx->d_kpro;
+    }
+    hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
 int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
@@ -630,6 +717,7 @@ void clear_attn_destroy(clear_attn_ctx* ctx)
     if (ctx->d_ws_ml) (void)hipFree(ctx->d_ws_ml);
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
     if (ctx->d_bwd_ws) (void)hipFree(ctx->d_bwd_ws);
+    if (ctx->d_kpro) (void)hipFree(ctx->d_kpro);
     delete ctx;
 }
 

@@ -76,6 +76,11 @@ struct FwdParams {
     float* band_lse;  // ... and the natural log of the softmax denominators [B*H][n_text] here, not O's text rows
     int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift
     float* lse;       // optional [B*H][N]: natural log of every row's softmax denominator sum_j exp(q.k_j / sqrt(d))
+    // Query prologue applied while the query rows are loaded (bf16 kernels; all null: Q is used as it is).
+    const float* q_gain;  // [head_dim] RMS-norm gain, or null: no normalisation
+    const float* rope_y;  // [gridH][head_dim/2][2] (cos, sin) per row, or null: no rotation
+    const float* rope_x;  // [gridW][head_dim/2][2] (cos, sin) per column
+    float norm_eps;
 };
 
 // Launchers (kernels_bf16.hip, kernels_f32.hip).  Each returns the first HIP error met.
@@ -123,6 +128,10 @@ struct MergeParts {
 };
 hipError_t launch_merge_text(const MergeParts& parts, int BH, int n_text, long long N, int head_dim, int mode, void* O, int dtype,
                              hipStream_t stream);
+// prologue.hip: RMS norm + rotary embedding of whole [BH][N][head_dim] bf16 tensors (the keys of a fused
+// forward pass; also the stand-alone pass).  X == Y is allowed.
+hipError_t launch_qk_prologue(const void* X, void* Y, long long BH, int n_text, int gridH, int gridW, int head_dim, const float* gain,
+                              float eps, const float* rope_y, const float* rope_x, hipStream_t stream);
 // mfma_peak.hip: sustained rate of back-to-back bf16 MFMAs on every SIMD, and the shader clock it ran at.
 hipError_t measure_mfma_peak(int num_cus, double seconds, double* tflops, double* shader_mhz);
 

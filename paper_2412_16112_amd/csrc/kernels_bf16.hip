@@ -319,7 +319,6 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
     }
-
     const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
     const const_u64_ptr mask_tbl = (const_u64_ptr)p.mask_tbl;
 
@@ -519,6 +518,35 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         for (int j = len; j < nx_len; ++j) issue_tile(nx + j, lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
     };
 
+    // Prologue of the block on the query row (RMS norm over the 128 channels - this lane holds 64 of them,
+    // lane ^ 32 the others -, rotary embedding for image queries, back to bf16).  Runs once, after the first
+    // stage's loads have been issued, so that the wait for the row and for the tables overlaps them.
+    auto query_prologue = [&]() __attribute__((always_inline)) {
+    if (p.q_gain || p.rope_y) {
+        float ss = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ss += (float)qf[s][j] * (float)qf[s][j];
+        ss = wave_pair_sum(ss);
+        const float inv_rms = 1.0f / sqrtf(ss * (1.0f / D) + p.norm_eps);
+        const bool turn = !TEXTQ && p.rope_y;
+        const float* const ry = p.rope_y + (size_t)imin(qy, p.gridH - 1) * D;
+        const float* const rx = p.rope_x + (size_t)imin(qx, p.gridW - 1) * D;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int c0 = 16 * s + 8 * hh;
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = (float)qf[s][j];
+            prologue_chunk(x, inv_rms, p.q_gain ? p.q_gain + c0 : nullptr, turn ? ry + c0 : nullptr, turn ? rx + c0 : nullptr);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) qf[s][j] = (__bf16)x[j];
+        }
+    }
+
+    };
+
     // One pass over the stage list.  CAREFUL = false: fast pass (fixed reference maximum); returns the
     // lanes that ran out of headroom.  CAREFUL = true: exact online softmax, slow.
     auto run_pass = [&](auto careful_tag) -> unsigned long long {
@@ -541,6 +569,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         // wait lands inside the key loop, where it would also drain the tile prefetches.
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
+        if (!CAREFUL) query_prologue();  // the fast pass always comes first
         int buf = 0;
         if (CAREFUL) {
             for (int t = 0; t < n_tiles;) {
