@@ -15,7 +15,7 @@
  * 16-byte aligned; O must not overlap Q, K or V.  Inputs are taken as given (post-RoPE); the only
  * scaling applied is 1/sqrt(head_dim).  Values must be finite.
  *
- * Supported: dtype CLEAR_BF16 with head_dim 128 (MFMA path; fp32 accumulation, one round-to-nearest
+ * Supported: dtype CLEAR_BF16 with head_dim 128 or 64 (MFMA path; fp32 accumulation, one round-to-nearest
  * -even to bf16 on output) and dtype CLEAR_F32 with head_dim 64 (plain fp32 accuracy path).
  * n_text >= 0, gridH, gridW >= 1, r >= 1, N < 2^31 / head_dim is NOT required (64-bit offsets).
  *

@@ -1,4 +1,5 @@
-// Device-side building blocks shared by the bf16 kernels (forward and backward) for gfx950, head_dim 128:
+// Device-side building blocks shared by the bf16 kernels (forward and backward) for gfx950, head_dim
+// CLEAR_HEAD_DIM (128 unless the including file sets 64):
 // vector types, the LDS layout of a staged 64-token tile and its swizzle, LDS-direct staging loads, MFMA
 // operand reads from a staged tile (row-wise and transposed), the element masks of Eq. 3, and the two
 // 32 x 32 block products every kernel is made of.
@@ -17,8 +18,16 @@ typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int D = 128;               // head_dim
+#ifndef CLEAR_HEAD_DIM
+#define CLEAR_HEAD_DIM 128
+#endif
+constexpr int D = CLEAR_HEAD_DIM;    // head_dim
+static_assert(D == 128 || D == 64, "row layout, swizzle and operand addresses are worked out for 128 and 64 channels");
+constexpr int KS = D / 16;           // contraction steps of Q K^T (16 channels per matrix instruction)
+constexpr int NDB = D / 32;          // 32-channel slices of O
+constexpr int CHUNKS = D / 8;        // 16-byte chunks per token row
 constexpr int ROW_BYTES = D * 2;     // one token row of K or V
+constexpr int ROWS_PER_LOAD = 1024 / ROW_BYTES;  // token rows one LDS-direct wave load covers
 constexpr int TILE_KEYS = kKeyTileKeys;
 constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
 #ifndef CLEAR_OPERAND_PREFETCH
@@ -33,11 +42,19 @@ constexpr int STAGE_BYTES = TPS * 2 * TILE_BYTES;
 constexpr float FAST_SUM_LIMIT = 1.0e30f;  // the fast pass is discarded when a query's sums leave [0, 1e30)
 constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)
 
-// LDS layout of a staged tile: 64 rows of 256 B, unpadded (the LDS-direct load writes 1 KB = 4 rows per
-// wave instruction), with the 16-byte chunks of each row permuted: logical chunk c of row k sits in
-// slot c ^ swz(k).  swz is a bijection on 16 consecutive rows (the 32 key rows of a K read spread over
-// all banks) and sends 4 consecutive rows to 4 different 64-byte quads (so does the transposed V read).
-__host__ __device__ constexpr int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+// LDS layout of a staged tile: 64 rows of ROW_BYTES, unpadded (the LDS-direct load writes 1 KB per wave
+// instruction), with the 16-byte chunks of each row permuted: logical chunk c of row k sits in slot
+// c ^ swz(k).
+// 256-byte rows (a row = one sweep over the banks): swz is a bijection on 16 consecutive rows (the 32 key
+// rows of a K read spread over all banks) and sends 4 consecutive rows to 4 different 64-byte quads (so does
+// the transposed V read).
+// 128-byte rows (two rows per sweep): on the even rows of 16 consecutive rows swz is a bijection onto the 8
+// chunks (K read), and rows k and k + 2, which share a half sweep, land in different 64-byte quads (V read).
+// Both have period 16 in the row.
+__host__ __device__ constexpr int swz(int row)
+{
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | (((row >> 3) & 1) << 1) | ((row >> 2) & 1));
+}
 
 __device__ __forceinline__ float wave_pair_max(float x)
 {
@@ -98,7 +115,7 @@ __device__ __forceinline__ void prologue_chunk(float (&x)[8], float inv_rms, con
 }
 
 struct WaveState {
-    f32x16 oacc[4];  // O^T tiles: channel 32*db + 8*(reg/4) + 4*hh + reg%4 of this lane's query
+    f32x16 oacc[NDB];  // O^T tiles: channel 32*db + 8*(reg/4) + 4*hh + reg%4 of this lane's query
     float m_run;     // running maximum, raw logits (may lag the true maximum by < 2^8 in the exponent)
     float l_run;     // this lane's share of the denominator
     float c;         // log2(e) / sqrt(head_dim)
@@ -106,14 +123,15 @@ struct WaveState {
 
 // Per-lane LDS read offsets inside a staged tile.  All operand addresses of a tile derive from two
 // offsets by XOR with small constants and by adding multiples of 4 KB (ds_read immediates):
-//   K operand, block blk, contraction step ks:  ((tile + k0) ^ (ks << 5)) + blk * 8192
-//   V operand, block blk, step s2, slice db:    ((tile + TILE_BYTES + v0 [^ V_HI]) ^ (db << 6)) + blk * 8192 + s2 * 4096
+//   K operand, block blk, contraction step ks:  ((tile + k0) ^ (ks << 5)) + blk * 32 rows
+//   V operand, block blk, step s2, slice db:    ((tile + TILE_BYTES + v0 [^ V_HI]) ^ (db << 6)) + blk * 32 rows + s2 * 16 rows
 // (tile addresses are multiples of 1 KB, so the XORs stay inside the offsets' own bits).
 struct LaneOffsets {
-    unsigned k0;  // row qi, logical chunk hh:  qi * 256 + ((hh ^ swz(qi)) << 4)
+    unsigned k0;  // row qi, logical chunk hh:  qi * ROW_BYTES + ((hh ^ swz(qi)) << 4)
     unsigned v0;  // transpose read, slice 0, first half of the 16-key step
 };
-constexpr unsigned V_HI = (1u << 5) | (1u << 11);  // second half of the step: key rows + 8 (and their swizzle)
+// second half of the step: key rows + 8 (8 * ROW_BYTES) and what that does to their swizzle (chunk bit 1 either way)
+constexpr unsigned V_HI = (1u << 5) | (unsigned)(8 * ROW_BYTES);
 
 // Lane addresses of one staged tile (LDS byte addresses).
 struct TileAddr {
@@ -233,20 +251,20 @@ __device__ __forceinline__ bf16x8 read_v_operand(const TileAddr& ta, int blk, in
     return u.v;
 }
 
-__device__ __forceinline__ f32x16 qk_block(const TileAddr& ta, int blk, const bf16x8 (&qf)[8])
+__device__ __forceinline__ f32x16 qk_block(const TileAddr& ta, int blk, const bf16x8 (&qf)[KS])
 {
     f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(ta, blk, ks), qf[ks], s, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(ta, blk, ks), qf[ks], s, 0, 0, 0);
     return s;
 }
 
 // O^T += V_blk^T P^T for one 32-key block.  The contraction step s2 pairs P registers 8*s2 .. 8*s2+7
 // with key slots 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}.
-__device__ __forceinline__ void pv_block(f32x16 (&oacc)[4], const TileAddr& ta, int blk, const bf16x8 (&pf)[2])
+__device__ __forceinline__ void pv_block(f32x16 (&oacc)[NDB], const TileAddr& ta, int blk, const bf16x8 (&pf)[2])
 {
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
             oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db), pf[s2], oacc[db], 0, 0, 0);

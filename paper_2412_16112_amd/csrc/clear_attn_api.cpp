@@ -65,9 +65,9 @@ static int check_kernel(int head_dim, int dtype, std::string* why)
 {
     if (dtype != CLEAR_BF16 && dtype != CLEAR_F32) { *why = "dtype must be CLEAR_BF16 or CLEAR_F32"; return CLEAR_ERR_INVALID_ARG; }
     if (head_dim < 1) { *why = "head_dim must be >= 1"; return CLEAR_ERR_INVALID_ARG; }
-    if (dtype == CLEAR_BF16 && head_dim == 128) return CLEAR_OK;
+    if (dtype == CLEAR_BF16 && (head_dim == 128 || head_dim == 64)) return CLEAR_OK;
     if (dtype == CLEAR_F32 && head_dim == 64) return CLEAR_OK;
-    *why = "supported kernels: bf16 with head_dim 128, f32 with head_dim 64";
+    *why = "supported kernels: bf16 with head_dim 128 or 64, f32 with head_dim 64";
     return CLEAR_ERR_UNSUPPORTED;
 }
 
@@ -429,7 +429,8 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
 
 static hipError_t launch(const clear_attn_ctx* ctx, const FwdParams& p, hipStream_t stream, int phase)
 {
-    return (ctx->dtype == CLEAR_BF16) ? launch_bf16_d128(p, stream, phase) : launch_f32_d64(p, stream, phase);
+    if (ctx->dtype == CLEAR_BF16) return ctx->head_dim == 128 ? launch_bf16_d128(p, stream, phase) : launch_bf16_d64(p, stream, phase);
+    return launch_f32_d64(p, stream, phase);
 }
 
 int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
@@ -583,7 +584,7 @@ int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (BH < 1 || BH > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be in [1, 65535]");
-    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
     if (BH <= ctx->bwd_BH) return CLEAR_OK;
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
     if (ctx->d_bwd_ws) (void)hipFree(ctx->d_bwd_ws);
@@ -615,7 +616,7 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     if (B < 1 || H < 1 || (long long)B * H > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "B, H must be >= 1 and B*H <= 65535");
     if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
         return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
-    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
     const long long N = (long long)n_text + (long long)gridH * gridW;
     {
         // outputs must not overlap inputs or each other

@@ -87,6 +87,7 @@ struct FwdParams {
 // phase: kPhaseAll, or one of the three kernels of a forward pass (used to time them one by one).
 enum Phase : int { kPhaseAll = -1, kPhaseImage = 0, kPhaseTextQuery = 1, kPhaseTextMerge = 2 };
 hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase);
+hipError_t launch_bf16_d64(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
 void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl);

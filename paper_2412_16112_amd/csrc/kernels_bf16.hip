@@ -1,4 +1,5 @@
-// bf16 MFMA kernels for the CLEAR local-attention forward pass on gfx950 (head_dim 128).
+// bf16 MFMA kernels for the CLEAR local-attention forward pass on gfx950 (head_dim 128; kernels_bf16_d64.hip
+// compiles this file a second time for head_dim 64).
 //
 // Everything is computed "transposed" so that one lane owns one query for the whole pass:
 //   S^T = K_blk * Q^T   (32 keys x 32 queries per MFMA tile, A = keys from LDS, B = queries in VGPRs)
@@ -24,12 +25,20 @@
 #include "block_class.h"
 #include "clear_internal.h"
 
+#if CLEAR_HEAD_DIM == 64
+// second compilation of this file: its own kernel and launcher names
+#define clear_fwd_bf16_kernel clear_fwd_bf16_d64_kernel
+#define launch_bf16 launch_bf16_d64
+#else
+#define launch_bf16 launch_bf16_d128
+#endif
+
 namespace clear {
 namespace {
 
 // Careful pass, one staged tile: block by block, exact running maximum, O and the denominator rescaled
 // at every block (Eq. 1 as a textbook online softmax).  Slow; only runs when the fast pass gave up.
-__device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo, unsigned tile_lds,
+__device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[KS], const LaneOffsets& lo, unsigned tile_lds,
                                               int cls0, int cls1, bool linear, const MaskArgs& ma)
 {
     const TileAddr ta = tile_addr(tile_lds, lo);
@@ -48,7 +57,7 @@ __device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[
         const float alpha = __builtin_amdgcn_exp2f((ws.m_run - m_new) * ws.c);
         ws.l_run *= alpha;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) ws.oacc[db][r] *= alpha;
         ws.m_run = m_new;
@@ -70,9 +79,10 @@ __device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
 // Pins the instruction order: nothing is scheduled across this point.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// This wave's share of the staging loads of one tile: 2 of the tile's 16 row groups (4 token rows = 1 KB
-// each), for K and for V.  Load k covers row group k / 2, K for even k and V for odd k.
-constexpr int kRowGroupsPerWave = 2;
+// This wave's share of the staging loads of one tile: with 8 waves, 2 of the tile's 16 row groups (4 token
+// rows = 1 KB each) at head_dim 128, 1 of 8 (8 rows each) at head_dim 64, for K and for V.  Load k covers
+// row group k / 2, K for even k and V for odd k.
+constexpr int kRowGroupsPerWave = TILE_KEYS / ROWS_PER_LOAD / 8;
 constexpr int kTileLoads = 2 * kRowGroupsPerWave;
 struct TileLoads {
     const void* ksrc;                  // the head's K and V arrays
@@ -88,11 +98,13 @@ __device__ __forceinline__ void issue_tile_load(const TileLoads& tl, int k)
 
 __device__ __forceinline__ void issue_tile_loads(const TileLoads& tl)
 {
-    static_assert(kTileLoads == 4, "written out: a loop around inline asm is not unrolled");
+    static_assert(kTileLoads == 4 || kTileLoads == 2, "written out: a loop around inline asm is not unrolled");
     issue_tile_load(tl, 0);
     issue_tile_load(tl, 1);
-    issue_tile_load(tl, 2);
-    issue_tile_load(tl, 3);
+    if constexpr (kTileLoads == 4) {
+        issue_tile_load(tl, 2);
+        issue_tile_load(tl, 3);
+    }
 }
 
 // f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}), in order.
@@ -109,7 +121,8 @@ __device__ __forceinline__ void static_for(F& f)
 
 // Fast pass, one staged tile.  The reference maximum of a query never moves once set, so O is only
 // ever touched by the matrix pipeline and there is no data-dependent branch.
-// The tile's two 32-key blocks run as one hand-ordered pipeline of 32 matrix instructions:
+// The tile's two 32-key blocks run as one hand-ordered pipeline of 32 matrix instructions (head_dim 128;
+// 16 at head_dim 64, where every phase below is half as long and carries two score pairs per slot):
 //   slots  0- 7  S of block 0
 //   slots  8-15  S of block 1                      | mask, maximum, reference, P[0..7] of block 0
 //   slots 16-19  P V of block 0, keys of P[0..7]   | P[8..15] of block 0
@@ -126,7 +139,7 @@ __device__ __forceinline__ void static_for(F& f)
 // wave of the workgroup would be issuing loads and no matrix instruction.  No branch inside the pipeline:
 // all four always go out.
 template <int MASK, bool ADOPT, bool RIDE>
-__device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8], const LaneOffsets& lo,
+__device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS], const LaneOffsets& lo,
                                            unsigned tile_lds, const MaskArgs& ma, const TileLoads& tl)
 {
     constexpr int kb0 = 0;
@@ -137,13 +150,15 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
     bf16x8 pf0[2], pf1[2];
     float sum = 0.f;
 
-    // operand ring: K operands for slots 0-15, V operands for slots 16-31 (V slot i: s2 = (i/4)%2, db = i%4)
-    auto k_operand = [&](int slot) { return read_k_operand(ta, slot >> 3, slot & 7); };
+    // slots: [0, S1) S of block 0, [S1, PV0) S of block 1, [PV0, PV1) P V of block 0, [PV1, NSLOT) P V of block 1
+    constexpr int S1 = KS, PV0 = 2 * KS, PV1 = PV0 + 2 * NDB, NSLOT = PV1 + 2 * NDB;
+    // operand ring: K operands for the S slots, V operands for the P V slots (V slot i: s2 = (i / NDB) % 2, db = i % NDB)
+    auto k_operand = [&](int slot) { return read_k_operand(ta, slot / KS, slot % KS); };
     auto v_operand = [&](int slot) {
-        const int i = slot - 16;
-        return read_v_operand(ta, i >> 3, (i >> 2) & 1, i & 3);
+        const int i = slot - PV0;
+        return read_v_operand(ta, i / (2 * NDB), (i / NDB) & 1, i % NDB);
     };
-    auto block1_slot = [](int slot) { return (slot >= 8 && slot < 16) || slot >= 24; };
+    auto block1_slot = [](int slot) { return (slot >= S1 && slot < PV0) || slot >= PV1; };
     // operands are read PD slots ahead into a ring of PD + 2 (the extra entry keeps a read from landing on
     // the registers the previous matrix instruction is still reading)
     constexpr int PD = CLEAR_OPERAND_PREFETCH, RING = PD + 2;
@@ -163,8 +178,8 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
     auto run_slot = [&](auto slot_tag) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_tag)::value;
         // prefetch the operand of slot + PD
-        if (slot + PD < 32 && (!block1_slot(slot + PD) || has1)) {
-            if (slot + PD < 16)
+        if (slot + PD < NSLOT && (!block1_slot(slot + PD) || has1)) {
+            if (slot + PD < PV0)
                 op[(slot + PD) % RING] = k_operand(slot + PD);
             else
                 op[(slot + PD) % RING] = v_operand(slot + PD);
@@ -172,16 +187,17 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
         // a staging load for the next stage riding along (odd slots at the start)
         if (RIDE && (slot & 1) && (slot >> 1) < kTileLoads) issue_tile_load(tl, slot >> 1);
         // matrix instruction of this slot
-        if (slot < 8)
+        constexpr int pv_i = slot >= PV0 ? slot - PV0 : 0, pv_db = pv_i % NDB, pv_s2 = (pv_i / NDB) & 1;
+        if (slot < S1)
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], qf[slot], s0, 0, 0, 0);
-        else if (slot < 16) {
-            if (has1) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], qf[slot - 8], s1, 0, 0, 0);
-        } else if (slot < 24)
-            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf0[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+        else if (slot < PV0) {
+            if (has1) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], qf[slot - S1], s1, 0, 0, 0);
+        } else if (slot < PV1)
+            ws.oacc[pv_db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf0[pv_s2], ws.oacc[pv_db], 0, 0, 0);
         else if (has1)
-            ws.oacc[slot & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf1[(slot >> 2) & 1], ws.oacc[slot & 3], 0, 0, 0);
+            ws.oacc[pv_db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf1[pv_s2], ws.oacc[pv_db], 0, 0, 0);
         // vector work riding along
-        if (slot == 8) {
+        if (slot == S1) {
             if (MASK == kMaskTable) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s0[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s0[r] : -INFINITY;
@@ -193,11 +209,11 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
                 mc = ws.m_run * c;
             }
         }
-        if (slot == 9 && MASK == kMaskTable) {
+        if (slot == S1 + 1 && MASK == kMaskTable) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) mw[r] = ma.row[(kb0 + 1) & 1][r];
         }
-        if (slot == 16 && has1) {
+        if (slot == PV0 && has1) {
             if (MASK == kMaskTable) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s1[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s1[r] : -INFINITY;
@@ -210,34 +226,37 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
             }
         }
         // Exponentials as a three-deep vector pipeline over pairs of scores, so that the instructions of
-        // one slot do not wait on each other: pair g of block 0 is scaled in slot 8 + g, exponentiated in
-        // slot 9 + g, summed and packed in slot 10 + g; block 1 runs the same eight slots later.  P[0..7]
-        // of a block is complete three slots before the matrix instruction that needs it.
+        // one slot do not wait on each other: at head_dim 128 pair g of block 0 is scaled in slot 8 + g,
+        // exponentiated in slot 9 + g, summed and packed in slot 10 + g; block 1 runs the same eight slots
+        // later.  P[0..7] of a block is complete three slots before the matrix instruction that needs it.
+        // (head_dim 64: two pairs per slot from slot 4 on, block 1 four slots later.)
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
-            if (slot == 8 + g) {
+            constexpr int PPS = 8 / KS;  // score pairs per slot
+            const int b0 = S1 + g / PPS, b1 = PV0 + g / PPS;
+            if (slot == b0) {
                 s0[2 * g] = __builtin_fmaf(s0[2 * g], c, -mc);
                 s0[2 * g + 1] = __builtin_fmaf(s0[2 * g + 1], c, -mc);
             }
-            if (slot == 9 + g) {
+            if (slot == b0 + 1) {
                 s0[2 * g] = __builtin_amdgcn_exp2f(s0[2 * g]);
                 s0[2 * g + 1] = __builtin_amdgcn_exp2f(s0[2 * g + 1]);
             }
-            if (slot == 10 + g) {
+            if (slot == b0 + 2) {
                 sum += s0[2 * g] + s0[2 * g + 1];
                 pf0[g >> 2][2 * (g & 3)] = (__bf16)s0[2 * g];
                 pf0[g >> 2][2 * (g & 3) + 1] = (__bf16)s0[2 * g + 1];
             }
             if (has1) {
-                if (slot == 16 + g) {
+                if (slot == b1) {
                     s1[2 * g] = __builtin_fmaf(s1[2 * g], c, -mc1);
                     s1[2 * g + 1] = __builtin_fmaf(s1[2 * g + 1], c, -mc1);
                 }
-                if (slot == 17 + g) {
+                if (slot == b1 + 1) {
                     s1[2 * g] = __builtin_amdgcn_exp2f(s1[2 * g]);
                     s1[2 * g + 1] = __builtin_amdgcn_exp2f(s1[2 * g + 1]);
                 }
-                if (slot == 18 + g) {
+                if (slot == b1 + 2) {
                     sum += s1[2 * g] + s1[2 * g + 1];
                     pf1[g >> 2][2 * (g & 3)] = (__bf16)s1[2 * g];
                     pf1[g >> 2][2 * (g & 3) + 1] = (__bf16)s1[2 * g + 1];
@@ -246,7 +265,7 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[8],
         }
         SCHED_FENCE();
     };
-    static_for<32>(run_slot);  // (not a loop: one that contains inline asm is not unrolled)
+    static_for<NSLOT>(run_slot);  // (not a loop: one that contains inline asm is not unrolled)
     ws.l_run += sum;
 }
 
@@ -255,7 +274,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 {
     constexpr int NW = NWY * NWX;
     constexpr int NI = kRowGroupsPerWave;  // 1 KB load instructions per wave per tile, for K and for V each
-    static_assert(NI * NW == 16, "64 rows = 16 instructions of 4 rows");
+    static_assert(NI * NW * ROWS_PER_LOAD == TILE_KEYS, "the waves' load instructions cover the tile's 64 rows exactly");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][K tile | V tile]
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -312,12 +331,12 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         q_token = p.n_text + imin(qy, p.gridH - 1) * p.gridW + imin(qx, p.gridW - 1);
     }
 
-    // Q^T as MFMA B operand: 8 contraction steps of 16 channels; this lane supplies channels 16*s + 8*hh .. +7
-    bf16x8 qf[8];
+    // Q^T as MFMA B operand: KS contraction steps of 16 channels; this lane supplies channels 16*s + 8*hh .. +7
+    bf16x8 qf[KS];
     {
         const __bf16* qrow = Qh + (long long)q_token * D + 8 * hh;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
+        for (int s = 0; s < KS; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
     }
     const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
     const const_u64_ptr mask_tbl = (const_u64_ptr)p.mask_tbl;
@@ -360,8 +379,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         }
     };
 
-    // ---- LDS-direct staging.  Load instruction ii (0..15) of a tile covers rows 4 ii .. 4 ii + 3; lane i
-    // writes slot i % 16 of row 4 ii + i / 16 and therefore fetches logical chunk (i % 16) ^ swz(row).
+    // ---- LDS-direct staging.  Load instruction ii of a tile covers ROWS_PER_LOAD rows (4 at head_dim 128); lane i
+    // writes slot i % CHUNKS of row ROWS_PER_LOAD ii + i / CHUNKS and therefore fetches logical chunk (i % CHUNKS) ^ swz(row).
     // Addresses are clamped to valid tokens; slots beyond the range or the grid are masked in the compute.
     auto issue_tile = [&](int i, unsigned lds_tile) {
         int a, b;
@@ -369,7 +388,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
             const int ii = wave * NI + n;
-            const int row = 4 * ii + (lane >> 4);
+            const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
             int token;
             if (b < 0) {
                 token = imin(a + row, lin_limit - 1);
@@ -379,7 +398,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 const int kx = imin(b + (row & 7), p.gridW - 1);
                 token = p.n_text + ky * p.gridW + kx;
             }
-            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
+            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
             load_to_lds_16B(Kh, voff, lds_tile + ii * 1024);
             load_to_lds_16B(Vh, voff, lds_tile + TILE_BYTES + ii * 1024);
         }
@@ -394,7 +413,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
             const int ii = wave * NI + n;
-            const int row = 4 * ii + (lane >> 4);
+            const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
             int token;
             if (b < 0) {
                 token = imin(a + row, lin_limit - 1);
@@ -404,7 +423,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 const int kx = imin(b + (row & 7), p.gridW - 1);
                 token = p.n_text + ky * p.gridW + kx;
             }
-            tl.voff[n] = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
+            tl.voff[n] = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
             tl.lds[n] = lds_tile + ii * 1024;
         }
         return tl;
@@ -518,14 +537,14 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         for (int j = len; j < nx_len; ++j) issue_tile(nx + j, lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
     };
 
-    // Prologue of the block on the query row (RMS norm over the 128 channels - this lane holds 64 of them,
+    // Prologue of the block on the query row (RMS norm over the head's channels - this lane holds half of them,
     // lane ^ 32 the others -, rotary embedding for image queries, back to bf16).  Runs once, after the first
     // stage's loads have been issued, so that the wait for the row and for the tables overlaps them.
     auto query_prologue = [&]() __attribute__((always_inline)) {
     if (p.q_gain || p.rope_y) {
         float ss = 0.f;
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
+        for (int s = 0; s < KS; ++s)
 #pragma unroll
             for (int j = 0; j < 8; ++j) ss += (float)qf[s][j] * (float)qf[s][j];
         ss = wave_pair_sum(ss);
@@ -534,7 +553,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         const float* const ry = p.rope_y + (size_t)imin(qy, p.gridH - 1) * D;
         const float* const rx = p.rope_x + (size_t)imin(qx, p.gridW - 1) * D;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
+        for (int s = 0; s < KS; ++s) {
             const int c0 = 16 * s + 8 * hh;
             float x[8];
 #pragma unroll
@@ -552,7 +571,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     auto run_pass = [&](auto careful_tag) -> unsigned long long {
         constexpr bool CAREFUL = decltype(careful_tag)::value;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) ws.oacc[db][r] = 0.f;
         ws.m_run = M_INIT;
@@ -568,7 +587,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         // The Q fragments are waited for here, once, with the first tiles already on their way: otherwise the
         // wait lands inside the key loop, where it would also drain the tile prefetches.
 #pragma unroll
-        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qf[s]));
         if (!CAREFUL) query_prologue();  // the fast pass always comes first
         int buf = 0;
         if (CAREFUL) {
@@ -658,7 +677,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             // the fast pass stands only if every sum stayed finite and moderate
             float chk = ws.l_run;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) chk += __builtin_fabsf(ws.oacc[db][r]);
             bad = __builtin_amdgcn_ballot_w64(!(chk < FAST_SUM_LIMIT));
@@ -682,7 +701,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 
     const float m_run = ws.m_run;
     const float l_run = ws.l_run;
-    f32x16(&oacc)[4] = ws.oacc;
+    f32x16(&oacc)[NDB] = ws.oacc;
     // ---- epilogue
     const float l_tot = wave_pair_sum(l_run);
     if (TEXTQ) {
@@ -690,7 +709,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             const long long row = ((long long)bh * p.n_splits + split) * p.n_text + q_token;
             float* wo = p.ws_o + row * D;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     f32x4 v = {oacc[db][4 * g], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]};
@@ -702,15 +721,15 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             }
         }
     } else {
-        // The wave's 32 x 128 output tile is turned round in LDS (the stage buffers are idle by now: every wave
-        // has passed the barrier above) so that it leaves as whole 256-byte rows: a lane owns a query, and
+        // The wave's 32 x D output tile is turned round in LDS (the stage buffers are idle by now: every wave
+        // has passed the barrier above) so that it leaves as whole rows: a lane owns a query, and
         // storing from that layout would scatter 8-byte pieces over 32 rows per instruction.
         if (p.lse && q_valid && hh == 0) p.lse[(long long)bh * p.N + q_token] = __logf(l_tot) + m_run * p.scale_log2e * 0.6931471805599453f;
         constexpr int OROW = ROW_BYTES + 16;  // padded row pitch in LDS
         unsigned char* const wbase = smem + wave * (32 * OROW);
         const float inv = 1.0f / l_tot;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 bf16x4 v;
@@ -718,15 +737,15 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 for (int t = 0; t < 4; ++t) v[t] = (__bf16)(oacc[db][4 * g + t] * inv);
                 *(bf16x4*)(wbase + qi * OROW + (32 * db + 8 * g + 4 * hh) * 2) = v;
             }
-        // 16 lanes per row, 4 rows per store instruction
+        // CHUNKS lanes per row, ROWS_PER_LOAD rows per store instruction
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = 4 * i + (lane >> 4);  // query slot of the patch
+        for (int i = 0; i < 32 / ROWS_PER_LOAD; ++i) {
+            const int row = ROWS_PER_LOAD * i + lane / CHUNKS;  // query slot of the patch
             const int oy = wy0 + (row >> 3), ox = wx0 + (row & 7);
-            const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane & 15) * 16);
+            const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane % CHUNKS) * 16);
             if (oy < p.gridH && ox < p.gridW && oy >= p.own_y0 && oy < p.own_y1) {
                 __bf16* orow = (__bf16*)p.O + head_off + ((long long)p.n_text + (long long)oy * p.gridW + ox) * D;
-                *(f32x4*)(orow + (lane & 15) * 8) = chunk;
+                *(f32x4*)(orow + (lane % CHUNKS) * 8) = chunk;
             }
         }
     }
@@ -780,6 +799,7 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 
 }  // namespace
 
+#if CLEAR_HEAD_DIM == 128
 int bf16_text_queries_per_block() { return kBf16NWY * kBf16NWX * kTextQueriesPerWave; }
 
 // Lane masks of the bf16 kernels for a (4 x 8 query patch, 4 x 8 key block) pair whose origins differ by
@@ -806,7 +826,9 @@ void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long
     for (int reg = 0; reg < 16; ++reg) ones[reg] = ~0ull;
 }
 
-hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase)
+#endif  // CLEAR_HEAD_DIM == 128
+
+hipError_t launch_bf16(const FwdParams& p, hipStream_t stream, int phase)
 {
     const int BH = p.B * p.H;
     hipError_t e = hipSuccess;

@@ -45,6 +45,10 @@ WORKLOADS = {
         Workload("flux-4096-r32", 1, 24, 512, 256, 256, 128, 32, "bf16", 3),
         Workload("flux-4096-192x320-r32", 1, 24, 512, 192, 320, 128, 32, "bf16", 4),
         Workload("flux-8k-r16", 1, 24, 512, 512, 512, 128, 16, "bf16", 5, per_head_q_scale=True),
+        # head_dim 64: the geometry of an SD3.5-Large-style block (38 heads of 64 channels, 333 text tokens; the
+        # paper deploys CLEAR on that model with r = 16 but does not print its shapes)
+        Workload("sd35l-1024-r16", 1, 38, 333, 64, 64, 64, 16, "bf16", 6),
+        Workload("sd35l-4096-r16", 1, 38, 333, 256, 256, 64, 16, "bf16", 7),
     ]
 }
 
