@@ -34,7 +34,11 @@
  * are the sparse-attention variants the paper compares with, kept under the same text rule:
  * 1: square window, |dx| < r and |dy| < r (neighbourhood attention, window cut off at the border);
  * 2: Swin windows: both tokens in the same r x r cell of the partition whose origin is moved up and left
- *    by `shift` tokens.
+ *    by `shift` tokens;
+ * 3: strided attention (appendix on the compared attentions): key j is kept when its offset from the query,
+ *    taken modulo r on each axis (non-negative remainder), equals (r_x, r_y) = (l % r, (l / r) % r), where the
+ *    layer index l travels in `shift`.  Reading: the offset is key minus query, and l / r wraps modulo r for
+ *    layers beyond r^2 (the paper writes r_y = l // r and says nothing about either point).
  * A process-wide setting (set it, call the oracle, set it back): every function below goes through oracle_mask.
  */
 static int g_mask_kind = 0, g_mask_shift = 0;
@@ -52,6 +56,11 @@ int oracle_mask(int64_t i, int64_t j, int n_text, int gridH, int gridW, int r)
     if (g_mask_kind == 1) return (llabs(dx) < r && llabs(dy) < r) ? 1 : 0;
     if (g_mask_kind == 2)
         return ((yi + g_mask_shift) / r == (yj + g_mask_shift) / r && (xi + g_mask_shift) / r == (xj + g_mask_shift) / r) ? 1 : 0;
+    if (g_mask_kind == 3) {
+        int rx = g_mask_shift % r, ry = (g_mask_shift / r) % r;
+        int mx = (int)(((xj - xi) % r + r) % r), my = (int)(((yj - yi) % r + r) % r);
+        return (mx == rx && my == ry) ? 1 : 0;
+    }
     return (dx * dx + dy * dy < (int64_t)r * r) ? 1 : 0;
 }
 

@@ -55,7 +55,7 @@ def _load():
     return _lib
 
 
-MASK_DISC, MASK_SQUARE, MASK_SWIN = 0, 1, 2
+MASK_DISC, MASK_SQUARE, MASK_SWIN, MASK_STRIDED = 0, 1, 2, 3
 
 
 class mask_kind:
