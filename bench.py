@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--band", type=int, default=-1, help="which band (default: a middle one, halo on both sides)")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (dQ, dK, dV from dO and the forward pass's log-sum-exp) instead of the forward pass")
+    ap.add_argument("--mask", default="disc", choices=["disc", "square", "swin", "strided"],
+                    help="image-image mask of the forward bench: the paper's disc (default) or one of the compared local masks")
+    ap.add_argument("--shift", type=int, default=0, help="Swin: window shift (0 <= shift < r); strided: layer index")
     ap.add_argument("--prologue", action="store_true",
                     help="time the forward pass with the query/key prologue (RMS norm, rotary embedding, logit scale) fused in, "
                          "against the plain forward pass and against the prologue as two passes of their own")
@@ -77,7 +80,9 @@ def main():
     Q, K, V = make_qkv(w, dev)
     O = torch.empty_like(Q)
     dtype_code = ca.CLEAR_BF16 if w.dtype == "bf16" else ca.CLEAR_F32
-    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, dtype_code)
+    mask_kind = {"disc": ca.CLEAR_MASK_DISC, "square": ca.CLEAR_MASK_SQUARE, "swin": ca.CLEAR_MASK_SWIN,
+                 "strided": ca.CLEAR_MASK_STRIDED}[args.mask]
+    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, dtype_code, mask_kind, args.shift)
     ctx.reserve(w.B * w.H)
 
     for _ in range(args.warmup):
@@ -94,7 +99,7 @@ def main():
     phase_ms = ctx.forward_profile(Q, K, V, O, reps=max(3, args.steps))
 
     BH = w.B * w.H
-    sum_m = ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r)
+    sum_m = ca.clear_attn_mask_count_masked(w.n_text, w.gridH, w.gridW, w.r, mask_kind, args.shift)
     useful_flop = 4.0 * sum_m * w.head_dim * BH
     exec_pairs = ctx.executed_pairs()
     executed_flop = 4.0 * exec_pairs * w.head_dim * BH
@@ -109,7 +114,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(w.name, {}).get("image_query_kernel_bytes_per_launch")
+            traffic = json.load(f).get(w.name if args.mask == "disc" else "", {}).get("image_query_kernel_bytes_per_launch")
     roofline = {
         "bound": "mfma", "kernel": "clear_fwd_bf16_kernel<image queries>",
         "achieved": img_flop / (img_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -126,7 +131,8 @@ def main():
         "metric": "local-attn useful TFLOP/s (4*sumM*d)", "value": useful_tflops, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text,
+        "config": {"workload": w.name if args.mask == "disc" else "%s mask=%s shift=%d" % (w.name, args.mask, args.shift),
+                   "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text,
                    "gridH": w.gridH, "gridW": w.gridW, "r": w.r, "sum_M_per_head": sum_m},
         "useful_tflops": useful_tflops, "executed_tflops": executed_tflops,
         "useful_frac_of_mfma_peak": useful_tflops / MFMA_BF16_PEAK_TFLOPS,
@@ -144,7 +150,8 @@ def main():
         h = w.H // 2
         q, k, v = (t[0, h].float().cpu().double().numpy() for t in (Q, K, V))
         tc0 = time.perf_counter()
-        ref, _, _, cnt = orc.attention_rows(q, k, v, rows, w.n_text, w.gridH, w.gridW, w.r, return_stats=True)
+        with orc.mask_kind(mask_kind, args.shift):  # (the two sides number the mask kinds alike)
+            ref, _, _, cnt = orc.attention_rows(q, k, v, rows, w.n_text, w.gridH, w.gridW, w.r, return_stats=True)
         tc1 = time.perf_counter()
         got = O[0, h][torch.from_numpy(rows).to(dev)].float().cpu().numpy()
         diff = got - ref

@@ -129,9 +129,17 @@ int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pai
  *   CLEAR_MASK_SWIN    both tokens in the same r x r window of the partition whose origin is moved up and left
  *                      by `shift` (0 <= shift < r; the windows cut by the border are smaller); shift 0 and r/2
  *                      on alternate layers give the shifted-window scheme
- * Every other entry point takes such a context unchanged (forward, forward_band, backward, ...); the executed
- * work differs: only the disc has precomputed lane masks, the other kinds use the arithmetic element mask. */
-typedef enum { CLEAR_MASK_DISC = 0, CLEAR_MASK_SQUARE = 1, CLEAR_MASK_SWIN = 2 } clear_mask_kind;
+ *   CLEAR_MASK_STRIDED the key's offset from the query (key minus query), modulo r on each axis with a non-negative
+ *                      remainder, equals (l % r, (l / r) % r); the layer index l >= 0 is passed as `shift`.  Each
+ *                      query sees one key per r x r cell.  bf16 only, gridH >= r and gridW >= r; forward (with or
+ *                      without prologue, with or without lse) only: no row bands, no backward pass (the mask is
+ *                      not symmetric).  It runs as r*r dense problems, one per residue class (y % r, x % r) of the
+ *                      queries, with strided token addresses; the context's tile schedule (clear_attn_schedule_size /
+ *                      _copy) is that of one class, a ceil(gridH / r) x ceil(gridW / r) grid; clear_attn_schedule_
+ *                      host_masked returns CLEAR_ERR_UNSUPPORTED for it.
+ * Every other entry point takes a square or Swin context unchanged (forward, forward_band, backward, ...); the
+ * executed work differs: only the disc has precomputed lane masks, they use the arithmetic element mask. */
+typedef enum { CLEAR_MASK_DISC = 0, CLEAR_MASK_SQUARE = 1, CLEAR_MASK_SWIN = 2, CLEAR_MASK_STRIDED = 3 } clear_mask_kind;
 int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r,
                              int dtype, int mask_kind, int shift);
 /* clear_attn_schedule_host for a mask kind. */

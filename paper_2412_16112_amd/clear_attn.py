@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libclear_attn.so")
 CLEAR_OK, CLEAR_ERR_INVALID_ARG, CLEAR_ERR_UNSUPPORTED, CLEAR_ERR_ALLOC, CLEAR_ERR_HIP, CLEAR_ERR_MISMATCH = range(6)
 CLEAR_BF16, CLEAR_F32 = 0, 1
 CLEAR_MERGE_EXACT, CLEAR_MERGE_AVERAGE = 0, 1
-CLEAR_MASK_DISC, CLEAR_MASK_SQUARE, CLEAR_MASK_SWIN = 0, 1, 2
+CLEAR_MASK_DISC, CLEAR_MASK_SQUARE, CLEAR_MASK_SWIN, CLEAR_MASK_STRIDED = 0, 1, 2, 3
 CLEAR_TILE_PARTIAL, CLEAR_TILE_FULL = 0, 1
 
 EXPORTS = [

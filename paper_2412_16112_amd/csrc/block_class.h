@@ -38,7 +38,11 @@ __host__ __device__ inline int classify_image_block(int qy0, int qx0, int qh, in
 //   kMaskSquare  |dx| < r and |dy| < r                               (neighbourhood-style square window, cut off at the border)
 //   kMaskSwin    both tokens in the same r x r window of the partition whose origin is moved up and left by `shift`
 //                (shift 0: windows start at the grid origin; the paper alternates shift 0 and r / 2 between layers)
-enum MaskKind : int { kMaskDisc = 0, kMaskSquare = 1, kMaskSwin = 2 };
+//   strided      the key's offset from the query, modulo r on each axis (non-negative remainder), equals
+//                (shift % r, (shift / r) % r); shift carries the layer index.  The bf16 kernels do not test
+//                this predicate: they run one dense problem per residue class of (y % r, x % r) with strided
+//                token addresses, inside which every pair is admitted (kMaskFull).
+enum MaskKind : int { kMaskDisc = 0, kMaskSquare = 1, kMaskSwin = 2, kMaskStrided = 3, kMaskFull = 4 };
 
 struct MaskSpec {
     int kind;
@@ -52,6 +56,8 @@ __host__ __device__ inline bool mask_admits(const MaskSpec& m, int qy, int qx, i
     const int dy = qy - ky, dx = qx - kx;
     if (m.kind == kMaskSquare) return dy < m.r && -dy < m.r && dx < m.r && -dx < m.r;
     if (m.kind == kMaskSwin) return (qy + m.shift) / m.r == (ky + m.shift) / m.r && (qx + m.shift) / m.r == (kx + m.shift) / m.r;
+    if (m.kind == kMaskStrided) return ((-dx % m.r) + m.r) % m.r == m.shift % m.r && ((-dy % m.r) + m.r) % m.r == (m.shift / m.r) % m.r;
+    if (m.kind == kMaskFull) return true;
     return dx * dx + dy * dy < m.r * m.r;
 }
 
@@ -78,6 +84,14 @@ __host__ __device__ inline int classify_image_block_spec(const MaskSpec& m, int 
     const int uqy1 = (qy0 + qh - 1 + m.shift) / m.r, uqx1 = (qx0 + qw - 1 + m.shift) / m.r;
     const bool one = wqy0 == uqy1 && wky0 == wky1 && wqy0 == wky0 && wqx0 == uqx1 && wkx0 == wkx1 && wqx0 == wkx0;
     return (inside && one) ? kBlockFull : kBlockPartial;
+}
+
+// Every pair admitted (one residue class of the strided mask): the query patch lives on a qH x qW grid, the key
+// block on a kH x kW grid of its own.
+__host__ __device__ inline int classify_full_block(int qy0, int qx0, int qH, int qW, int ky0, int kx0, int kh, int kw, int kH, int kW)
+{
+    if (qy0 >= qH || qx0 >= qW || ky0 >= kH || kx0 >= kW) return kBlockSkip;
+    return (ky0 + kh <= kH && kx0 + kw <= kW) ? kBlockFull : kBlockPartial;
 }
 
 // Keys taken from a contiguous token range [.., limit): block = tokens [base, base + n).

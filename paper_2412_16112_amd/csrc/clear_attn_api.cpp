@@ -12,6 +12,7 @@
 #include <string>
 #include <vector>
 
+#include "block_class.h"
 #include "clear_internal.h"
 
 using namespace clear;
@@ -150,6 +151,8 @@ int clear_attn_schedule_host_masked(int gridH, int gridW, int r, int mask_kind, 
     if (rc == CLEAR_OK) rc = check_mask(mask_kind, r, shift, &why);
     if (rc != CLEAR_OK) return fail(nullptr, rc, why);
     if (q_tile_h < 1 || q_tile_w < 1 || k_tile_h < 1 || k_tile_w < 1) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "tile sizes must be >= 1");
+    if (mask_kind == CLEAR_MASK_STRIDED)
+        return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the strided mask has no tile schedule on the raster grid: it runs as one dense problem per residue class");
     if (!n_q_tiles || !n_pairs) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "n_q_tiles / n_pairs is NULL");
     const bool sizes_only = !row_ptr && !col_idx && !flags;
     if (!sizes_only && (!row_ptr || !col_idx || !flags)) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "row_ptr, col_idx and flags must be all NULL or all set");
@@ -171,7 +174,14 @@ int clear_attn_schedule_host_masked(int gridH, int gridW, int r, int mask_kind, 
 
 static int check_mask(int mask_kind, int r, int shift, std::string* why)
 {
-    if (mask_kind != CLEAR_MASK_DISC && mask_kind != CLEAR_MASK_SQUARE && mask_kind != CLEAR_MASK_SWIN) { *why = "mask_kind must be CLEAR_MASK_DISC, CLEAR_MASK_SQUARE or CLEAR_MASK_SWIN"; return CLEAR_ERR_INVALID_ARG; }
+    if (mask_kind != CLEAR_MASK_DISC && mask_kind != CLEAR_MASK_SQUARE && mask_kind != CLEAR_MASK_SWIN && mask_kind != CLEAR_MASK_STRIDED) {
+        *why = "mask_kind must be CLEAR_MASK_DISC, CLEAR_MASK_SQUARE, CLEAR_MASK_SWIN or CLEAR_MASK_STRIDED";
+        return CLEAR_ERR_INVALID_ARG;
+    }
+    if (mask_kind == CLEAR_MASK_STRIDED) {
+        if (shift < 0) { *why = "the layer index given as shift must be >= 0 for CLEAR_MASK_STRIDED"; return CLEAR_ERR_INVALID_ARG; }
+        return CLEAR_OK;
+    }
     if (mask_kind == CLEAR_MASK_SWIN ? (shift < 0 || shift >= r) : shift != 0) { *why = "shift must be 0, or in [0, r) for CLEAR_MASK_SWIN"; return CLEAR_ERR_INVALID_ARG; }
     return CLEAR_OK;
 }
@@ -207,6 +217,11 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
     if (dtype == CLEAR_BF16 && (long long)n_text + (long long)gridH * gridW > (1LL << 24) - 1)
         return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "bf16 kernels address one head with 32-bit byte offsets: n_text + gridH*gridW must be < 2^24");
 
+    const bool strided = mask_kind == CLEAR_MASK_STRIDED;
+    if (strided && dtype != CLEAR_BF16) return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the strided mask is built for the bf16 kernels only");
+    if (strided && (gridH < r || gridW < r))
+        return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the strided mask needs gridH >= r and gridW >= r (every residue class non-empty)");
+
     clear_attn_ctx* ctx = new (std::nothrow) clear_attn_ctx;
     if (!ctx) return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory");
     ctx->n_text = n_text; ctx->gridH = gridH; ctx->gridW = gridW;
@@ -214,8 +229,16 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
     ctx->mask_kind = mask_kind; ctx->mask_shift = shift;
     int qth, qtw, kth, ktw;
     clear_attn_tile_shape(head_dim, dtype, &qth, &qtw, &kth, &ktw);
+    // Strided: the tile lists describe one residue class, a (gridH / r) x (gridW / r) grid (rounded up) on which
+    // every query tile meets every key tile; tiles count as inside the grid only if they are so for the
+    // smallest class (extents rounded down).
+    const int schedH = strided ? (gridH + r - 1) / r : gridH, schedW = strided ? (gridW + r - 1) / r : gridW;
+    const int cutH = strided ? gridH / r : gridH, cutW = strided ? gridW / r : gridW;
     try {
-        build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &ctx->sched, mask_kind, shift);
+        if (strided)
+            build_schedule(schedH, schedW, schedH + schedW, qth, qtw, kth, ktw, &ctx->sched, CLEAR_MASK_DISC, 0);
+        else
+            build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &ctx->sched, mask_kind, shift);
     } catch (const std::bad_alloc&) {
         delete ctx;
         return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
@@ -227,7 +250,7 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
         const Schedule& sc = ctx->sched;
         auto cut = [&](int id) {
             const int ty = id / sc.n_ktx, tx = id % sc.n_ktx;
-            return (ty + 1) * sc.kth > gridH || (tx + 1) * sc.ktw > gridW;
+            return (ty + 1) * sc.kth > cutH || (tx + 1) * sc.ktw > cutW;
         };
         auto origin = [&](int id) { return ((id / sc.n_ktx) * sc.kth) << 16 | ((id % sc.n_ktx) * sc.ktw); };
         std::vector<int> plain, used;
@@ -268,14 +291,15 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
         }
     }
     std::vector<unsigned long long> mask_tbl;
-    if (dtype == CLEAR_BF16 && mask_kind == CLEAR_MASK_DISC) {  // (other masks take the arithmetic element mask)
+    if (dtype == CLEAR_BF16 && (mask_kind == CLEAR_MASK_DISC || mask_kind == CLEAR_MASK_SQUARE)) {
+        // (masks that depend on the offset between the tokens alone; Swin windows take the arithmetic element mask)
         // relative block offsets that a non-empty (patch, block) pair can have
         ctx->mask_ry = std::min((r + 2) / 4, (gridH + 3) / 4);
         ctx->mask_rx = std::min((r + 6) / 8, (gridW + 7) / 8);
         const size_t entries = (size_t)(2 * ctx->mask_ry + 1) * (2 * ctx->mask_rx + 1) + 2;
         if (entries * 128 <= (64u << 20)) {  // beyond 64 MB the kernels fall back to arithmetic masks
             try {
-                build_bf16_mask_table(r, ctx->mask_ry, ctx->mask_rx, &mask_tbl);
+                build_bf16_mask_table(r, ctx->mask_ry, ctx->mask_rx, mask_kind, &mask_tbl);
             } catch (const std::bad_alloc&) {
                 delete ctx;
                 return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the mask table");
@@ -392,6 +416,14 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.mask_ry = ctx->mask_ry;
     p.mask_rx = ctx->mask_rx;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
+    p.n_classes = 1; p.stride = 1; p.stride_rx = p.stride_ry = 0;
+    if (ctx->mask_kind == CLEAR_MASK_STRIDED) {
+        if (band) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "row bands are not built for the strided mask");
+        p.mask_kind = kMaskFull;  // inside a residue class every pair is admitted
+        p.n_classes = r * r; p.stride = r;
+        p.stride_rx = ctx->mask_shift % r; p.stride_ry = (ctx->mask_shift / r) % r;
+        if (n_q_tiles * BH * p.n_classes > 0x7fffffffLL) return fail(ctx, CLEAR_ERR_INVALID_ARG, "too many workgroups: B*H*r*r*query tiles must fit in 31 bits");
+    }
     p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     p.own_y0 = 0;
     p.own_y1 = gridH;
@@ -585,6 +617,7 @@ int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (BH < 1 || BH > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be in [1, 65535]");
     if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (ctx->mask_kind == CLEAR_MASK_STRIDED) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is not built for the strided mask (it is not symmetric)");
     if (BH <= ctx->bwd_BH) return CLEAR_OK;
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
     if (ctx->d_bwd_ws) (void)hipFree(ctx->d_bwd_ws);
@@ -617,6 +650,7 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
         return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
     if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (ctx->mask_kind == CLEAR_MASK_STRIDED) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is not built for the strided mask (it is not symmetric)");
     const long long N = (long long)n_text + (long long)gridH * gridW;
     {
         // outputs must not overlap inputs or each other
@@ -749,8 +783,10 @@ int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_i
 int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pairs_per_head)
 {
     if (!ctx || !pairs_per_head) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL argument");
-    *pairs_per_head = (ctx->dtype == CLEAR_BF16) ? executed_pairs_bf16(ctx->sched, ctx->n_text, 0)
-                                                 : executed_pairs_f32(ctx->sched, ctx->n_text);
+    if (ctx->mask_kind == CLEAR_MASK_STRIDED)
+        *pairs_per_head = executed_pairs_bf16_strided(ctx->sched, ctx->n_text, ctx->gridH, ctx->gridW, ctx->r, ctx->mask_shift);
+    else
+        *pairs_per_head = (ctx->dtype == CLEAR_BF16) ? executed_pairs_bf16(ctx->sched, ctx->n_text, 0) : executed_pairs_f32(ctx->sched, ctx->n_text);
     return CLEAR_OK;
 }
 

@@ -38,6 +38,8 @@ void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int 
 unsigned long long mask_count(int n_text, int gridH, int gridW, int r, int mask_kind = 0, int mask_shift = 0);
 // Pairs fed to the matrix pipeline per (batch, head) by the bf16 kernels (image pass + text-query pass).
 unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys);
+// The same for a strided context (s: the schedule of the class sub-grid; gridH, gridW: the real grid).
+unsigned long long executed_pairs_bf16_strided(const Schedule& s, int n_text, int gridH, int gridW, int stride, int layer);
 // Pairs visited by the fp32 path (it tests every slot of every staged tile).
 unsigned long long executed_pairs_f32(const Schedule& s, int n_text);
 
@@ -76,6 +78,10 @@ struct FwdParams {
     float* band_lse;  // ... and the natural log of the softmax denominators [B*H][n_text] here, not O's text rows
     int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift
     float* lse;       // optional [B*H][N]: natural log of every row's softmax denominator sum_j exp(q.k_j / sqrt(d))
+    // Strided mask: n_classes = stride^2 dense problems per (batch, head), one per residue class (y % stride,
+    // x % stride) of the queries; class (a, b) takes its keys from class ((a + stride_rx) % stride, (b + stride_ry)
+    // % stride).  The tile lists then describe the class sub-grid.  Otherwise n_classes = 1, stride = 1.
+    int n_classes, stride, stride_rx, stride_ry;
     // Query prologue applied while the query rows are loaded (bf16 kernels; all null: Q is used as it is).
     const float* q_gain;  // [head_dim] RMS-norm gain, or null: no normalisation
     const float* rope_y;  // [gridH][head_dim/2][2] (cos, sin) per row, or null: no rotation
@@ -90,7 +96,7 @@ hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_bf16_d64(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
-void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl);
+void build_bf16_mask_table(int r, int ry, int rx, int mask_kind, std::vector<unsigned long long>* tbl);
 int f32_text_queries_per_block();
 // Backward pass (kernels_bf16_bwd.hip).
 struct BwdParams {

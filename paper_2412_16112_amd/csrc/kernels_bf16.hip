@@ -295,6 +295,12 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         vid = xcd * q + imin(xcd, rem) + idx;
     }
     int bh, qt, split = 0;
+    // Image queries live on a qH x qW grid and their image keys on a kH x kW grid; grid point (y, x) is image
+    // token (y * stride + oy, x * stride + ox) of the raster.  Plain masks: both are the raster itself.
+    // Strided mask: the workgroup belongs to one residue class of the queries, (q_oy, q_ox) = (y % stride,
+    // x % stride), and reads the keys of the class moved by (stride_ry, stride_rx).
+    int stride = 1, q_oy = 0, q_ox = 0, k_oy = 0, k_ox = 0;
+    int qH = p.gridH, qW = p.gridW, kH = p.gridH, kW = p.gridW;
     if (TEXTQ) {
         split = vid % p.n_splits;
         const int t = vid / p.n_splits;
@@ -303,6 +309,19 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     } else {
         qt = p.qt_begin + vid % p.n_q_tiles_launch;
         bh = vid / p.n_q_tiles_launch;
+        if (p.mask_kind == kMaskFull) {
+            const int cls = bh % p.n_classes;
+            bh /= p.n_classes;
+            stride = p.stride;
+            q_oy = cls / stride;
+            q_ox = cls % stride;
+            k_oy = (q_oy + p.stride_ry) % stride;
+            k_ox = (q_ox + p.stride_rx) % stride;
+            qH = (p.gridH - q_oy + stride - 1) / stride;  // >= 1: the host requires gridH, gridW >= stride
+            qW = (p.gridW - q_ox + stride - 1) / stride;
+            kH = (p.gridH - k_oy + stride - 1) / stride;
+            kW = (p.gridW - k_ox + stride - 1) / stride;
+        }
     }
     const long long head_off = (long long)bh * p.N * D;  // elements
     const __bf16* const Qh = (const __bf16*)p.Q + head_off;
@@ -326,9 +345,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         qy = wy0 + (qi >> 3);
         qx = wx0 + (qi & 7);
         // (row-band mode: only the rows [own_y0, own_y1) carry queries; the halo rows are keys only)
-        q_valid = qy < p.gridH && qx < p.gridW && qy >= p.own_y0 && qy < p.own_y1;
-        wave_has_queries = wy0 < p.gridH && wx0 < p.gridW && wy0 < p.own_y1 && wy0 + kWaveQH > p.own_y0;
-        q_token = p.n_text + imin(qy, p.gridH - 1) * p.gridW + imin(qx, p.gridW - 1);
+        q_valid = qy < qH && qx < qW && qy >= p.own_y0 && qy < p.own_y1;
+        wave_has_queries = wy0 < qH && wx0 < qW && wy0 < p.own_y1 && wy0 + kWaveQH > p.own_y0;
+        q_token = p.n_text + (imin(qy, qH - 1) * stride + q_oy) * p.gridW + imin(qx, qW - 1) * stride + q_ox;
     }
 
     // Q^T as MFMA B operand: KS contraction steps of 16 channels; this lane supplies channels 16*s + 8*hh .. +7
@@ -360,7 +379,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         n_tiles = n_lin_tiles + (row_ptr[qt + 1] - csr_begin);
     }
     const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
-    const int cb3 = TEXTQ ? n_lin_tiles : (p.mask_tbl ? n_lin_tiles + n_plain[qt] : n_lin_tiles);
+    const bool dense_image = !TEXTQ && p.mask_kind == kMaskFull;  // strided: tiles inside the class grid need no mask
+    const int cb3 = TEXTQ ? n_lin_tiles : ((p.mask_tbl || dense_image) ? n_lin_tiles + n_plain[qt] : n_lin_tiles);
     const int cb4 = n_tiles;
     auto stage_len = [&](int t) {  // tiles in the stage that starts at tile t
         const int e = t < cb1 ? cb1 : (t < cb2 ? cb2 : (t < cb3 ? cb3 : cb4));
@@ -394,9 +414,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 token = imin(a + row, lin_limit - 1);
                 if (TEXTQ && token >= p.vkeys_text) token += p.vshift;  // position in the key list -> token
             } else {
-                const int ky = imin(a + (row >> 3), p.gridH - 1);
-                const int kx = imin(b + (row & 7), p.gridW - 1);
-                token = p.n_text + ky * p.gridW + kx;
+                const int ky = imin(a + (row >> 3), kH - 1);
+                const int kx = imin(b + (row & 7), kW - 1);
+                token = p.n_text + (ky * stride + k_oy) * p.gridW + kx * stride + k_ox;
             }
             const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
             load_to_lds_16B(Kh, voff, lds_tile + ii * 1024);
@@ -419,9 +439,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 token = imin(a + row, lin_limit - 1);
                 if (TEXTQ && token >= p.vkeys_text) token += p.vshift;
             } else {
-                const int ky = imin(a + (row >> 3), p.gridH - 1);
-                const int kx = imin(b + (row & 7), p.gridW - 1);
-                token = p.n_text + ky * p.gridW + kx;
+                const int ky = imin(a + (row >> 3), kH - 1);
+                const int kx = imin(b + (row & 7), kW - 1);
+                token = p.n_text + (ky * stride + k_oy) * p.gridW + kx * stride + k_ox;
             }
             tl.voff[n] = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
             tl.lds[n] = lds_tile + ii * 1024;
@@ -488,6 +508,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             si.cls1 = classify_linear_block(ta + 32, 32, lin_limit);
         } else if (TEXTQ) {
             si.cls0 = si.cls1 = kBlockSkip;
+        } else if (p.mask_kind == kMaskFull) {
+            si.cls0 = classify_full_block(wy0, wx0, qH, qW, ta, tb, kKeyBlockH, kKeyBlockW, kH, kW);
+            si.cls1 = classify_full_block(wy0, wx0, qH, qW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, kH, kW);
         } else {
             const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
             si.cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
@@ -497,7 +520,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         si.ma.hh = hh;
         si.ma.a = ta;                          // linear: first token of the tile; image: tile origin row
         si.ma.b = si.linear ? lin_limit : tb;  // linear: token limit;             image: tile origin col
-        si.ma.qy = qy; si.ma.qx = qx; si.ma.gridH = p.gridH; si.ma.gridW = p.gridW; si.ma.r2 = p.r2;
+        si.ma.qy = qy; si.ma.qx = qx; si.ma.gridH = kH; si.ma.gridW = kW; si.ma.r2 = p.r2;
         si.ma.kind = p.mask_kind; si.ma.r = p.mask_r; si.ma.shift = p.mask_shift;
         si.ma.row[0] = si.ma.row[1] = mask_tbl;
         if (!TEXTQ && !si.linear && p.mask_tbl) {
@@ -550,8 +573,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         ss = wave_pair_sum(ss);
         const float inv_rms = 1.0f / sqrtf(ss * (1.0f / D) + p.norm_eps);
         const bool turn = !TEXTQ && p.rope_y;
-        const float* const ry = p.rope_y + (size_t)imin(qy, p.gridH - 1) * D;
-        const float* const rx = p.rope_x + (size_t)imin(qx, p.gridW - 1) * D;
+        const float* const ry = p.rope_y + (size_t)(imin(qy, qH - 1) * stride + q_oy) * D;
+        const float* const rx = p.rope_x + (size_t)(imin(qx, qW - 1) * stride + q_ox) * D;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const int c0 = 16 * s + 8 * hh;
@@ -644,6 +667,26 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 }
             }
             t = cb2;
+            if (dense_image) {
+                // strided mask, tiles inside the class grid: every key of the tile is admitted for every query
+                for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
+                    begin_stage(buf);
+#pragma unroll 1
+                    for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
+                        const TileInfo si = tile_info(t + j, buf, j);
+                        if (wave_has_queries) fast_stage<kMaskNone, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    }
+                    adopting = wave_has_queries && still_adopting();
+                }
+                for (; t < cb3; t += TPS, buf ^= 1) {
+                    begin_stage(buf);
+#pragma unroll 1
+                    for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
+                        const TileInfo si = tile_info(t + j, buf, j);
+                        if (wave_has_queries) fast_stage<kMaskNone, false, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    }
+                }
+            }
             if (!TEXTQ) {
                 // image tiles inside the grid
                 for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
@@ -743,8 +786,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             const int row = ROWS_PER_LOAD * i + lane / CHUNKS;  // query slot of the patch
             const int oy = wy0 + (row >> 3), ox = wx0 + (row & 7);
             const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane % CHUNKS) * 16);
-            if (oy < p.gridH && ox < p.gridW && oy >= p.own_y0 && oy < p.own_y1) {
-                __bf16* orow = (__bf16*)p.O + head_off + ((long long)p.n_text + (long long)oy * p.gridW + ox) * D;
+            if (oy < qH && ox < qW && oy >= p.own_y0 && oy < p.own_y1) {
+                __bf16* orow = (__bf16*)p.O + head_off + ((long long)p.n_text + (long long)(oy * stride + q_oy) * p.gridW + ox * stride + q_ox) * D;
                 *(f32x4*)(orow + (lane % CHUNKS) * 8) = chunk;
             }
         }
@@ -805,9 +848,11 @@ int bf16_text_queries_per_block() { return kBf16NWY * kBf16NWX * kTextQueriesPer
 // Lane masks of the bf16 kernels for a (4 x 8 query patch, 4 x 8 key block) pair whose origins differ by
 // (4 dby, 8 dbx), |dby| <= ry, |dbx| <= rx: entry (dby + ry) * (2 rx + 1) + dbx + rx holds 16 words, one per
 // score register r; bit l is set iff lane l (query l % 32 of the patch, key slot 8 (r/4) + 4 (l/32) + r % 4
-// of the block) is admitted by Eq. 3, dx^2 + dy^2 < r^2.  Two more entries follow: all ones, all zeros.
-void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long>* tbl)
+// of the block) is admitted by the mask: Eq. 3, dx^2 + dy^2 < r^2, or the square window |dx| < r and |dy| < r
+// (the two kinds that depend on the offset alone).  Two more entries follow: all ones, all zeros.
+void build_bf16_mask_table(int r, int ry, int rx, int mask_kind, std::vector<unsigned long long>* tbl)
 {
+    const MaskSpec spec = {mask_kind, r, 0};
     const long long r2 = (long long)r * r;
     const int ncol = 2 * rx + 1;
     tbl->assign((size_t)((2 * ry + 1) * ncol + 2) * 16, 0ull);
@@ -819,7 +864,8 @@ void build_bf16_mask_table(int r, int ry, int rx, std::vector<unsigned long long
                     const int qi = l & 31, hh = l >> 5;
                     const long long dy = 4 * dby + (reg >> 2) - (qi >> 3);
                     const long long dx = 8 * dbx + 4 * hh + (reg & 3) - (qi & 7);
-                    if (dx * dx + dy * dy < r2) e[reg] |= 1ull << l;
+                    const bool in_reach = dx > -r && dx < r && dy > -r && dy < r;  // (also keeps the products below in range)
+                    if (in_reach && (mask_kind == kMaskDisc ? dx * dx + dy * dy < r2 : mask_admits(spec, 0, 0, (int)dy, (int)dx))) e[reg] |= 1ull << l;
                 }
         }
     unsigned long long* ones = tbl->data() + tbl->size() - 32;
@@ -833,7 +879,7 @@ hipError_t launch_bf16(const FwdParams& p, hipStream_t stream, int phase)
     const int BH = p.B * p.H;
     hipError_t e = hipSuccess;
     if (phase == kPhaseAll || phase == kPhaseImage) {
-        e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_q_tiles_launch, stream);
+        e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_classes * p.n_q_tiles_launch, stream);
         if (e != hipSuccess) return e;
     }
     if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextQuery)) {

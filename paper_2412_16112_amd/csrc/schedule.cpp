@@ -65,6 +65,16 @@ void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int 
 
 unsigned long long mask_count(int n_text, int gridH, int gridW, int r, int mask_kind, int mask_shift)
 {
+    if (mask_kind == kMaskStrided) {
+        // a query in column residue a sees the columns of residue (a + r_x) % r; rows likewise; the two axes factorise
+        const unsigned long long n_img = (unsigned long long)gridH * gridW, N = n_img + n_text;
+        const int rx = mask_shift % r, ry = (mask_shift / r) % r;
+        auto count = [&](int n, int a) -> unsigned long long { return a < n ? (unsigned long long)((n - a + r - 1) / r) : 0ull; };
+        unsigned long long sx = 0, sy = 0;
+        for (int a = 0; a < r; ++a) sx += count(gridW, a) * count(gridW, (a + rx) % r);
+        for (int b = 0; b < r; ++b) sy += count(gridH, b) * count(gridH, (b + ry) % r);
+        return (unsigned long long)n_text * N + n_img * n_text + sx * sy;
+    }
     if (mask_kind == kMaskSwin) {
         // every window of h x w tokens contributes (h w)^2 pairs; windows are the cells of the shifted partition
         const unsigned long long n_img = (unsigned long long)gridH * gridW, N = n_img + n_text;
@@ -128,6 +138,42 @@ unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_s
                 }
         }
     // text-query pass: every wave that holds at least one text query visits every 32-key block of [0, N)
+    const unsigned long long text_waves = (unsigned long long)ceil_div(n_text, kTextQueriesPerWave);
+    blocks += text_waves * 2ull * (unsigned long long)((N + kKeyTileKeys - 1) / kKeyTileKeys);
+    return blocks * 1024ull;
+}
+
+unsigned long long executed_pairs_bf16_strided(const Schedule& s, int n_text, int gridH, int gridW, int stride, int layer)
+{
+    const long long N = (long long)n_text + (long long)gridH * gridW;
+    const int rx = layer % stride, ry = (layer / stride) % stride;
+    const int n_text_tiles = ceil_div(n_text, kKeyTileKeys);
+    const int nwy = s.qth / kWaveQH, nwx = s.qtw / kWaveQW;
+    auto extent = [&](int n, int a) { return a < n ? (n - a + stride - 1) / stride : 0; };
+    unsigned long long blocks = 0;
+    for (int b = 0; b < stride; ++b)
+        for (int a = 0; a < stride; ++a) {
+            const int qH = extent(gridH, b), qW = extent(gridW, a);
+            const int kH = extent(gridH, (b + ry) % stride), kW = extent(gridW, (a + rx) % stride);
+            for (int ty = 0; ty < s.n_qty; ++ty)
+                for (int tx = 0; tx < s.n_qtx; ++tx) {
+                    const int qt = ty * s.n_qtx + tx;
+                    for (int wy = 0; wy < nwy; ++wy)
+                        for (int wx = 0; wx < nwx; ++wx) {
+                            const int y0 = ty * s.qth + wy * kWaveQH, x0 = tx * s.qtw + wx * kWaveQW;
+                            if (y0 >= qH || x0 >= qW) continue;
+                            for (int t = 0; t < n_text_tiles; ++t)
+                                blocks += 2 * (classify_linear_block((long long)t * kKeyTileKeys, 32, n_text) != kBlockSkip);
+                            for (int e = s.row_ptr[qt]; e < s.row_ptr[qt + 1]; ++e) {
+                                const int ky0 = (s.col_idx[e] / s.n_ktx) * s.kth, kx0 = (s.col_idx[e] % s.n_ktx) * s.ktw;
+                                bool any = false;
+                                for (int kb = 0; kb < 2; ++kb)
+                                    any |= classify_full_block(y0, x0, qH, qW, ky0 + kKeyBlockH * kb, kx0, kKeyBlockH, kKeyBlockW, kH, kW) != kBlockSkip;
+                                blocks += 2 * any;
+                            }
+                        }
+                }
+        }
     const unsigned long long text_waves = (unsigned long long)ceil_div(n_text, kTextQueriesPerWave);
     blocks += text_waves * 2ull * (unsigned long long)((N + kKeyTileKeys - 1) / kKeyTileKeys);
     return blocks * 1024ull;

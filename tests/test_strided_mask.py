@@ -71,3 +71,128 @@ def test_strided_attention_is_dense_attention_on_the_residue_classes():
     # text queries: everything
     ref = torch.nn.functional.scaled_dot_product_attention(torch.tensor(Q[:n_text])[None], torch.tensor(K)[None], torch.tensor(V)[None])[0].numpy()
     np.testing.assert_allclose(O[:n_text], ref, rtol=1e-12, atol=1e-12)
+
+
+# ---- the library's host side
+
+@pytest.mark.parametrize("n_text,gridH,gridW,r,layer", [(3, 8, 12, 4, 6), (0, 10, 7, 3, 5), (2, 9, 13, 5, 27), (512, 64, 64, 16, 100),
+                                                          (7, 33, 50, 16, 17)])
+def test_library_mask_count_equals_the_oracle(n_text, gridH, gridW, r, layer):
+    with orc.mask_kind(orc.MASK_STRIDED, layer):
+        ref = orc.mask_count(n_text, gridH, gridW, r)
+    assert ca.clear_attn_mask_count_masked(n_text, gridH, gridW, r, ca.CLEAR_MASK_STRIDED, layer) == ref
+
+
+def test_no_raster_schedule_for_the_strided_mask():
+    with pytest.raises(ca.ClearAttnError) as e:
+        ca.clear_attn_schedule_host_masked(32, 32, 4, ca.CLEAR_MASK_STRIDED, 0, 16, 16, 8, 8)
+    assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+
+
+# ---- GPU parity
+
+DEV = "cuda:0"
+
+
+def gpu_compare(n_text, gridH, gridW, r, layer, H=1, d=128, seed=0, B=1):
+    print(f"[case] strided n_text={n_text} grid={gridH}x{gridW} r={r} layer={layer} H={H} d={d}", flush=True)
+    Q, K, V = make_qkv_shape(B, H, n_text, gridH, gridW, d, "bf16", seed, device="cpu")
+    ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, layer)
+    try:
+        O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
+        ctx.forward(Q.to(DEV), K.to(DEV), V.to(DEV), O)
+        torch.cuda.synchronize()
+        executed = ctx.executed_pairs()
+    finally:
+        ctx.destroy()
+    with orc.mask_kind(orc.MASK_STRIDED, layer):
+        ref = orc.attention(Q, K, V, n_text, gridH, gridW, r)
+        useful = orc.mask_count(n_text, gridH, gridW, r)
+    O = O.float().cpu().numpy()
+    assert np.isfinite(O).all()  # every row written
+    mx, rms = error_metrics(O, ref)
+    assert mx <= TOL["bf16"][0] and rms <= TOL["bf16"][1], (mx, rms)
+    assert executed >= useful
+    return executed, useful
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n_text,gridH,gridW,r,layer,H,d", [
+    (8, 16, 16, 4, 0, 1, 128),       # layer 0: a query sees its own residue class
+    (37, 21, 30, 4, 6, 2, 128),      # ragged classes (extents 5/6 and 7/8), ragged text tile
+    (0, 16, 24, 8, 9, 1, 128),       # no text tokens
+    (100, 64, 64, 16, 35, 1, 128),   # the paper's ratio: 4 x 4 keys per query, class grid smaller than one tile
+    (64, 70, 45, 2, 3, 1, 128),      # class grid 35 x 23: several query tiles, border tiles
+    (5, 9, 11, 1, 0, 1, 128),        # r = 1: full attention
+    (20, 40, 40, 4, 21, 1, 128),     # layer beyond r^2: the row offset wraps
+    (37, 21, 30, 4, 6, 2, 64),       # head_dim 64
+    (333, 64, 64, 16, 35, 1, 64),
+])
+def test_gpu_forward_strided(n_text, gridH, gridW, r, layer, H, d):
+    gpu_compare(n_text, gridH, gridW, r, layer, H=H, d=d, seed=400 + gridH)
+
+
+@pytest.mark.gpu
+def test_gpu_strided_batch_of_two():
+    gpu_compare(16, 24, 24, 4, 5, H=2, d=128, seed=77, B=2)
+
+
+@pytest.mark.gpu
+def test_gpu_strided_executes_only_useful_pairs_on_an_even_shape():
+    """64 x 64 grid, r = 4: every class is a 16 x 16 grid = one query tile and four whole key tiles; 64 text tokens
+    = one whole tile: nothing is padded, so the executed pairs are exactly sum(M)."""
+    executed, useful = gpu_compare(64, 64, 64, 4, 2, seed=78)
+    assert executed == useful
+
+
+@pytest.mark.gpu
+def test_gpu_strided_with_lse_and_prologue():
+    from oracle import prologue as pro
+    from paper_2412_16112_amd.inputs import make_prologue_inputs
+    n_text, gridH, gridW, r, layer, d = 30, 26, 19, 4, 7, 128
+    Q, K, V = make_qkv_shape(1, 1, n_text, gridH, gridW, d, "bf16", seed=79, device=DEV, q_scale=2.0)
+    gq, gk, ty, tx = make_prologue_inputs(gridH, gridW, d, seed=80, device=DEV)
+    f64 = lambda t: t.detach().cpu().double().numpy()
+    ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, layer)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        Op = ctx.forward_prologue(Q, K, V, q_gain=gq, k_gain=gk, rope_y=ty, rope_x=tx, logit_scale=0.9)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    N = n_text + gridH * gridW
+    with orc.mask_kind(orc.MASK_STRIDED, layer):
+        ref, m, l, _ = orc.attention_rows(f64(Q[0, 0]), f64(K[0, 0]), f64(V[0, 0]), np.arange(N), n_text, gridH, gridW, r, return_stats=True)
+        qp = pro.qk_prologue(f64(Q[0, 0]), f64(gq), 1e-6, n_text, gridH, gridW, f64(ty), f64(tx))
+        kp = pro.qk_prologue(f64(K[0, 0]), f64(gk), 1e-6, n_text, gridH, gridW, f64(ty), f64(tx))
+        refp = orc.attention_rows(qp * 0.9, kp, f64(V[0, 0]), np.arange(N), n_text, gridH, gridW, r)
+    mx, rms = error_metrics(f64(O[0, 0]), ref)
+    assert mx <= TOL["bf16"][0] and rms <= TOL["bf16"][1], (mx, rms)
+    assert np.abs(f64(lse[0, 0]) - (m + np.log(l))).max() <= 5e-3
+    mx, rms = error_metrics(f64(Op[0, 0]), refp)
+    assert mx <= TOL["bf16"][0] and rms <= TOL["bf16"][1], (mx, rms)
+
+
+@pytest.mark.gpu
+def test_gpu_strided_unsupported_combinations():
+    with pytest.raises(ca.ClearAttnError) as e:
+        ca.ClearAttn(8, 16, 16, 64, 4, ca.CLEAR_F32, ca.CLEAR_MASK_STRIDED, 0)
+    assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+    with pytest.raises(ca.ClearAttnError) as e:
+        ca.ClearAttn(8, 3, 16, 128, 4, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, 0)
+    assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+    with pytest.raises(ca.ClearAttnError) as e:
+        ca.ClearAttn(8, 16, 16, 128, 4, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, -1)
+    assert e.value.status == ca.CLEAR_ERR_INVALID_ARG
+    Q, K, V = make_qkv_shape(1, 1, 8, 16, 16, 128, "bf16", seed=81, device=DEV)
+    ctx = ca.ClearAttn(8, 16, 16, 128, 4, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, 3)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        with pytest.raises(ca.ClearAttnError) as e:
+            ctx.backward(Q, K, V, O, O, lse)
+        assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+        with pytest.raises(ca.ClearAttnError) as e:
+            ctx.forward_band(Q, K, V, torch.empty_like(Q), 0, 16, True)
+        assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
+    finally:
+        ctx.destroy()
