@@ -306,6 +306,18 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
             }
         }
     }
+    if (dtype == CLEAR_BF16 && mask_kind == CLEAR_MASK_SWIN && r % 8 == 0 && shift % 8 == 0) {
+        // Windows whose edges fall on multiples of 8: a 4 x 8 query patch and a 4 x 8 key block each lie in one
+        // window, so inside the grid a block is either wholly admitted or out of reach.  The table then only
+        // needs its all-ones and all-zeros entries (the entry for offset (0, 0) in front of them is never used).
+        ctx->mask_ry = ctx->mask_rx = 0;
+        try {
+            build_bf16_mask_table(r, 0, 0, mask_kind, &mask_tbl);
+        } catch (const std::bad_alloc&) {
+            delete ctx;
+            return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the mask table");
+        }
+    }
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) {
         hipDeviceProp_t prop;
