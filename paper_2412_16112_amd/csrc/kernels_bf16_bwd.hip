@@ -13,20 +13,26 @@
 //   dQ    queries   K | V                    K q^T         V dO^T         dS   K^T dS
 //   dK    keys      Q | dO                   Q k^T         dO v^T         dS   Q^T dS
 //   dV    keys      Q | dO                   Q k^T         -              P    dO^T P
+//   dK+dV keys      Q | dO                   Q k^T         dO v^T         both of the above from one S (image rows)
 // lse and delta belong to the query: a per-lane scalar for dQ, a per-column vector (staged next to the tile)
 // for dK and dV.  Text rows sum over every token: they are split along the columns into partial sums that a
-// small kernel adds up, like the text-query rows of the forward pass.  Plain block-by-block code (no
-// hand-ordered pipeline): this is the first correct version of the backward pass, not a tuned one.
+// small kernel adds up, like the text-query rows of the forward pass.  dK and dV of a key tile are produced
+// by one pass from one S and one dP (the separate modes remain for reference).  Plain block-by-block code, no
+// hand-ordered pipeline.
 #include <hip/hip_runtime.h>
 
 #include "bf16_common.h"
 #include "block_class.h"
 #include "clear_internal.h"
 
+#ifndef CLEAR_BWD_FUSED_KV
+#define CLEAR_BWD_FUSED_KV 1
+#endif
+
 namespace clear {
 namespace {
 
-enum BwdMode : int { kBwdQ = 0, kBwdK = 1, kBwdV = 2 };
+enum BwdMode : int { kBwdQ = 0, kBwdK = 1, kBwdV = 2, kBwdKV = 3 };
 
 constexpr int STATS_BYTES = TILE_KEYS * 2 * 4;                           // per staged tile: lse2 and delta of its 64 columns
 constexpr int BWD_LDS_BYTES = NBUF * STAGE_BYTES + NBUF * TPS * STATS_BYTES;
@@ -204,10 +210,14 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     }
 
     f32x16 acc[4];  // gradient^T tiles: channel 32 db + 8 (reg / 4) + 4 hh + reg % 4 of this lane's row
+    f32x16 acc_v[MODE == kBwdKV ? 4 : 1];  // fused mode: acc holds dK, acc_v holds dV
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+        for (int r = 0; r < 16; ++r) {
+            acc[db][r] = 0.f;
+            if constexpr (MODE == kBwdKV) acc_v[db][r] = 0.f;
+        }
     const float c = p.scale_log2e;
 
     // One 32-column block of a staged tile.
@@ -231,13 +241,23 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
             }
         } else {
             const f32x16 dp = qk_block(t2, blk, r2f);
+            bf16x8 pf[2];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int slot = 32 * blk + 8 * (r >> 2) + 4 * hh + (r & 3);
                 const float l2 = COLSTAT ? tile_stats[slot] : lse2_row;
                 const float dl = COLSTAT ? tile_stats[TILE_KEYS + slot] : delta_row;
                 const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l2));
+                if constexpr (MODE == kBwdKV) pf[r >> 3][r & 7] = (__bf16)pr;
                 xf[r >> 3][r & 7] = (__bf16)(pr * (dp[r] - dl));
+            }
+            if constexpr (MODE == kBwdKV) {
+                // dV += dO^T P from the same probabilities (the dO tile read transposed)
+                TileAddr tv;
+                tv.kb = 0;
+                tv.vb0 = tile_lds + TILE_BYTES + lo.v0;
+                tv.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
+                pv_block(acc_v, tv, blk, pf);
             }
         }
         pv_block(acc, tt, blk, xf);
@@ -320,7 +340,8 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     const float out_scale = MODE == kBwdV ? 1.0f : p.scale;  // dQ and dK carry the 1 / sqrt(d) of the logits
     if (LINROWS) {
         // partial sums of this column split: [mode][bh][split][row][d] fp32
-        float* wo = p.ws + ((((long long)MODE * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
+        constexpr int slot0 = MODE == kBwdKV ? (int)kBwdK : MODE;
+        float* wo = p.ws + ((((long long)slot0 * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -328,8 +349,18 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
                 f32x4 v = {acc[db][4 * g] * out_scale, acc[db][4 * g + 1] * out_scale, acc[db][4 * g + 2] * out_scale, acc[db][4 * g + 3] * out_scale};
                 *(f32x4*)(wo + 32 * db + 8 * g + 4 * hh) = v;
             }
+        if constexpr (MODE == kBwdKV) {
+            float* wv = p.ws + ((((long long)kBwdV * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 v = {acc_v[db][4 * g], acc_v[db][4 * g + 1], acc_v[db][4 * g + 2], acc_v[db][4 * g + 3]};
+                    *(f32x4*)(wv + 32 * db + 8 * g + 4 * hh) = v;
+                }
+        }
     } else {
-        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdK ? p.dK : p.dV)) + head_off + (long long)r_token * D;
+        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdV ? p.dV : p.dK)) + head_off + (long long)r_token * D;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -339,6 +370,18 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
                 for (int u = 0; u < 4; ++u) v[u] = (__bf16)(acc[db][4 * g + u] * out_scale);
                 *(bf16x4*)(orow + 32 * db + 8 * g + 4 * hh) = v;
             }
+        if constexpr (MODE == kBwdKV) {
+            __bf16* vrow = (__bf16*)p.dV + head_off + (long long)r_token * D;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 v;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v[u] = (__bf16)acc_v[db][4 * g + u];
+                    *(bf16x4*)(vrow + 32 * db + 8 * g + 4 * hh) = v;
+                }
+        }
     }
 }
 
@@ -399,13 +442,21 @@ hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* d
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = launch_bwd<kBwdQ, false>(p, BH * p.n_q_tiles, stream);
+#if CLEAR_BWD_FUSED_KV
+    if (e == hipSuccess) e = launch_bwd<kBwdKV, false>(p, BH * p.n_q_tiles, stream);
+#else
     if (e == hipSuccess) e = launch_bwd<kBwdK, false>(p, BH * p.n_q_tiles, stream);
     if (e == hipSuccess) e = launch_bwd<kBwdV, false>(p, BH * p.n_q_tiles, stream);
+#endif
     if (e != hipSuccess || p.n_text == 0) return e;
     const int nlin = BH * p.n_tq_tiles * p.n_splits;
     e = launch_bwd<kBwdQ, true>(p, nlin, stream);
+#if CLEAR_BWD_FUSED_KV
+    if (e == hipSuccess) e = launch_bwd<kBwdKV, true>(p, nlin, stream);
+#else
     if (e == hipSuccess) e = launch_bwd<kBwdK, true>(p, nlin, stream);
     if (e == hipSuccess) e = launch_bwd<kBwdV, true>(p, nlin, stream);
+#endif
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(clear_bwd_reduce_kernel, dim3((unsigned)(3LL * BH * p.n_text)), dim3(D), 0, stream, p);
     return hipGetLastError();
