@@ -213,6 +213,11 @@ def bench_prologue(args, w, dev):
     sum_m = ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r)
     useful = 4.0 * sum_m * w.head_dim * w.B * w.H
     tensor_bytes = Q.numel() * 2
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(w.name + " + prologue", {}).get("qk_prologue_kernel_bytes_per_launch")
     result = {
         "metric": "local-attn forward with fused q/k prologue, useful TFLOP/s (4*sumM*d)", "value": useful / (ms_fused * 1e-3) / 1e12,
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_fused, "higher_is_better": True,
@@ -223,7 +228,7 @@ def bench_prologue(args, w, dev):
                       "one_prologue_pass": ms_pass},
         # the pass of its own is the HBM-bound kernel here: one tensor read, one written
         "roofline": {"bound": "hbm", "kernel": "qk_prologue_kernel<128>", "achieved": 2 * tensor_bytes / (ms_pass * 1e-3) / 1e9, "peak": 8000.0,
-                     "unit": "GB/s", "frac": 2 * tensor_bytes / (ms_pass * 1e-3) / 1e9 / 8000.0, "traffic": None},
+                     "unit": "GB/s", "frac": 2 * tensor_bytes / (ms_pass * 1e-3) / 1e9 / 8000.0, "traffic": traffic},
     }
     if not args.no_cpu_baseline:
         from oracle import clear_oracle as orc
