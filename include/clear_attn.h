@@ -132,8 +132,7 @@ int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pai
  *   CLEAR_MASK_STRIDED the key's offset from the query (key minus query), modulo r on each axis with a non-negative
  *                      remainder, equals (l % r, (l / r) % r); the layer index l >= 0 is passed as `shift`.  Each
  *                      query sees one key per r x r cell.  bf16 only, gridH >= r and gridW >= r; forward (with or
- *                      without prologue, with or without lse) only: no row bands, no backward pass (the mask is
- *                      not symmetric).  It runs as r*r dense problems, one per residue class (y % r, x % r) of the
+ *                      without prologue, with or without lse) and backward, no row bands.  It runs as r*r dense problems, one per residue class (y % r, x % r) of the
  *                      queries, with strided token addresses; the context's tile schedule (clear_attn_schedule_size /
  *                      _copy) is that of one class, a ceil(gridH / r) x ceil(gridW / r) grid; clear_attn_schedule_
  *                      host_masked returns CLEAR_ERR_UNSUPPORTED for it.

@@ -14,12 +14,12 @@ from . import clear_attn as ca
 _contexts = {}
 
 
-def _context(device, n_text, gridH, gridW, head_dim, r, dtype_code):
-    key = (device.index, n_text, gridH, gridW, head_dim, r, dtype_code)
+def _context(device, n_text, gridH, gridW, head_dim, r, dtype_code, mask_kind=ca.CLEAR_MASK_DISC, shift=0):
+    key = (device.index, n_text, gridH, gridW, head_dim, r, dtype_code, mask_kind, shift)
     ctx = _contexts.get(key)
     if ctx is None:
         with torch.cuda.device(device):
-            ctx = ca.ClearAttn(n_text, gridH, gridW, head_dim, r, dtype_code)
+            ctx = ca.ClearAttn(n_text, gridH, gridW, head_dim, r, dtype_code, mask_kind, shift)
         _contexts[key] = ctx
     return ctx
 
@@ -32,9 +32,9 @@ def clear_context_cache():
 
 class ClearAttentionFunction(torch.autograd.Function):
     @staticmethod
-    def forward(fctx, Q, K, V, n_text, gridH, gridW, r):
+    def forward(fctx, Q, K, V, n_text, gridH, gridW, r, mask_kind=ca.CLEAR_MASK_DISC, shift=0):
         Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
-        ctx = _context(Q.device, n_text, gridH, gridW, Q.shape[-1], r, ca._dtype_code(Q))
+        ctx = _context(Q.device, n_text, gridH, gridW, Q.shape[-1], r, ca._dtype_code(Q), mask_kind, shift)
         needs_grad = any(fctx.needs_input_grad[:3])
         with torch.cuda.device(Q.device):
             if needs_grad:
@@ -50,9 +50,10 @@ class ClearAttentionFunction(torch.autograd.Function):
         Q, K, V, O, lse = fctx.saved_tensors
         with torch.cuda.device(Q.device):
             dQ, dK, dV = fctx.clear_ctx.backward(Q, K, V, O, dO.contiguous().to(Q.dtype), lse)
-        return dQ, dK, dV, None, None, None, None
+        return dQ, dK, dV, None, None, None, None, None, None
 
 
-def clear_attention(Q, K, V, n_text, gridH, gridW, r):
-    """softmax(Q K^T / sqrt(d) under the CLEAR mask) V for [B, H, n_text + gridH*gridW, d] device tensors."""
-    return ClearAttentionFunction.apply(Q, K, V, n_text, gridH, gridW, r)
+def clear_attention(Q, K, V, n_text, gridH, gridW, r, mask_kind=ca.CLEAR_MASK_DISC, shift=0):
+    """softmax(Q K^T / sqrt(d) under the CLEAR mask) V for [B, H, n_text + gridH*gridW, d] device tensors.
+    mask_kind / shift select one of the compared local masks instead of the disc (clear_attn_create_masked)."""
+    return ClearAttentionFunction.apply(Q, K, V, n_text, gridH, gridW, r, mask_kind, shift)

@@ -629,7 +629,7 @@ int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (BH < 1 || BH > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be in [1, 65535]");
     if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
-    if (ctx->mask_kind == CLEAR_MASK_STRIDED) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is not built for the strided mask (it is not symmetric)");
+
     if (BH <= ctx->bwd_BH) return CLEAR_OK;
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
     if (ctx->d_bwd_ws) (void)hipFree(ctx->d_bwd_ws);
@@ -662,7 +662,7 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
         return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
     if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
-    if (ctx->mask_kind == CLEAR_MASK_STRIDED) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is not built for the strided mask (it is not symmetric)");
+
     const long long N = (long long)n_text + (long long)gridH * gridW;
     {
         // outputs must not overlap inputs or each other
@@ -689,6 +689,13 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     p.row_ptr = ctx->d_row_ptr; p.col_idx = ctx->d_col_idx; p.n_plain = ctx->d_n_plain; p.mask_tbl = ctx->d_mask_tbl;
     p.mask_ry = ctx->mask_ry; p.mask_rx = ctx->mask_rx;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
+    p.n_classes = 1; p.stride = 1; p.stride_rx = p.stride_ry = 0;
+    if (ctx->mask_kind == CLEAR_MASK_STRIDED) {
+        p.mask_kind = kMaskFull;  // inside a residue class every pair is admitted
+        p.n_classes = r * r; p.stride = r;
+        p.stride_rx = ctx->mask_shift % r; p.stride_ry = (ctx->mask_shift / r) % r;
+        if ((long long)p.n_q_tiles * B * H * p.n_classes > 0x7fffffffLL) return fail(ctx, CLEAR_ERR_INVALID_ARG, "too many workgroups: B*H*r*r*row tiles must fit in 31 bits");
+    }
     p.scale = (float)(1.0 / std::sqrt((double)head_dim));
     p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)head_dim));
     if (n_text > 0) {

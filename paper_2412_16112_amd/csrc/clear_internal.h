@@ -118,6 +118,7 @@ struct BwdParams {
     const unsigned long long* mask_tbl;
     int mask_ry, mask_rx;
     int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift
+    int n_classes, stride, stride_rx, stride_ry;  // strided mask, as in FwdParams (otherwise 1, 1, 0, 0)
     float scale_log2e;  // log2(e) / sqrt(head_dim)
     float scale;        // 1 / sqrt(head_dim)
     // text rows: sums over every token, split along the columns, partial sums added up afterwards

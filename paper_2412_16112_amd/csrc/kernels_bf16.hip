@@ -82,7 +82,7 @@ __device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
 // This wave's share of the staging loads of one tile: with 8 waves, 2 of the tile's 16 row groups (4 token
 // rows = 1 KB each) at head_dim 128, 1 of 8 (8 rows each) at head_dim 64, for K and for V.  Load k covers
 // row group k / 2, K for even k and V for odd k.
-constexpr int kRowGroupsPerWave = TILE_KEYS / ROWS_PER_LOAD / 8;
+constexpr int kRowGroupsPerWave = TILE_KEYS / ROWS_PER_LOAD / (kBf16NWY * kBf16NWX);
 constexpr int kTileLoads = 2 * kRowGroupsPerWave;
 struct TileLoads {
     const void* ksrc;                  // the head's K and V arrays
@@ -98,12 +98,18 @@ __device__ __forceinline__ void issue_tile_load(const TileLoads& tl, int k)
 
 __device__ __forceinline__ void issue_tile_loads(const TileLoads& tl)
 {
-    static_assert(kTileLoads == 4 || kTileLoads == 2, "written out: a loop around inline asm is not unrolled");
+    static_assert(kTileLoads == 8 || kTileLoads == 4 || kTileLoads == 2, "written out: a loop around inline asm is not unrolled");
     issue_tile_load(tl, 0);
     issue_tile_load(tl, 1);
-    if constexpr (kTileLoads == 4) {
+    if constexpr (kTileLoads >= 4) {
         issue_tile_load(tl, 2);
         issue_tile_load(tl, 3);
+    }
+    if constexpr (kTileLoads >= 8) {
+        issue_tile_load(tl, 4);
+        issue_tile_load(tl, 5);
+        issue_tile_load(tl, 6);
+        issue_tile_load(tl, 7);
     }
 }
 

@@ -71,6 +71,26 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         rt = vid % p.n_q_tiles;
         bh = vid / p.n_q_tiles;
     }
+    // Image rows live on an rH x rW grid and image columns on a cH x cW grid; grid point (y, x) is image token
+    // (y * stride + oy, x * stride + ox) of the raster.  Plain masks: both are the raster.  Strided mask: the
+    // workgroup belongs to one residue class of its rows; queries of class c meet the keys of class c + (ry, rx),
+    // so the columns of a key class are the queries of class c - (ry, rx).
+    int stride = 1, r_oy = 0, r_ox = 0, c_oy = 0, c_ox = 0;
+    int rH = p.gridH, rW = p.gridW, cH = p.gridH, cW = p.gridW;
+    if (!LINROWS && p.mask_kind == kMaskFull) {
+        const int cls = bh % p.n_classes;
+        bh /= p.n_classes;
+        stride = p.stride;
+        r_oy = cls / stride;
+        r_ox = cls % stride;
+        const int dy = MODE == kBwdQ ? p.stride_ry : stride - p.stride_ry, dx = MODE == kBwdQ ? p.stride_rx : stride - p.stride_rx;
+        c_oy = (r_oy + dy) % stride;
+        c_ox = (r_ox + dx) % stride;
+        rH = (p.gridH - r_oy + stride - 1) / stride;  // >= 1: the host requires gridH, gridW >= stride
+        rW = (p.gridW - r_ox + stride - 1) / stride;
+        cH = (p.gridH - c_oy + stride - 1) / stride;
+        cW = (p.gridW - c_ox + stride - 1) / stride;
+    }
     const long long head_off = (long long)bh * p.N * D;  // elements
     const __bf16* const R1 = (const __bf16*)(MODE == kBwdQ ? p.Q : p.K) + head_off;
     const __bf16* const R2 = (const __bf16*)(MODE == kBwdQ ? p.dO : p.V) + head_off;
@@ -94,9 +114,9 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         wx0 = (rt % p.n_qtx) * (NWX * kWaveQW) + (wave % NWX) * kWaveQW;
         ry = wy0 + (qi >> 3);
         rx = wx0 + (qi & 7);
-        r_valid = ry < p.gridH && rx < p.gridW;
-        wave_has_rows = wy0 < p.gridH && wx0 < p.gridW;
-        r_token = p.n_text + imin(ry, p.gridH - 1) * p.gridW + imin(rx, p.gridW - 1);
+        r_valid = ry < rH && rx < rW;
+        wave_has_rows = wy0 < rH && wx0 < rW;
+        r_token = p.n_text + (imin(ry, rH - 1) * stride + r_oy) * p.gridW + imin(rx, rW - 1) * stride + r_ox;
     }
     // B operands: 8 contraction steps of 16 channels, this lane supplying channels 16 s + 8 hh .. + 7
     bf16x8 r1f[8], r2f[8];
@@ -139,7 +159,8 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         n_tiles = n_lin_tiles + (row_ptr[rt + 1] - csr_begin);
     }
     const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
-    const int cb3 = LINROWS ? n_lin_tiles : (p.mask_tbl ? n_lin_tiles + n_plain[rt] : n_lin_tiles);
+    const bool dense_image = !LINROWS && p.mask_kind == kMaskFull;  // strided: tiles inside the class grid need no mask
+    const int cb3 = LINROWS ? n_lin_tiles : ((p.mask_tbl || dense_image) ? n_lin_tiles + n_plain[rt] : n_lin_tiles);
     const int cb4 = n_tiles;
     auto stage_len = [&](int t) {
         const int e = t < cb1 ? cb1 : (t < cb2 ? cb2 : (t < cb3 ? cb3 : cb4));
@@ -157,9 +178,9 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     };
     auto slot_token = [&](int a, int b, int slot) {  // token staged in slot `slot` (0..63) of the tile with origin (a, b)
         if (b < 0) return imin(a + slot, lin_limit - 1);
-        const int ky = imin(a + (slot >> 3), p.gridH - 1);
-        const int kx = imin(b + (slot & 7), p.gridW - 1);
-        return p.n_text + ky * p.gridW + kx;
+        const int ky = imin(a + (slot >> 3), cH - 1);
+        const int kx = imin(b + (slot & 7), cW - 1);
+        return p.n_text + (ky * stride + c_oy) * p.gridW + kx * stride + c_ox;
     };
 
     // ---- staging: LDS-direct loads of the two column tiles (same layout and swizzle as K and V in the
@@ -286,6 +307,9 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         } else if (linear) {
             cls0 = classify_linear_block(ta, 32, lin_limit);
             cls1 = classify_linear_block(ta + 32, 32, lin_limit);
+        } else if (p.mask_kind == kMaskFull) {
+            cls0 = classify_full_block(wy0, wx0, rH, rW, ta, tb, kKeyBlockH, kKeyBlockW, cH, cW);
+            cls1 = classify_full_block(wy0, wx0, rH, rW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, cH, cW);
         } else {
             const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
             cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
@@ -295,7 +319,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         ma.hh = hh;
         ma.a = ta;
         ma.b = linear ? lin_limit : tb;
-        ma.qy = ry; ma.qx = rx; ma.gridH = p.gridH; ma.gridW = p.gridW; ma.r2 = p.r2;
+        ma.qy = ry; ma.qx = rx; ma.gridH = cH; ma.gridW = cW; ma.r2 = p.r2;
         ma.kind = p.mask_kind; ma.r = p.mask_r; ma.shift = p.mask_shift;
         ma.row[0] = ma.row[1] = mask_tbl;
         if (!LINROWS && !linear && p.mask_tbl) {
@@ -331,6 +355,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     run_category(std::integral_constant<int, kMaskNone>{}, t, cb1, buf);
     run_category(std::integral_constant<int, kMaskLinear>{}, t, cb2, buf);
     if (!LINROWS) {
+        if (dense_image) run_category(std::integral_constant<int, kMaskNone>{}, t, cb3, buf);
         run_category(std::integral_constant<int, kMaskTable>{}, t, cb3, buf);
         run_category(std::integral_constant<int, kMaskImage>{}, t, cb4, buf);
     }
@@ -441,12 +466,13 @@ hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* d
     hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = launch_bwd<kBwdQ, false>(p, BH * p.n_q_tiles, stream);
+    const int nimg = BH * p.n_classes * p.n_q_tiles;
+    e = launch_bwd<kBwdQ, false>(p, nimg, stream);
 #if CLEAR_BWD_FUSED_KV
-    if (e == hipSuccess) e = launch_bwd<kBwdKV, false>(p, BH * p.n_q_tiles, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdKV, false>(p, nimg, stream);
 #else
-    if (e == hipSuccess) e = launch_bwd<kBwdK, false>(p, BH * p.n_q_tiles, stream);
-    if (e == hipSuccess) e = launch_bwd<kBwdV, false>(p, BH * p.n_q_tiles, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdK, false>(p, nimg, stream);
+    if (e == hipSuccess) e = launch_bwd<kBwdV, false>(p, nimg, stream);
 #endif
     if (e != hipSuccess || p.n_text == 0) return e;
     const int nlin = BH * p.n_tq_tiles * p.n_splits;

@@ -187,12 +187,62 @@ def test_gpu_strided_unsupported_combinations():
     Q, K, V = make_qkv_shape(1, 1, 8, 16, 16, 128, "bf16", seed=81, device=DEV)
     ctx = ca.ClearAttn(8, 16, 16, 128, 4, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, 3)
     try:
-        O, lse = ctx.forward_lse(Q, K, V)
-        with pytest.raises(ca.ClearAttnError) as e:
-            ctx.backward(Q, K, V, O, O, lse)
-        assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
         with pytest.raises(ca.ClearAttnError) as e:
             ctx.forward_band(Q, K, V, torch.empty_like(Q), 0, 16, True)
         assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
     finally:
         ctx.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n_text,gridH,gridW,r,layer", [
+    (37, 21, 30, 4, 6),     # ragged classes; the key class differs from the query class on both axes
+    (8, 16, 16, 4, 0),      # layer 0: query class = key class
+    (0, 16, 24, 8, 9),      # no text tokens
+    (64, 70, 45, 2, 3),     # several row tiles per class, border tiles
+    (20, 40, 40, 4, 21),    # layer beyond r^2
+])
+def test_gpu_backward_strided(n_text, gridH, gridW, r, layer):
+    """The mask is not symmetric: a key's queries are those of the class moved back by (r_y, r_x)."""
+    d = 128
+    Q, K, V = make_qkv_shape(1, 1, n_text, gridH, gridW, d, "bf16", seed=500 + gridH, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(501)
+    dO = torch.randn(Q.shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16, ca.CLEAR_MASK_STRIDED, layer)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        dQ = dK = dV = None
+        dQ, dK, dV = ctx.backward(Q, K, V, O, dO, lse)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    q, k, v, go = (t[0, 0].float().cpu().numpy() for t in (Q, K, V, dO))
+    with orc.mask_kind(orc.MASK_STRIDED, layer):
+        rQ, rK, rV = orc.backward(q, k, v, go, n_text, gridH, gridW, r)
+    for name, got, ref in (("dQ", dQ, rQ), ("dK", dK, rK), ("dV", dV, rV)):
+        got = got[0, 0].float().cpu().numpy()
+        assert np.isfinite(got).all()
+        max_abs, rel_rms = error_metrics(got, ref)
+        assert max_abs <= TOL["bf16"][0] * np.abs(ref).max() and rel_rms <= TOL["bf16"][1], (name, max_abs, rel_rms)
+
+
+@pytest.mark.gpu
+def test_gpu_autograd_with_a_mask_kind():
+    from paper_2412_16112_amd.autograd import clear_attention, clear_context_cache
+    n_text, gridH, gridW, r, layer, d = 16, 24, 24, 4, 5, 128
+    Q, K, V = make_qkv_shape(1, 1, n_text, gridH, gridW, d, "bf16", seed=510, device=DEV)
+    Q.requires_grad_(True); K.requires_grad_(True); V.requires_grad_(True)
+    g = torch.Generator(device=DEV).manual_seed(511)
+    dO = torch.randn(Q.shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    try:
+        O = clear_attention(Q, K, V, n_text, gridH, gridW, r, ca.CLEAR_MASK_STRIDED, layer)
+        O.backward(dO)
+        torch.cuda.synchronize()
+    finally:
+        clear_context_cache()
+    q, k, v, go = (t[0, 0].detach().float().cpu().numpy() for t in (Q, K, V, dO))
+    with orc.mask_kind(orc.MASK_STRIDED, layer):
+        rQ, rK, rV = orc.backward(q, k, v, go, n_text, gridH, gridW, r)
+    for got, ref in ((Q.grad, rQ), (K.grad, rK), (V.grad, rV)):
+        max_abs, rel_rms = error_metrics(got[0, 0].float().cpu().numpy(), ref)
+        assert max_abs <= TOL["bf16"][0] * np.abs(ref).max() and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
