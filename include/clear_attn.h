@@ -181,7 +181,7 @@ int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int
 
 /* ---- Training: forward with the softmax statistics, and the backward pass (the attention layers are the
  * trained parameters of the distillation of Sec. 3.3; the gradients follow from differentiating Eq. 1
- * under the mask of Eq. 3).  bf16 with head_dim 128 only.
+ * under the mask of Eq. 3).  bf16 only (head_dim 128 or 64).
  *
  * clear_attn_forward_lse: clear_attn_forward that also writes, for every row, the natural logarithm of its
  * softmax denominator sum_j exp(q_i.k_j / sqrt(head_dim)) over the attended keys to lse (device, fp32,

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libclear_attn.so")
-SOURCES = ["clear_attn_api.cpp", "schedule.cpp", "kernels_bf16.hip", "kernels_bf16_d64.hip", "kernels_f32.hip", "mfma_peak.hip", "band_merge.hip", "kernels_bf16_bwd.hip", "prologue.hip"]
+SOURCES = ["clear_attn_api.cpp", "schedule.cpp", "kernels_bf16.hip", "kernels_bf16_d64.hip", "kernels_f32.hip", "mfma_peak.hip", "band_merge.hip", "kernels_bf16_bwd.hip", "kernels_bf16_bwd_d64.hip", "prologue.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-fp32 instructions

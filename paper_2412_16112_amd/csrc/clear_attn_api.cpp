@@ -628,7 +628,7 @@ int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (BH < 1 || BH > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "BH must be in [1, 65535]");
-    if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 only");
 
     if (BH <= ctx->bwd_BH) return CLEAR_OK;
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
@@ -661,7 +661,7 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     if (B < 1 || H < 1 || (long long)B * H > 65535) return fail(ctx, CLEAR_ERR_INVALID_ARG, "B, H must be >= 1 and B*H <= 65535");
     if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
         return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
-    if (ctx->dtype != CLEAR_BF16 || ctx->head_dim != 128) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 with head_dim 128 only");
+    if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 only");
 
     const long long N = (long long)n_text + (long long)gridH * gridW;
     {
@@ -704,7 +704,8 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
         choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
         p.ws = ctx->d_bwd_ws;
     }
-    hipError_t e = launch_bf16_d128_backward(p, O, ctx->d_bwd_delta, (hipStream_t)stream);
+    hipError_t e = ctx->head_dim == 128 ? launch_bf16_d128_backward(p, O, ctx->d_bwd_delta, (hipStream_t)stream)
+                                        : launch_bf16_d64_backward(p, O, ctx->d_bwd_delta, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("backward launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }

@@ -126,6 +126,7 @@ struct BwdParams {
     float* ws;  // [3 (dQ, dK, dV)][B*H][n_splits][n_text][head_dim]
 };
 hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream);
+hipError_t launch_bf16_d64_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream);
 
 // band_merge.hip: combination of the text-query outputs of several row bands.
 constexpr int kMaxMergeParts = 64;

@@ -1,4 +1,5 @@
-// Backward pass of the CLEAR local attention for gfx950 (bf16, head_dim 128): dQ, dK, dV of Eq. 1 under the
+// Backward pass of the CLEAR local attention for gfx950 (bf16, head_dim 128; kernels_bf16_bwd_d64.hip compiles
+// this file a second time for head_dim 64): dQ, dK, dV of Eq. 1 under the
 // mask of Eq. 3, given dO and the per-row log-sum-exp the forward pass can return.  With
 //   s_ij = q_i.k_j / sqrt(d),  p_ij = exp(s_ij - lse_i) for M_ij = 1 (else 0),  delta_i = dO_i . O_i,
 //   dp_ij = dO_i . v_j,        ds_ij = p_ij (dp_ij - delta_i):
@@ -29,6 +30,16 @@
 #define CLEAR_BWD_FUSED_KV 1
 #endif
 
+#if CLEAR_HEAD_DIM == 64
+// second compilation of this file: its own kernel and launcher names
+#define clear_bwd_bf16_kernel clear_bwd_bf16_d64_kernel
+#define clear_bwd_delta_kernel clear_bwd_delta_d64_kernel
+#define clear_bwd_reduce_kernel clear_bwd_reduce_d64_kernel
+#define launch_bf16_backward launch_bf16_d64_backward
+#else
+#define launch_bf16_backward launch_bf16_d128_backward
+#endif
+
 namespace clear {
 namespace {
 
@@ -41,7 +52,7 @@ template <int MODE, bool LINROWS>
 __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams p)
 {
     constexpr int NWY = kBf16NWY, NWX = kBf16NWX, NW = NWY * NWX;
-    constexpr int NI = 16 / NW;
+    constexpr int NI = TILE_KEYS / ROWS_PER_LOAD / NW;  // 1 KB load instructions per wave per tile, for each of the two tiles
     constexpr bool COLSTAT = MODE != kBwdQ;  // lse / delta indexed by column
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][C1 tile | C2 tile], then the column statistics
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -118,10 +129,10 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         wave_has_rows = wy0 < rH && wx0 < rW;
         r_token = p.n_text + (imin(ry, rH - 1) * stride + r_oy) * p.gridW + imin(rx, rW - 1) * stride + r_ox;
     }
-    // B operands: 8 contraction steps of 16 channels, this lane supplying channels 16 s + 8 hh .. + 7
-    bf16x8 r1f[8], r2f[8];
+    // B operands: KS contraction steps of 16 channels, this lane supplying channels 16 s + 8 hh .. + 7
+    bf16x8 r1f[KS], r2f[KS];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < KS; ++s) {
         r1f[s] = *(const bf16x8*)(R1 + (long long)r_token * D + 8 * hh + 16 * s);
         if (MODE != kBwdV) r2f[s] = *(const bf16x8*)(R2 + (long long)r_token * D + 8 * hh + 16 * s);
     }
@@ -133,7 +144,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         delta_row = delta[r_token];
     }
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < KS; ++s) {
         asm volatile("" : "+v"(r1f[s]));
         if (MODE != kBwdV) asm volatile("" : "+v"(r2f[s]));
     }
@@ -192,9 +203,9 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
             const int ii = wave * NI + n;
-            const int row = 4 * ii + (lane >> 4);
+            const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
             const int token = slot_token(a, b, row);
-            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane & 15) ^ swz(row)) << 4);
+            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
             load_to_lds_16B(C1, voff, lds_tile + ii * 1024);
             load_to_lds_16B(C2, voff, lds_tile + TILE_BYTES + ii * 1024);
         }
@@ -230,10 +241,10 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         lo.v0 = (unsigned)(row * ROW_BYTES + ((chunk ^ swz(row)) << 4) + 8 * (j & 1));
     }
 
-    f32x16 acc[4];  // gradient^T tiles: channel 32 db + 8 (reg / 4) + 4 hh + reg % 4 of this lane's row
-    f32x16 acc_v[MODE == kBwdKV ? 4 : 1];  // fused mode: acc holds dK, acc_v holds dV
+    f32x16 acc[NDB];  // gradient^T tiles: channel 32 db + 8 (reg / 4) + 4 hh + reg % 4 of this lane's row
+    f32x16 acc_v[MODE == kBwdKV ? NDB : 1];  // fused mode: acc holds dK, acc_v holds dV
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             acc[db][r] = 0.f;
@@ -368,7 +379,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         constexpr int slot0 = MODE == kBwdKV ? (int)kBwdK : MODE;
         float* wo = p.ws + ((((long long)slot0 * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[db][4 * g] * out_scale, acc[db][4 * g + 1] * out_scale, acc[db][4 * g + 2] * out_scale, acc[db][4 * g + 3] * out_scale};
@@ -377,7 +388,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         if constexpr (MODE == kBwdKV) {
             float* wv = p.ws + ((((long long)kBwdV * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     f32x4 v = {acc_v[db][4 * g], acc_v[db][4 * g + 1], acc_v[db][4 * g + 2], acc_v[db][4 * g + 3]};
@@ -387,7 +398,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     } else {
         __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdV ? p.dV : p.dK)) + head_off + (long long)r_token * D;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 bf16x4 v;
@@ -398,7 +409,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         if constexpr (MODE == kBwdKV) {
             __bf16* vrow = (__bf16*)p.dV + head_off + (long long)r_token * D;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     bf16x4 v;
@@ -410,11 +421,11 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     }
 }
 
-// delta_i = dO_i . O_i for every row: 16 lanes per row (8 channels = 16 bytes each), 16 rows per workgroup.
+// delta_i = dO_i . O_i for every row: D / 8 lanes per row (8 channels = 16 bytes each).
 __global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, const __bf16* dO, float* delta, long long rows)
 {
-    const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int part = threadIdx.x & 15;
+    const long long row = (long long)blockIdx.x * (256 / CHUNKS) + threadIdx.x / CHUNKS;
+    const int part = threadIdx.x % CHUNKS;
     float s = 0.f;
     if (row < rows) {
         const bf16x8 o = *(const bf16x8*)(O + row * D + 8 * part);
@@ -423,7 +434,7 @@ __global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, c
         for (int j = 0; j < 8; ++j) s += (float)o[j] * (float)g[j];
     }
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    for (int off = CHUNKS / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (row < rows && part == 0) delta[row] = s;
 }
 
@@ -459,11 +470,12 @@ hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream)
+hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream)
 {
     const int BH = p.B * p.H;
     const long long rows = (long long)BH * p.N;
-    hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
+    constexpr int rows_per_block = 256 / CHUNKS;
+    hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int nimg = BH * p.n_classes * p.n_q_tiles;

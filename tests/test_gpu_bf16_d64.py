@@ -86,9 +86,6 @@ def test_lse_and_bands_and_prologue_at_d64():
         O, lse = ctx.forward_lse(Q, K, V)
         Op = ctx.forward_prologue(Q, K, V, q_gain=gq, k_gain=gk, rope_y=ty, rope_x=tx, logit_scale=1.2)
         torch.cuda.synchronize()
-        with pytest.raises(ca.ClearAttnError) as e:
-            ctx.backward(Q, K, V, O, O, lse)
-        assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
     finally:
         ctx.destroy()
     N = n_text + gh * gw
@@ -132,3 +129,32 @@ def test_sd35l_1024_sampled():
 
 def test_sd35l_4096_sampled():
     sampled("sd35l-4096-r16", [0, 37], 1024, 64)
+
+
+@pytest.mark.parametrize("n_text,gh,gw,r,H,kind,shift", [
+    (37, 40, 24, 8, 2, ca.CLEAR_MASK_DISC, 0),
+    (0, 33, 17, 9, 1, ca.CLEAR_MASK_DISC, 0),
+    (333, 48, 48, 16, 1, ca.CLEAR_MASK_DISC, 0),
+    (21, 37, 29, 8, 1, ca.CLEAR_MASK_SWIN, 4),
+    (37, 21, 30, 4, 1, ca.CLEAR_MASK_STRIDED, 6),
+])
+def test_backward_at_d64(n_text, gh, gw, r, H, kind, shift):
+    Q, K, V = make_qkv_shape(1, H, n_text, gh, gw, 64, "bf16", seed=600 + gh, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(601)
+    dO = torch.randn(Q.shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    ctx = ca.ClearAttn(n_text, gh, gw, 64, r, ca.CLEAR_BF16, kind, shift)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        dQ, dK, dV = ctx.backward(Q, K, V, O, dO, lse)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    for h in range(H):
+        q, k, v, go = (t[0, h].float().cpu().numpy() for t in (Q, K, V, dO))
+        with orc.mask_kind(kind, shift):
+            rQ, rK, rV = orc.backward(q, k, v, go, n_text, gh, gw, r)
+        for name, got, ref in (("dQ", dQ, rQ), ("dK", dK, rK), ("dV", dV, rV)):
+            got = got[0, h].float().cpu().numpy()
+            assert np.isfinite(got).all()
+            mx, rms = error_metrics(got, ref)
+            assert mx <= TOL["bf16"][0] * np.abs(ref).max() and rms <= TOL["bf16"][1], (name, h, mx, rms)
