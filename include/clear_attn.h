@@ -23,6 +23,10 @@
  * rejected before any device work.  clear_attn_last_error gives a human-readable reason.
  * Thread safety: a context may be used by one thread at a time; distinct contexts are independent.
  * All functions run on the current HIP device; a context belongs to the device current at create.
+ * Streams: work is enqueued on the stream passed in and is complete when that stream has reached the end of
+ * the call's work.  For small problems a forward call also uses a stream the context owns (default priority),
+ * forked from and joined to the caller's stream with events, so that independent kernels of the call overlap;
+ * nothing of this is visible to the caller beyond the order on its own stream.
  */
 #ifndef CLEAR_ATTN_H
 #define CLEAR_ATTN_H
