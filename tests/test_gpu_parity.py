@@ -194,3 +194,24 @@ def test_flux_4096_nonsquare_sampled():
 
 def test_flux_8k_r16_sampled():
     _sampled_workload_check("flux-8k-r16", [0, 12, 23], 2048, 48)
+
+
+def test_small_problem_on_a_side_stream_back_to_back():
+    """Small problems fork their text-query kernels onto a stream the context owns.  Three calls in a row on a
+    caller's side stream, each with its own inputs and output, synchronising that stream only: every output
+    must be complete and correct (the calls share the context's text-query workspace)."""
+    n_text, gh, gw, d, r, H = 96, 32, 40, 128, 8, 2
+    ctx = ca.ClearAttn(n_text, gh, gw, d, r, ca.CLEAR_BF16)
+    side = torch.cuda.Stream(device=DEV)
+    ins = [make_qkv_shape(1, H, n_text, gh, gw, d, "bf16", seed=900 + i, device=DEV) for i in range(3)]
+    torch.cuda.synchronize()
+    try:
+        with torch.cuda.stream(side):
+            outs = [ctx.forward(Q, K, V, stream=side.cuda_stream) for Q, K, V in ins]
+        side.synchronize()
+    finally:
+        ctx.destroy()
+    for (Q, K, V), O in zip(ins, outs):
+        ref = orc.attention(Q, K, V, n_text, gh, gw, r)
+        max_abs, rel_rms = error_metrics(O.float().cpu().numpy(), ref)
+        assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
