@@ -481,6 +481,15 @@ static hipError_t launch(const clear_attn_ctx* ctx, const FwdParams& p, hipStrea
     return launch_f32_d64(p, stream, phase);
 }
 
+static hipError_t ensure_aux_stream(clear_attn_ctx* ctx)
+{
+    if (ctx->aux_stream) return hipSuccess;
+    hipError_t e = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
+    return e;
+}
+
 // A whole forward pass.  The image-query rows and the text-query rows are independent (they read Q, K, V and
 // write disjoint rows of O).  When the image-query kernel has fewer than a few workgroups per CU - small images -
 // its rounds leave CUs idle, so the text-query kernel and its merge run beside it on a second stream, forked
@@ -492,13 +501,8 @@ static hipError_t launch_all(clear_attn_ctx* ctx, const FwdParams& p, hipStream_
     const long long image_wgs = (long long)p.B * p.H * p.n_classes * p.n_q_tiles_launch;
     const bool beside = ctx->dtype == CLEAR_BF16 && p.n_text > 0 && image_wgs <= 8LL * ctx->num_cus;
     if (!beside) return launch(ctx, p, stream, kPhaseAll);
-    hipError_t e = hipSuccess;
-    if (!ctx->aux_stream) {
-        e = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
-        if (e != hipSuccess) return e;
-    }
+    hipError_t e = ensure_aux_stream(ctx);
+    if (e != hipSuccess) return e;
     e = hipEventRecord(ctx->ev_fork, stream);
     if (e == hipSuccess) e = hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0);
     if (e == hipSuccess) e = launch(ctx, p, ctx->aux_stream, kPhaseTextQuery);
@@ -736,8 +740,29 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
         choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
         p.ws = ctx->d_bwd_ws;
     }
-    hipError_t e = ctx->head_dim == 128 ? launch_bf16_d128_backward(p, O, ctx->d_bwd_delta, (hipStream_t)stream)
-                                        : launch_bf16_d64_backward(p, O, ctx->d_bwd_delta, (hipStream_t)stream);
+    auto run = [&](hipStream_t st, int phase) {
+        return ctx->head_dim == 128 ? launch_bf16_d128_backward(p, O, ctx->d_bwd_delta, st, phase) : launch_bf16_d64_backward(p, O, ctx->d_bwd_delta, st, phase);
+    };
+    hipError_t e = hipSuccess;
+    const long long image_wgs = (long long)BH * p.n_classes * p.n_q_tiles;
+    if (image_wgs > 8LL * ctx->num_cus) {
+        e = run((hipStream_t)stream, kBwdPhaseAll);
+    } else {
+        // Small problems (the 1024 x 1024 training shape): the dQ kernels and the dK/dV kernels are independent and
+        // each leaves CUs idle in its last round, so they run side by side on two streams (as in the forward pass).
+        hipStream_t st = (hipStream_t)stream;
+        e = ensure_aux_stream(ctx);
+        if (e == hipSuccess) e = run(st, kBwdPhaseDelta);
+        if (e == hipSuccess) e = hipEventRecord(ctx->ev_fork, st);
+        if (e == hipSuccess) e = hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0);
+        if (e == hipSuccess) e = run(ctx->aux_stream, kBwdPhaseImageKV);
+        if (e == hipSuccess) e = run(st, kBwdPhaseImageQ);
+        if (e == hipSuccess) e = run(ctx->aux_stream, kBwdPhaseTextQ);
+        if (e == hipSuccess) e = run(st, kBwdPhaseTextKV);
+        if (e == hipSuccess) e = hipEventRecord(ctx->ev_join, ctx->aux_stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(st, ctx->ev_join, 0);
+        if (e == hipSuccess) e = run(st, kBwdPhaseReduce);
+    }
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("backward launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }

@@ -125,8 +125,11 @@ struct BwdParams {
     int n_tq_tiles, n_splits, split_keys;
     float* ws;  // [3 (dQ, dK, dV)][B*H][n_splits][n_text][head_dim]
 };
-hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream);
-hipError_t launch_bf16_d64_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream);
+// phase: kBwdPhaseAll, or one kernel of the pass: delta first; the image-row and text-row kernels are independent
+// of each other; the reduction of the text-row partial sums comes after the two text-row kernels.
+enum BwdPhase : int { kBwdPhaseAll = -1, kBwdPhaseDelta = 0, kBwdPhaseImageQ = 1, kBwdPhaseImageKV = 2, kBwdPhaseTextQ = 3, kBwdPhaseTextKV = 4, kBwdPhaseReduce = 5 };
+hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream, int phase);
+hipError_t launch_bf16_d64_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream, int phase);
 
 // band_merge.hip: combination of the text-query outputs of several row bands.
 constexpr int kMaxMergeParts = 64;

@@ -470,34 +470,43 @@ hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream)
+hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream, int phase)
 {
     const int BH = p.B * p.H;
-    const long long rows = (long long)BH * p.N;
-    constexpr int rows_per_block = 256 / CHUNKS;
-    hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const bool all = phase == kBwdPhaseAll;
+    hipError_t e = hipSuccess;
+    if (all || phase == kBwdPhaseDelta) {
+        const long long rows = (long long)BH * p.N;
+        constexpr int rows_per_block = 256 / CHUNKS;
+        hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
+        e = hipGetLastError();
+    }
     const int nimg = BH * p.n_classes * p.n_q_tiles;
-    e = launch_bwd<kBwdQ, false>(p, nimg, stream);
+    if (e == hipSuccess && (all || phase == kBwdPhaseImageQ)) e = launch_bwd<kBwdQ, false>(p, nimg, stream);
+    if (e == hipSuccess && (all || phase == kBwdPhaseImageKV)) {
 #if CLEAR_BWD_FUSED_KV
-    if (e == hipSuccess) e = launch_bwd<kBwdKV, false>(p, nimg, stream);
+        e = launch_bwd<kBwdKV, false>(p, nimg, stream);
 #else
-    if (e == hipSuccess) e = launch_bwd<kBwdK, false>(p, nimg, stream);
-    if (e == hipSuccess) e = launch_bwd<kBwdV, false>(p, nimg, stream);
+        e = launch_bwd<kBwdK, false>(p, nimg, stream);
+        if (e == hipSuccess) e = launch_bwd<kBwdV, false>(p, nimg, stream);
 #endif
+    }
     if (e != hipSuccess || p.n_text == 0) return e;
     const int nlin = BH * p.n_tq_tiles * p.n_splits;
-    e = launch_bwd<kBwdQ, true>(p, nlin, stream);
+    if (all || phase == kBwdPhaseTextQ) e = launch_bwd<kBwdQ, true>(p, nlin, stream);
+    if (e == hipSuccess && (all || phase == kBwdPhaseTextKV)) {
 #if CLEAR_BWD_FUSED_KV
-    if (e == hipSuccess) e = launch_bwd<kBwdKV, true>(p, nlin, stream);
+        e = launch_bwd<kBwdKV, true>(p, nlin, stream);
 #else
-    if (e == hipSuccess) e = launch_bwd<kBwdK, true>(p, nlin, stream);
-    if (e == hipSuccess) e = launch_bwd<kBwdV, true>(p, nlin, stream);
+        e = launch_bwd<kBwdK, true>(p, nlin, stream);
+        if (e == hipSuccess) e = launch_bwd<kBwdV, true>(p, nlin, stream);
 #endif
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(clear_bwd_reduce_kernel, dim3((unsigned)(3LL * BH * p.n_text)), dim3(D), 0, stream, p);
-    return hipGetLastError();
+    }
+    if (e == hipSuccess && (all || phase == kBwdPhaseReduce)) {
+        hipLaunchKernelGGL(clear_bwd_reduce_kernel, dim3((unsigned)(3LL * BH * p.n_text)), dim3(D), 0, stream, p);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace clear
