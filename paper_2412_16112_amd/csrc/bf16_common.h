@@ -149,6 +149,15 @@ __device__ __forceinline__ TileAddr tile_addr(unsigned tile_lds, const LaneOffse
 
 enum MaskMode : int { kMaskNone = 0, kMaskLinear = 1, kMaskImage = 2, kMaskTable = 3 };
 
+// Which family of image masks a kernel instance is compiled for.  The disc of Eq. 3 is the product path and
+// gets a kernel of its own, so that the code of the compared masks (integer divisions per element for the
+// Swin windows, strided token addresses) neither lengthens it nor shares its instruction cache.
+enum MaskCode : int { kCodeDisc = 0, kCodeGeneric = 1, kCodeFull = 2 };
+__host__ __device__ constexpr int mask_code_of(int mask_kind)
+{
+    return mask_kind == kMaskDisc ? kCodeDisc : (mask_kind == kMaskFull ? kCodeFull : kCodeGeneric);
+}
+
 // Read-only tables (tile lists, lane masks) are addressed through the constant address space so that
 // they are fetched with scalar loads: wave-uniform, and not counted among the vector loads whose
 // completion the tile prefetch waits on.
@@ -164,7 +173,7 @@ struct MaskArgs {
 
 // Sets the scores of inadmissible (query, key) pairs of key block kb to -inf.  Register r of this lane
 // is key slot 8*(r/4) + 4*hh + r%4 of the block (Eq. 3 for image keys; the token limit for linear tiles).
-template <int MASK>
+template <int MASK, int CODE>
 __device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma)
 {
     if (MASK == kMaskTable) {
@@ -177,14 +186,14 @@ __device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             if (base + 8 * (r >> 2) + (r & 3) >= ma.b) s[r] = -INFINITY;
-    } else if (MASK == kMaskImage && ma.kind != kMaskDisc) {
-        // the other local masks, element by element
+    } else if (MASK == kMaskImage && CODE != kCodeDisc) {
+        // the other local masks, element by element (kCodeFull: only the grid's edge)
         const MaskSpec spec = {ma.kind, ma.r, ma.shift};
         const int ky0 = ma.a + kKeyBlockH * kb, kx0 = ma.b + 4 * ma.hh;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int ky = ky0 + (e >> 2), kx = kx0 + (e & 3);
-            const bool keep = ky < ma.gridH && kx < ma.gridW && mask_admits(spec, ma.qy, ma.qx, ky, kx);
+            const bool keep = ky < ma.gridH && kx < ma.gridW && (CODE == kCodeFull || mask_admits(spec, ma.qy, ma.qx, ky, kx));
             s[e] = keep ? s[e] : -INFINITY;
         }
     } else if (MASK == kMaskImage) {

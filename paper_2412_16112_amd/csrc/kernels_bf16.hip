@@ -38,6 +38,7 @@ namespace {
 
 // Careful pass, one staged tile: block by block, exact running maximum, O and the denominator rescaled
 // at every block (Eq. 1 as a textbook online softmax).  Slow; only runs when the fast pass gave up.
+template <int CODE>
 __device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[KS], const LaneOffsets& lo, unsigned tile_lds,
                                               int cls0, int cls1, bool linear, const MaskArgs& ma)
 {
@@ -49,9 +50,9 @@ __device__ __forceinline__ void careful_stage(WaveState& ws, const bf16x8 (&qf)[
         f32x16 s = qk_block(ta, kb, qf);
         if (cls == kBlockPartial) {
             if (linear)
-                apply_mask<kMaskLinear>(s, kb, ma);
+                apply_mask<kMaskLinear, CODE>(s, kb, ma);
             else
-                apply_mask<kMaskImage>(s, kb, ma);
+                apply_mask<kMaskImage, CODE>(s, kb, ma);
         }
         const float m_new = fmaxf(ws.m_run, wave_pair_max(max_block(s)));
         const float alpha = __builtin_amdgcn_exp2f((ws.m_run - m_new) * ws.c);
@@ -144,7 +145,7 @@ __device__ __forceinline__ void static_for(F& f)
 // pipeline, one every other slot from slot 1 on, instead of in a burst right after the barrier, when every
 // wave of the workgroup would be issuing loads and no matrix instruction.  No branch inside the pipeline:
 // all four always go out.
-template <int MASK, bool ADOPT, bool RIDE>
+template <int MASK, bool ADOPT, bool RIDE, int CODE>
 __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS], const LaneOffsets& lo,
                                            unsigned tile_lds, const MaskArgs& ma, const TileLoads& tl)
 {
@@ -208,7 +209,7 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS]
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s0[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s0[r] : -INFINITY;
             } else {
-                apply_mask<MASK>(s0, kb0, ma);
+                apply_mask<MASK, CODE>(s0, kb0, ma);
             }
             if (ADOPT) {
                 adopt_reference(ws, wave_pair_max(max_block(s0)));
@@ -224,7 +225,7 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS]
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s1[r] = __builtin_amdgcn_inverse_ballot_w64(mw[r]) ? s1[r] : -INFINITY;
             } else {
-                apply_mask<MASK>(s1, kb0 + 1, ma);
+                apply_mask<MASK, CODE>(s1, kb0 + 1, ma);
             }
             if (ADOPT) {
                 adopt_reference(ws, wave_pair_max(max_block(s1)));
@@ -275,7 +276,7 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS]
     ws.l_run += sum;
 }
 
-template <int NWY, int NWX, bool TEXTQ>
+template <int NWY, int NWX, bool TEXTQ, int CODE>
 __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
 {
     constexpr int NW = NWY * NWX;
@@ -315,7 +316,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     } else {
         qt = p.qt_begin + vid % p.n_q_tiles_launch;
         bh = vid / p.n_q_tiles_launch;
-        if (p.mask_kind == kMaskFull) {
+        if (CODE == kCodeFull) {
             const int cls = bh % p.n_classes;
             bh /= p.n_classes;
             stride = p.stride;
@@ -385,7 +386,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         n_tiles = n_lin_tiles + (row_ptr[qt + 1] - csr_begin);
     }
     const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
-    const bool dense_image = !TEXTQ && p.mask_kind == kMaskFull;  // strided: tiles inside the class grid need no mask
+    constexpr bool dense_image = !TEXTQ && CODE == kCodeFull;  // strided: tiles inside the class grid need no mask
     const int cb3 = TEXTQ ? n_lin_tiles : ((p.mask_tbl || dense_image) ? n_lin_tiles + n_plain[qt] : n_lin_tiles);
     const int cb4 = n_tiles;
     auto stage_len = [&](int t) {  // tiles in the stage that starts at tile t
@@ -514,9 +515,12 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             si.cls1 = classify_linear_block(ta + 32, 32, lin_limit);
         } else if (TEXTQ) {
             si.cls0 = si.cls1 = kBlockSkip;
-        } else if (p.mask_kind == kMaskFull) {
+        } else if (CODE == kCodeFull) {
             si.cls0 = classify_full_block(wy0, wx0, qH, qW, ta, tb, kKeyBlockH, kKeyBlockW, kH, kW);
             si.cls1 = classify_full_block(wy0, wx0, qH, qW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, kH, kW);
+        } else if (CODE == kCodeDisc) {
+            si.cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+            si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
         } else {
             const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
             si.cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
@@ -558,7 +562,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             const TileInfo si = tile_info(t + j, buf, j);
             const TileLoads tl = plan_tile(imin(nx + j, n_tiles - 1), lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
             if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip)
-                fast_stage<MASK, false, true>(ws, qf, lo, si.tile_lds, si.ma, tl);
+                fast_stage<MASK, false, true, CODE>(ws, qf, lo, si.tile_lds, si.ma, tl);
             else
                 issue_tile_loads(tl);
         }
@@ -625,7 +629,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 const int len = stage_len(t);
                 for (int j = 0; j < len; ++j) {
                     const TileInfo si = tile_info(t + j, buf, j);
-                    careful_stage(ws, qf, lo, si.tile_lds, si.cls0, si.cls1, si.linear, si.ma);
+                    careful_stage<CODE>(ws, qf, lo, si.tile_lds, si.cls0, si.cls1, si.linear, si.ma);
                 }
                 t += len;
                 buf ^= 1;
@@ -644,7 +648,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                 for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
                     const TileInfo si = tile_info(t + j, buf, j);
-                    if (wave_has_queries) fast_stage<kMaskNone, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    if (wave_has_queries) fast_stage<kMaskNone, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                 }
                 adopting = wave_has_queries && still_adopting();
             }
@@ -658,7 +662,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (wave_has_queries) fast_stage<kMaskNone, false, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (wave_has_queries) fast_stage<kMaskNone, false, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                 }
             }
@@ -668,19 +672,19 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 begin_stage(buf);
                 const TileInfo si = tile_info(t, buf, 0);
                 if (si.cls0 != kBlockSkip) {
-                    fast_stage<kMaskLinear, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    fast_stage<kMaskLinear, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     adopting = still_adopting();
                 }
             }
             t = cb2;
-            if (dense_image) {
+            if constexpr (dense_image) {
                 // strided mask, tiles inside the class grid: every key of the tile is admitted for every query
                 for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (wave_has_queries) fast_stage<kMaskNone, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (wave_has_queries) fast_stage<kMaskNone, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
@@ -689,18 +693,19 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (wave_has_queries) fast_stage<kMaskNone, false, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (wave_has_queries) fast_stage<kMaskNone, false, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                 }
             }
             if (!TEXTQ) {
-                // image tiles inside the grid
+                // image tiles inside the grid (lane masks from the table); the strided variant has run them above
+                if constexpr (CODE != kCodeFull) {
                 for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
@@ -709,8 +714,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
+                }
                 }
                 t = cb3;
                 // image tiles cut by the border: few, keep them simple
@@ -719,7 +725,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb4 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true, false>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
                     }
                 }
             }
@@ -831,11 +837,11 @@ __global__ void __launch_bounds__(128) clear_text_merge_kernel(const FwdParams p
     }
 }
 
-template <int NWY, int NWX, bool TEXTQ>
+template <int NWY, int NWX, bool TEXTQ, int CODE>
 hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 {
     const size_t smem = (size_t)NBUF * STAGE_BYTES;
-    auto kern = clear_fwd_bf16_kernel<NWY, NWX, TEXTQ>;
+    auto kern = clear_fwd_bf16_kernel<NWY, NWX, TEXTQ, CODE>;
     static bool attr_set = false;  // the attribute is per function, set once per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -885,11 +891,15 @@ hipError_t launch_bf16(const FwdParams& p, hipStream_t stream, int phase)
     const int BH = p.B * p.H;
     hipError_t e = hipSuccess;
     if (phase == kPhaseAll || phase == kPhaseImage) {
-        e = launch_fwd<kBf16NWY, kBf16NWX, false>(p, BH * p.n_classes * p.n_q_tiles_launch, stream);
+        const int nblk = BH * p.n_classes * p.n_q_tiles_launch;
+        const int code = mask_code_of(p.mask_kind);  // one kernel per family of image masks
+        e = code == kCodeDisc   ? launch_fwd<kBf16NWY, kBf16NWX, false, kCodeDisc>(p, nblk, stream)
+            : code == kCodeFull ? launch_fwd<kBf16NWY, kBf16NWX, false, kCodeFull>(p, nblk, stream)
+                                : launch_fwd<kBf16NWY, kBf16NWX, false, kCodeGeneric>(p, nblk, stream);
         if (e != hipSuccess) return e;
     }
     if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextQuery)) {
-        e = launch_fwd<kBf16NWY, kBf16NWX, true>(p, BH * p.n_tq_tiles * p.n_splits, stream);
+        e = launch_fwd<kBf16NWY, kBf16NWX, true, kCodeDisc>(p, BH * p.n_tq_tiles * p.n_splits, stream);
         if (e != hipSuccess) return e;
     }
     if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextMerge)) {

@@ -48,7 +48,7 @@ enum BwdMode : int { kBwdQ = 0, kBwdK = 1, kBwdV = 2, kBwdKV = 3 };
 constexpr int STATS_BYTES = TILE_KEYS * 2 * 4;                           // per staged tile: lse2 and delta of its 64 columns
 constexpr int BWD_LDS_BYTES = NBUF * STAGE_BYTES + NBUF * TPS * STATS_BYTES;
 
-template <int MODE, bool LINROWS>
+template <int MODE, bool LINROWS, int CODE>
 __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams p)
 {
     constexpr int NWY = kBf16NWY, NWX = kBf16NWX, NW = NWY * NWX;
@@ -88,7 +88,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     // so the columns of a key class are the queries of class c - (ry, rx).
     int stride = 1, r_oy = 0, r_ox = 0, c_oy = 0, c_ox = 0;
     int rH = p.gridH, rW = p.gridW, cH = p.gridH, cW = p.gridW;
-    if (!LINROWS && p.mask_kind == kMaskFull) {
+    if (!LINROWS && CODE == kCodeFull) {
         const int cls = bh % p.n_classes;
         bh /= p.n_classes;
         stride = p.stride;
@@ -170,7 +170,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         n_tiles = n_lin_tiles + (row_ptr[rt + 1] - csr_begin);
     }
     const int cb1 = (lin_limit - lin_begin) / TILE_KEYS, cb2 = n_lin_tiles;
-    const bool dense_image = !LINROWS && p.mask_kind == kMaskFull;  // strided: tiles inside the class grid need no mask
+    constexpr bool dense_image = !LINROWS && CODE == kCodeFull;  // strided: tiles inside the class grid need no mask
     const int cb3 = LINROWS ? n_lin_tiles : ((p.mask_tbl || dense_image) ? n_lin_tiles + n_plain[rt] : n_lin_tiles);
     const int cb4 = n_tiles;
     auto stage_len = [&](int t) {
@@ -263,7 +263,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         tt.vb1 = tbase + (lo.v0 ^ V_HI);
         t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = 0;
         f32x16 s = qk_block(t1, blk, r1f);
-        apply_mask<MASK>(s, blk, ma);
+        apply_mask<MASK, CODE>(s, blk, ma);
         bf16x8 xf[2];
         if (MODE == kBwdV) {
 #pragma unroll
@@ -318,9 +318,12 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         } else if (linear) {
             cls0 = classify_linear_block(ta, 32, lin_limit);
             cls1 = classify_linear_block(ta + 32, 32, lin_limit);
-        } else if (p.mask_kind == kMaskFull) {
+        } else if (CODE == kCodeFull) {
             cls0 = classify_full_block(wy0, wx0, rH, rW, ta, tb, kKeyBlockH, kKeyBlockW, cH, cW);
             cls1 = classify_full_block(wy0, wx0, rH, rW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, cH, cW);
+        } else if (CODE == kCodeDisc) {
+            cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+            cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
         } else {
             const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
             cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
@@ -366,8 +369,10 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     run_category(std::integral_constant<int, kMaskNone>{}, t, cb1, buf);
     run_category(std::integral_constant<int, kMaskLinear>{}, t, cb2, buf);
     if (!LINROWS) {
-        if (dense_image) run_category(std::integral_constant<int, kMaskNone>{}, t, cb3, buf);
-        run_category(std::integral_constant<int, kMaskTable>{}, t, cb3, buf);
+        if constexpr (dense_image)
+            run_category(std::integral_constant<int, kMaskNone>{}, t, cb3, buf);
+        else
+            run_category(std::integral_constant<int, kMaskTable>{}, t, cb3, buf);
         run_category(std::integral_constant<int, kMaskImage>{}, t, cb4, buf);
     }
 
@@ -454,10 +459,10 @@ __global__ void __launch_bounds__(D) clear_bwd_reduce_kernel(const BwdParams p)
     out[((long long)bh * p.N + q) * D + ch] = (__bf16)s;
 }
 
-template <int MODE, bool LINROWS>
-hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
+template <int MODE, bool LINROWS, int CODE>
+hipError_t launch_bwd_code(const BwdParams& p, int nblk, hipStream_t stream)
 {
-    auto kern = clear_bwd_bf16_kernel<MODE, LINROWS>;
+    auto kern = clear_bwd_bf16_kernel<MODE, LINROWS, CODE>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BYTES);
@@ -466,6 +471,17 @@ hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
     }
     hipLaunchKernelGGL(kern, dim3(nblk), dim3(512), BWD_LDS_BYTES, stream, p);
     return hipGetLastError();
+}
+
+// One kernel per family of image masks for the image rows; text rows meet every token and need none.
+template <int MODE, bool LINROWS>
+hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
+{
+    if (LINROWS) return launch_bwd_code<MODE, LINROWS, kCodeDisc>(p, nblk, stream);
+    const int code = mask_code_of(p.mask_kind);
+    return code == kCodeDisc   ? launch_bwd_code<MODE, LINROWS, kCodeDisc>(p, nblk, stream)
+           : code == kCodeFull ? launch_bwd_code<MODE, LINROWS, kCodeFull>(p, nblk, stream)
+                               : launch_bwd_code<MODE, LINROWS, kCodeGeneric>(p, nblk, stream);
 }
 
 }  // namespace
