@@ -187,13 +187,19 @@ __device__ __forceinline__ void apply_mask(f32x16& s, int kb, const MaskArgs& ma
         for (int r = 0; r < 16; ++r)
             if (base + 8 * (r >> 2) + (r & 3) >= ma.b) s[r] = -INFINITY;
     } else if (MASK == kMaskImage && CODE != kCodeDisc) {
-        // the other local masks, element by element (kCodeFull: only the grid's edge)
-        const MaskSpec spec = {ma.kind, ma.r, ma.shift};
+        // The other local masks.  Square and Swin windows are products of a row condition and a column condition:
+        // 4 + 4 tests per block instead of 16 pair tests (kCodeFull: only the grid's edge).
         const int ky0 = ma.a + kKeyBlockH * kb, kx0 = ma.b + 4 * ma.hh;
+        bool row_ok[4], col_ok[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int ky = ky0 + g, kx = kx0 + g;
+            row_ok[g] = ky < ma.gridH && (CODE == kCodeFull || axis_admits(ma.kind, ma.r, ma.shift, ma.qy, ky));
+            col_ok[g] = kx < ma.gridW && (CODE == kCodeFull || axis_admits(ma.kind, ma.r, ma.shift, ma.qx, kx));
+        }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int ky = ky0 + (e >> 2), kx = kx0 + (e & 3);
-            const bool keep = ky < ma.gridH && kx < ma.gridW && (CODE == kCodeFull || mask_admits(spec, ma.qy, ma.qx, ky, kx));
+            const bool keep = row_ok[e >> 2] && col_ok[e & 3];
             s[e] = keep ? s[e] : -INFINITY;
         }
     } else if (MASK == kMaskImage) {

@@ -61,6 +61,13 @@ __host__ __device__ inline bool mask_admits(const MaskSpec& m, int qy, int qx, i
     return dx * dx + dy * dy < m.r * m.r;
 }
 
+// Square and Swin windows factor into one condition per axis: mask_admits = axis_admits(rows) && axis_admits(columns).
+__host__ __device__ inline bool axis_admits(int kind, int r, int shift, int q, int k)
+{
+    if (kind == kMaskSwin) return (q + shift) / r == (k + shift) / r;
+    return q - k < r && k - q < r;  // square window
+}
+
 // classify_image_block for any mask kind (same meaning of skip / full / partial).
 __host__ __device__ inline int classify_image_block_spec(const MaskSpec& m, int qy0, int qx0, int qh, int qw, int ky0, int kx0,
                                                          int kh, int kw, int gridH, int gridW)
