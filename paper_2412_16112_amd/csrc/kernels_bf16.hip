@@ -809,12 +809,13 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 // Combines the key-split partial results of the text-query rows: with m the largest running
 // maximum, O = sum_i 2^{(m_i - m) c} O_i / sum_i 2^{(m_i - m) c} l_i.
 template <typename OutT>
-__global__ void __launch_bounds__(128) clear_text_merge_kernel(const FwdParams p, int d)
+__global__ void __launch_bounds__(256) clear_text_merge_kernel(const FwdParams p, int d)
 {
-    const int row = blockIdx.x;  // bh * n_text + q
+    // 256 / d text rows per workgroup, one thread per channel
+    const int row = blockIdx.x * (256 / d) + threadIdx.x / d;  // bh * n_text + q
+    if (row >= p.B * p.H * p.n_text) return;
     const int bh = row / p.n_text, q = row % p.n_text;
-    const int ch = threadIdx.x;
-    if (ch >= d) return;
+    const int ch = threadIdx.x % d;
     float m = -INFINITY;
     for (int s = 0; s < p.n_splits; ++s) {
         const long long r = ((long long)bh * p.n_splits + s) * p.n_text + q;
@@ -903,7 +904,8 @@ hipError_t launch_bf16(const FwdParams& p, hipStream_t stream, int phase)
         if (e != hipSuccess) return e;
     }
     if (p.n_text > 0 && (phase == kPhaseAll || phase == kPhaseTextMerge)) {
-        hipLaunchKernelGGL(clear_text_merge_kernel<__bf16>, dim3(BH * p.n_text), dim3(128), 0, stream, p, D);
+        constexpr int rows_per_block = 256 / D;
+        hipLaunchKernelGGL(clear_text_merge_kernel<__bf16>, dim3((BH * p.n_text + rows_per_block - 1) / rows_per_block), dim3(256), 0, stream, p, D);
         e = hipGetLastError();
     }
     return e;
