@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--mask", default="disc", choices=["disc", "square", "swin", "strided"],
                     help="image-image mask of the forward bench: the paper's disc (default) or one of the compared local masks")
     ap.add_argument("--shift", type=int, default=0, help="Swin: window shift (0 <= shift < r); strided: layer index")
+    ap.add_argument("--layout", default="bhnd", choices=["bhnd", "bnhd"],
+                    help="storage of Q, K, V, O in the forward bench: [B, H, N, d] (default) or [B, N, H, d] passed with strides "
+                         "(what a projection produces; no transposing copy)")
     ap.add_argument("--prologue", action="store_true",
                     help="time the forward pass with the query/key prologue (RMS norm, rotary embedding, logit scale) fused in, "
                          "against the plain forward pass and against the prologue as two passes of their own")
@@ -85,15 +88,24 @@ def main():
     ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, dtype_code, mask_kind, args.shift)
     ctx.reserve(w.B * w.H)
 
+    if args.layout == "bnhd":
+        # the same values stored token-major; the library gets [B, H, N, d] views and their strides
+        Qs, Ks, Vs = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (Q, K, V))
+        Os = torch.empty_like(Qs.permute(0, 2, 1, 3)).permute(0, 2, 1, 3)
+        step = lambda: ctx.forward_strided(Qs, Ks, Vs, Os)
+    else:
+        step = lambda: ctx.forward(Q, K, V, O)
     for _ in range(args.warmup):
-        ctx.forward(Q, K, V, O)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.forward(Q, K, V, O)
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if args.layout == "bnhd":
+        O.copy_(Os)  # for the check against the oracle below
 
     # per-kernel durations, HIP events on the launch stream
     phase_ms = ctx.forward_profile(Q, K, V, O, reps=max(3, args.steps))
@@ -131,7 +143,8 @@ def main():
         "metric": "local-attn useful TFLOP/s (4*sumM*d)", "value": useful_tflops, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name if args.mask == "disc" else "%s mask=%s shift=%d" % (w.name, args.mask, args.shift),
+        "config": {"workload": (w.name if args.mask == "disc" else "%s mask=%s shift=%d" % (w.name, args.mask, args.shift))
+                               + ("" if args.layout == "bhnd" else " layout=[B,N,H,d]"),
                    "B": w.B, "H": w.H, "head_dim": w.head_dim, "n_text": w.n_text,
                    "gridH": w.gridH, "gridW": w.gridW, "r": w.r, "sum_M_per_head": sum_m},
         "useful_tflops": useful_tflops, "executed_tflops": executed_tflops,

@@ -183,6 +183,23 @@ int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int
                            const float* gain, float norm_eps, const float* rope_y, const float* rope_x,
                            void* stream);
 
+/* ---- Tensors in another layout.  Callers that cannot spare a transposing copy - Q, K, V straight out of a
+ * projection as [B, N, H, head_dim], or slices of one packed [B, N, 3, H, head_dim] tensor, and O wanted the same
+ * way - pass strides: `strides` points at 12 values, (batch, head, token) strides in elements for Q, K, V, O in this
+ * order; element (b, h, n, c) of a tensor is at base + b*sb + h*sh + n*sn + c (channels contiguous).  bf16 contexts
+ * only.  Every stride must be a multiple of 8 elements (base pointers 16-byte aligned as before), the token stride
+ * >= head_dim, the others >= 0 (an input may repeat over heads or batch; O's must be > 0); K and V are addressed
+ * with 32-bit byte offsets inside a head, so N * token stride * 2 must stay below 2^32; O's address range must not
+ * overlap an input's.  Same results, bit for bit, as the plain layout.  The log-sum-exp, row-band and backward
+ * entry points take the plain layout only. */
+int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
+                               const long long* strides, int B, int H, int n_text, int gridH, int gridW, int head_dim,
+                               int r, void* stream);
+int clear_attn_forward_prologue_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
+                                        const long long* strides, int B, int H, int n_text, int gridH, int gridW,
+                                        int head_dim, int r, const float* q_gain, const float* k_gain, float norm_eps,
+                                        const float* rope_y, const float* rope_x, float logit_scale, void* stream);
+
 /* ---- Training: forward with the softmax statistics, and the backward pass (the attention layers are the
  * trained parameters of the distillation of Sec. 3.3; the gradients follow from differentiating Eq. 1
  * under the mask of Eq. 3).  bf16 only (head_dim 128 or 64).

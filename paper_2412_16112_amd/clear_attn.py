@@ -23,6 +23,7 @@ EXPORTS = [
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
     "clear_attn_measure_mfma_peak", "clear_attn_last_error",
     "clear_attn_forward_prologue", "clear_attn_reserve_prologue", "clear_attn_qk_prologue",
+    "clear_attn_forward_strided", "clear_attn_forward_prologue_strided",
 ]
 
 _lib = None
@@ -70,6 +71,8 @@ def lib():
         L.clear_attn_forward_prologue.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp, vp, f, vp, vp, f, vp]
         L.clear_attn_reserve_prologue.argtypes = [vp, i]
         L.clear_attn_qk_prologue.argtypes = [vp, vp, i, i, i, i, i, i, vp, f, vp, vp, vp]
+        L.clear_attn_forward_strided.argtypes = [vp, vp, vp, vp, vp, llp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_forward_prologue_strided.argtypes = [vp, vp, vp, vp, vp, llp, i, i, i, i, i, i, i, vp, vp, f, vp, vp, f, vp]
         L.clear_attn_last_error.argtypes = [vp]
         L.clear_attn_last_error.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -195,6 +198,36 @@ class ClearAttn:
         _check(lib().clear_attn_forward_prologue(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, n_text, gridH, gridW,
                                                  head_dim, r, ptr(q_gain), ptr(k_gain), norm_eps, ptr(rope_y), ptr(rope_x), logit_scale,
                                                  ctypes.c_void_p(s)), self._ctx)
+        return O
+
+    def forward_strided(self, Q, K, V, O=None, stream=None, q_gain=None, k_gain=None, norm_eps=1e-6, rope_y=None, rope_x=None,
+                        logit_scale=None):
+        """clear_attn_forward_strided (or, with any prologue argument, clear_attn_forward_prologue_strided): Q, K, V, O are
+        [B, H, N, head_dim] views with any batch / head / token strides and contiguous channels, e.g. transposed views
+        of [B, N, H, head_dim] tensors or slices of a packed QKV tensor.  O defaults to a new tensor laid out like Q."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        if O is None:
+            O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+        for t in (Q, K, V, O):
+            if not (t.is_cuda and t.shape == Q.shape and t.dtype == Q.dtype and t.stride(3) == 1):
+                raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be device tensors of one shape and dtype with contiguous channels")
+        strides = (ctypes.c_longlong * 12)(*[t.stride(k) for t in (Q, K, V, O) for k in (0, 1, 2)])
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        prologue = any(x is not None for x in (q_gain, k_gain, rope_y, rope_x, logit_scale))
+        if prologue:
+            _check_prologue_tables(Q.device, head_dim, gridH, gridW, (q_gain, k_gain), rope_y, rope_x)
+            ptr = lambda t: None if t is None else t.data_ptr()
+            _check(lib().clear_attn_forward_prologue_strided(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), strides, B, H,
+                                                             n_text, gridH, gridW, head_dim, r, ptr(q_gain), ptr(k_gain), norm_eps, ptr(rope_y),
+                                                             ptr(rope_x), 1.0 if logit_scale is None else logit_scale, ctypes.c_void_p(s)),
+                   self._ctx)
+        else:
+            _check(lib().clear_attn_forward_strided(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), strides, B, H,
+                                                    n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
 
     def forward_lse(self, Q, K, V, O=None, lse=None, stream=None):

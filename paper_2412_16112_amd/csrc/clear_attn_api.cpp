@@ -386,7 +386,8 @@ struct BandArgs {
 };
 
 static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
-                           int n_text, int gridH, int gridW, int head_dim, int r, const BandArgs* band, FwdParams* out)
+                           int n_text, int gridH, int gridW, int head_dim, int r, const BandArgs* band, FwdParams* out,
+                           const long long* strides = nullptr)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (!Q || !K || !V || !O) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be non-NULL");
@@ -396,13 +397,32 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     if (n_text != ctx->n_text || gridH != ctx->gridH || gridW != ctx->gridW || head_dim != ctx->head_dim || r != ctx->r)
         return fail(ctx, CLEAR_ERR_MISMATCH, "shape arguments differ from those given to clear_attn_create");
     const long long N = (long long)n_text + (long long)gridH * gridW;
+    TensorStrides ts[4];  // Q, K, V, O
+    for (int t = 0; t < 4; ++t) {
+        ts[t].sn = strides ? strides[3 * t + 2] : head_dim;
+        ts[t].sh = strides ? strides[3 * t + 1] : N * head_dim;
+        ts[t].sb = strides ? strides[3 * t] : (long long)H * N * head_dim;
+    }
+    if (strides) {
+        if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "strided tensors are built for the bf16 kernels only");
+        if (band) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "row bands take the plain layout");
+        for (int t = 0; t < 4; ++t) {
+            if (ts[t].sn < head_dim || ts[t].sh < 0 || ts[t].sb < 0 || (t == 3 && (ts[t].sh <= 0 || (B > 1 && ts[t].sb <= 0))))
+                return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides: the token stride must be >= head_dim, the others >= 0 (> 0 for O)");
+            if ((ts[t].sn | ts[t].sh | ts[t].sb) & 7) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides must be multiples of 8 elements (16-byte rows)");
+        }
+        for (int t = 1; t <= 2; ++t)
+            if ((N - 1) * ts[t].sn * 2 + 2 * head_dim > 0xffffffffLL)
+                return fail(ctx, CLEAR_ERR_UNSUPPORTED, "K and V are addressed with 32-bit byte offsets inside one head: N * token stride * 2 must be < 2^32");
+    }
     {
-        // O must not overlap an input
-        const size_t bytes = (size_t)B * H * N * head_dim * (ctx->dtype == CLEAR_BF16 ? 2 : 4);
-        const uintptr_t o0 = (uintptr_t)O, o1 = o0 + bytes;
+        // O must not overlap an input (compared by the address ranges the tensors span)
+        const size_t esz = ctx->dtype == CLEAR_BF16 ? 2 : 4;
+        auto span = [&](const TensorStrides& st) { return (size_t)((B - 1) * st.sb + (H - 1) * st.sh + (N - 1) * st.sn + head_dim) * esz; };
+        const uintptr_t o0 = (uintptr_t)O, o1 = o0 + span(ts[3]);
         const void* ins[3] = {Q, K, V};
-        for (const void* in : ins) {
-            const uintptr_t i0 = (uintptr_t)in, i1 = i0 + bytes;
+        for (int t = 0; t < 3; ++t) {
+            const uintptr_t i0 = (uintptr_t)ins[t], i1 = i0 + span(ts[t]);
             if (o0 < i1 && i0 < o1) return fail(ctx, CLEAR_ERR_INVALID_ARG, "O overlaps an input tensor");
         }
     }
@@ -420,6 +440,7 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     FwdParams p;
     memset(&p, 0, sizeof(p));
     p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.qs = ts[0]; p.ks = ts[1]; p.vs = ts[2]; p.os = ts[3];
     p.B = B; p.H = H; p.n_text = n_text; p.gridH = gridH; p.gridW = gridW; p.r2 = r * r;
     p.N = N;
     p.n_q_tiles = (int)n_q_tiles;
@@ -524,6 +545,18 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
     return CLEAR_OK;
 }
 
+int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, const long long* strides, int B,
+                               int H, int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+{
+    if (!strides) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides is NULL");
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, strides);
+    if (rc != CLEAR_OK) return rc;
+    hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
 int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
                                int n_text, int gridH, int gridW, int head_dim, int r, void* stream, int reps,
                                float* phase_ms)
@@ -604,7 +637,8 @@ int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int
         const uintptr_t x0 = (uintptr_t)X, y0 = (uintptr_t)Y;
         if (x0 < y0 + bytes && y0 < x0 + bytes) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "X and Y must be the same tensor or must not overlap");
     }
-    hipError_t e = launch_qk_prologue(X, Y, (long long)B * H, n_text, gridH, gridW, head_dim, gain, norm_eps, rope_y, rope_x, (hipStream_t)stream);
+    const TensorStrides plain = {(long long)H * N * head_dim, N * head_dim, head_dim};
+    hipError_t e = launch_qk_prologue(X, plain, Y, plain, B, H, n_text, gridH, gridW, head_dim, gain, norm_eps, rope_y, rope_x, (hipStream_t)stream);
     if (e != hipSuccess) return fail(nullptr, CLEAR_ERR_HIP, std::string("prologue launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }
@@ -629,12 +663,12 @@ int clear_attn_reserve_prologue(clear_attn_ctx* ctx, int BH)
     return CLEAR_OK;
 }
 
-int clear_attn_forward_prologue(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H, int n_text,
-                                int gridH, int gridW, int head_dim, int r, const float* q_gain, const float* k_gain, float norm_eps,
-                                const float* rope_y, const float* rope_x, float logit_scale, void* stream)
+static int forward_prologue_impl(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, const long long* strides, int B,
+                                 int H, int n_text, int gridH, int gridW, int head_dim, int r, const float* q_gain, const float* k_gain,
+                                 float norm_eps, const float* rope_y, const float* rope_x, float logit_scale, void* stream)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, strides);
     if (rc != CLEAR_OK) return rc;
     if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the fused prologue is built for bf16 only");
     rc = check_prologue(ctx, head_dim, q_gain, k_gain, norm_eps, rope_y, rope_x);
@@ -650,14 +684,34 @@ int clear_attn_forward_prologue(clear_attn_ctx* ctx, const void* Q, const void* 
         // kernels, into the context's buffer; the query rows are handled as each workgroup loads its own.
         rc = clear_attn_reserve_prologue(ctx, B * H);
         if (rc != CLEAR_OK) return rc;
-        hipError_t e = launch_qk_prologue(K, ctx->d_kpro, (long long)B * H, n_text, gridH, gridW, head_dim, k_gain, norm_eps, rope_y, rope_x,
+        const TensorStrides plain = {(long long)H * p.N * head_dim, p.N * head_dim, head_dim};  // the context's buffer
+        hipError_t e = launch_qk_prologue(K, p.ks, ctx->d_kpro, plain, B, H, n_text, gridH, gridW, head_dim, k_gain, norm_eps, rope_y, rope_x,
                                           (hipStream_t)stream);
         if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("prologue launch failed: ") + hipGetErrorString(e));
         p.K = ctx->d_kpro;
+        p.ks = plain;
     }
     hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
+}
+
+int clear_attn_forward_prologue(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H, int n_text,
+                                int gridH, int gridW, int head_dim, int r, const float* q_gain, const float* k_gain, float norm_eps,
+                                const float* rope_y, const float* rope_x, float logit_scale, void* stream)
+{
+    return forward_prologue_impl(ctx, Q, K, V, O, nullptr, B, H, n_text, gridH, gridW, head_dim, r, q_gain, k_gain, norm_eps, rope_y, rope_x,
+                                 logit_scale, stream);
+}
+
+int clear_attn_forward_prologue_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, const long long* strides,
+                                        int B, int H, int n_text, int gridH, int gridW, int head_dim, int r, const float* q_gain,
+                                        const float* k_gain, float norm_eps, const float* rope_y, const float* rope_x, float logit_scale,
+                                        void* stream)
+{
+    if (!strides) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides is NULL");
+    return forward_prologue_impl(ctx, Q, K, V, O, strides, B, H, n_text, gridH, gridW, head_dim, r, q_gain, k_gain, norm_eps, rope_y, rope_x,
+                                 logit_scale, stream);
 }
 
 int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)

@@ -43,11 +43,18 @@ unsigned long long executed_pairs_bf16_strided(const Schedule& s, int n_text, in
 // Pairs visited by the fp32 path (it tests every slot of every staged tile).
 unsigned long long executed_pairs_f32(const Schedule& s, int n_text);
 
+// Where element (b, h, n, c) of a [B, H, N, head_dim] tensor lives: base + b * sb + h * sh + n * sn + c (in
+// elements; channels are contiguous).  The plain layout is sn = head_dim, sh = N * head_dim, sb = H * N * head_dim.
+struct TensorStrides {
+    long long sb, sh, sn;
+};
+
 struct FwdParams {
     const void* Q;
     const void* K;
     const void* V;
     void* O;
+    TensorStrides qs, ks, vs, os;  // bf16 kernels only; the fp32 kernel takes the plain layout
     int B, H, n_text, gridH, gridW, r2;
     long long N;       // tokens per (batch, head)
     int n_q_tiles;     // image query tiles per head
@@ -142,8 +149,9 @@ hipError_t launch_merge_text(const MergeParts& parts, int BH, int n_text, long l
                              hipStream_t stream);
 // prologue.hip: RMS norm + rotary embedding of whole [BH][N][head_dim] bf16 tensors (the keys of a fused
 // forward pass; also the stand-alone pass).  X == Y is allowed.
-hipError_t launch_qk_prologue(const void* X, void* Y, long long BH, int n_text, int gridH, int gridW, int head_dim, const float* gain,
-                              float eps, const float* rope_y, const float* rope_x, hipStream_t stream);
+hipError_t launch_qk_prologue(const void* X, const TensorStrides& xs, void* Y, const TensorStrides& ys, int B, int H, int n_text, int gridH,
+                              int gridW, int head_dim, const float* gain, float eps, const float* rope_y, const float* rope_x,
+                              hipStream_t stream);
 // mfma_peak.hip: sustained rate of back-to-back bf16 MFMAs on every SIMD, and the shader clock it ran at.
 hipError_t measure_mfma_peak(int num_cus, double seconds, double* tflops, double* shader_mhz);
 

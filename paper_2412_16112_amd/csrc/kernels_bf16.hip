@@ -88,13 +88,14 @@ constexpr int kTileLoads = 2 * kRowGroupsPerWave;
 struct TileLoads {
     const void* ksrc;                  // the head's K and V arrays
     const void* vsrc;
-    unsigned voff[kRowGroupsPerWave];  // per lane: byte offset of its 16-byte chunk in the arrays
+    unsigned koff[kRowGroupsPerWave];  // per lane: byte offset of its 16-byte chunk in the K array ...
+    unsigned voff[kRowGroupsPerWave];  // ... and in the V array (the two may have different row pitches)
     unsigned lds[kRowGroupsPerWave];   // LDS address of the row group in the tile's K half (V: + TILE_BYTES)
 };
 
 __device__ __forceinline__ void issue_tile_load(const TileLoads& tl, int k)
 {
-    load_to_lds_16B((k & 1) ? tl.vsrc : tl.ksrc, tl.voff[k >> 1], tl.lds[k >> 1] + ((k & 1) ? TILE_BYTES : 0));
+    load_to_lds_16B((k & 1) ? tl.vsrc : tl.ksrc, (k & 1) ? tl.voff[k >> 1] : tl.koff[k >> 1], tl.lds[k >> 1] + ((k & 1) ? TILE_BYTES : 0));
 }
 
 __device__ __forceinline__ void issue_tile_loads(const TileLoads& tl)
@@ -330,10 +331,11 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             kW = (p.gridW - k_ox + stride - 1) / stride;
         }
     }
-    const long long head_off = (long long)bh * p.N * D;  // elements
-    const __bf16* const Qh = (const __bf16*)p.Q + head_off;
-    const unsigned char* const Kh = (const unsigned char*)((const __bf16*)p.K + head_off);
-    const unsigned char* const Vh = (const unsigned char*)((const __bf16*)p.V + head_off);
+    const int batch = bh / p.H, head = bh % p.H;
+    const __bf16* const Qh = (const __bf16*)p.Q + batch * p.qs.sb + head * p.qs.sh;
+    const unsigned char* const Kh = (const unsigned char*)((const __bf16*)p.K + batch * p.ks.sb + head * p.ks.sh);
+    const unsigned char* const Vh = (const unsigned char*)((const __bf16*)p.V + batch * p.vs.sb + head * p.vs.sh);
+    const unsigned k_pitch = (unsigned)p.ks.sn * 2, v_pitch = (unsigned)p.vs.sn * 2;  // bytes from one token row to the next
 
     // ---- this lane's query
     int wy0 = 0, wx0 = 0;  // origin of the wave's 4 x 8 query patch (image mode)
@@ -360,7 +362,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     // Q^T as MFMA B operand: KS contraction steps of 16 channels; this lane supplies channels 16*s + 8*hh .. +7
     bf16x8 qf[KS];
     {
-        const __bf16* qrow = Qh + (long long)q_token * D + 8 * hh;
+        const __bf16* qrow = Qh + (long long)q_token * p.qs.sn + 8 * hh;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
     }
@@ -425,9 +427,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 const int kx = imin(b + (row & 7), kW - 1);
                 token = p.n_text + (ky * stride + k_oy) * p.gridW + kx * stride + k_ox;
             }
-            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
-            load_to_lds_16B(Kh, voff, lds_tile + ii * 1024);
-            load_to_lds_16B(Vh, voff, lds_tile + TILE_BYTES + ii * 1024);
+            const unsigned chunk_off = (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
+            load_to_lds_16B(Kh, (unsigned)token * k_pitch + chunk_off, lds_tile + ii * 1024);
+            load_to_lds_16B(Vh, (unsigned)token * v_pitch + chunk_off, lds_tile + TILE_BYTES + ii * 1024);
         }
     };
     // the same loads, not issued but written down (they ride in the compute pipeline of another tile)
@@ -450,7 +452,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 const int kx = imin(b + (row & 7), kW - 1);
                 token = p.n_text + (ky * stride + k_oy) * p.gridW + kx * stride + k_ox;
             }
-            tl.voff[n] = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
+            const unsigned chunk_off = (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
+            tl.koff[n] = (unsigned)token * k_pitch + chunk_off;
+            tl.voff[n] = (unsigned)token * v_pitch + chunk_off;
             tl.lds[n] = lds_tile + ii * 1024;
         }
         return tl;
@@ -799,7 +803,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             const int oy = wy0 + (row >> 3), ox = wx0 + (row & 7);
             const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane % CHUNKS) * 16);
             if (oy < qH && ox < qW && oy >= p.own_y0 && oy < p.own_y1) {
-                __bf16* orow = (__bf16*)p.O + head_off + ((long long)p.n_text + (long long)(oy * stride + q_oy) * p.gridW + ox * stride + q_ox) * D;
+                __bf16* orow = (__bf16*)p.O + batch * p.os.sb + head * p.os.sh + ((long long)p.n_text + (long long)(oy * stride + q_oy) * p.gridW + ox * stride + q_ox) * p.os.sn;
                 *(f32x4*)(orow + (lane % CHUNKS) * 8) = chunk;
             }
         }
@@ -833,7 +837,7 @@ __global__ void __launch_bounds__(256) clear_text_merge_kernel(const FwdParams p
         // sum_j exp(s_j / sqrt(d)) = den * 2^{m c}
         if (ch == 0) p.band_lse[row] = __logf(den) + m * p.scale_log2e * 0.6931471805599453f;
     } else {
-        ((OutT*)p.O)[((long long)bh * p.N + q) * d + ch] = (OutT)(num / den);
+        ((OutT*)p.O)[(bh / p.H) * p.os.sb + (bh % p.H) * p.os.sh + q * p.os.sn + ch] = (OutT)(num / den);
         if (p.lse && ch == 0) p.lse[(long long)bh * p.N + q] = __logf(den) + m * p.scale_log2e * 0.6931471805599453f;
     }
 }

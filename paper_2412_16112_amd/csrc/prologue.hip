@@ -15,19 +15,25 @@ namespace {
 constexpr int kRowsPerThread = 4;  // independent 16-byte loads in flight per lane
 
 template <int HD>
-__global__ void __launch_bounds__(256) qk_prologue_kernel(const __bf16* __restrict__ X, __bf16* __restrict__ Y, long long rows_total, long long N,
-                                                          int n_text, int gridW, const float* __restrict__ gain, float eps,
-                                                          const float* __restrict__ rope_y, const float* __restrict__ rope_x)
+__global__ void __launch_bounds__(256) qk_prologue_kernel(const __bf16* __restrict__ X, TensorStrides xs, __bf16* __restrict__ Y, TensorStrides ys,
+                                                          int H, long long rows_total, long long N, int n_text, int gridW,
+                                                          const float* __restrict__ gain, float eps, const float* __restrict__ rope_y,
+                                                          const float* __restrict__ rope_x)
 {
     constexpr int LPR = HD / 8;        // lanes per row
     constexpr int RPB = 256 / LPR;     // rows per block and sweep
     const int c0 = 8 * (threadIdx.x % LPR);
     const long long row0 = (long long)blockIdx.x * (RPB * kRowsPerThread) + threadIdx.x / LPR;
+    // row = (b * H + h) * N + token  ->  element offset in a strided [B, H, N, HD] tensor
+    auto offset = [&](long long row, const TensorStrides& st) {
+        const long long bh = row / N, t = row % N;
+        return (bh / H) * st.sb + (bh % H) * st.sh + t * st.sn;
+    };
     bf16x8 in[kRowsPerThread];
 #pragma unroll
     for (int i = 0; i < kRowsPerThread; ++i) {
         const long long row = row0 + (long long)i * RPB;
-        in[i] = *(const bf16x8*)(X + (row < rows_total ? row : rows_total - 1) * HD + c0);
+        in[i] = *(const bf16x8*)(X + offset(row < rows_total ? row : rows_total - 1, xs) + c0);
     }
 #pragma unroll
     for (int i = 0; i < kRowsPerThread; ++i) {
@@ -52,27 +58,28 @@ __global__ void __launch_bounds__(256) qk_prologue_kernel(const __bf16* __restri
         bf16x8 out;
 #pragma unroll
         for (int j = 0; j < 8; ++j) out[j] = (__bf16)x[j];
-        if (live) *(bf16x8*)(Y + rr * HD + c0) = out;
+        if (live) *(bf16x8*)(Y + offset(rr, ys) + c0) = out;
     }
 }
 
 }  // namespace
 
-hipError_t launch_qk_prologue(const void* X, void* Y, long long BH, int n_text, int gridH, int gridW, int head_dim, const float* gain,
-                              float eps, const float* rope_y, const float* rope_x, hipStream_t stream)
+hipError_t launch_qk_prologue(const void* X, const TensorStrides& xs, void* Y, const TensorStrides& ys, int B, int H, int n_text, int gridH,
+                              int gridW, int head_dim, const float* gain, float eps, const float* rope_y, const float* rope_x,
+                              hipStream_t stream)
 {
     const long long N = (long long)n_text + (long long)gridH * gridW;
-    const long long rows = BH * N;
+    const long long rows = (long long)B * H * N;
     if (rows == 0) return hipSuccess;
     const int rows_per_block = 256 / (head_dim / 8) * kRowsPerThread;
     const long long blocks = (rows + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (head_dim == 128)
-        hipLaunchKernelGGL(qk_prologue_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, stream, (const __bf16*)X, (__bf16*)Y, rows, N, n_text,
-                           gridW, gain, eps, rope_y, rope_x);
+        hipLaunchKernelGGL(qk_prologue_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, stream, (const __bf16*)X, xs, (__bf16*)Y, ys, H, rows, N,
+                           n_text, gridW, gain, eps, rope_y, rope_x);
     else if (head_dim == 64)
-        hipLaunchKernelGGL(qk_prologue_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream, (const __bf16*)X, (__bf16*)Y, rows, N, n_text,
-                           gridW, gain, eps, rope_y, rope_x);
+        hipLaunchKernelGGL(qk_prologue_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream, (const __bf16*)X, xs, (__bf16*)Y, ys, H, rows, N,
+                           n_text, gridW, gain, eps, rope_y, rope_x);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
