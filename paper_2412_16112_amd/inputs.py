@@ -45,6 +45,14 @@ WORKLOADS = {
         Workload("flux-4096-r32", 1, 24, 512, 256, 256, 128, 32, "bf16", 3),
         Workload("flux-4096-192x320-r32", 1, 24, 512, 192, 320, 128, 32, "bf16", 4),
         Workload("flux-8k-r16", 1, 24, 512, 512, 512, 128, 16, "bf16", 5, per_head_q_scale=True),
+        # the remaining (resolution, r) pairs of the paper's efficiency tables (Tables 2, 3 and 7)
+        Workload("flux-1024-r8", 1, 24, 512, 64, 64, 128, 8, "bf16", 11),
+        Workload("flux-1024-r32", 1, 24, 512, 64, 64, 128, 32, "bf16", 12),
+        Workload("flux-2048-r32", 1, 24, 512, 128, 128, 128, 32, "bf16", 13),
+        Workload("flux-4096-r8", 1, 24, 512, 256, 256, 128, 8, "bf16", 14),
+        Workload("flux-4096-r16", 1, 24, 512, 256, 256, 128, 16, "bf16", 15),
+        Workload("flux-8k-r8", 1, 24, 512, 512, 512, 128, 8, "bf16", 16, per_head_q_scale=True),
+        Workload("flux-8k-r32", 1, 24, 512, 512, 512, 128, 32, "bf16", 17, per_head_q_scale=True),
         # head_dim 64: the geometry of an SD3.5-Large-style block (38 heads of 64 channels, 333 text tokens; the
         # paper deploys CLEAR on that model with r = 16 but does not print its shapes)
         Workload("sd35l-1024-r16", 1, 38, 333, 64, 64, 64, 16, "bf16", 6),

@@ -28,6 +28,9 @@ def test_mask_count_matches_known_values(name):
     w = WORKLOADS[name]
     expected = {"tiny": 13484, "flux-1024": 7051328, "flux-2048-r16": 28693056, "flux-2048-r8": 20038564,
                 "flux-4096-r32": 255670316, "flux-4096-192x320-r32": 238348332, "flux-8k-r16": 471125568,
+                # (each of these reproduces the figure the paper prints for it: 4 * sum(M) * 3072, tests/golden/)
+                "flux-1024-r8": 5166500, "flux-1024-r32": 12541484, "flux-2048-r32": 58940460, "flux-4096-r8": 79691684,
+                "flux-4096-r16": 116631104, "flux-8k-r8": 318633892, "flux-8k-r32": 1064857644,
                 # 333 text tokens: the image-image part is that of the 512-text-token workload of the same grid
                 "sd35l-1024-r16": 5433705, "sd35l-4096-r16": 93017961}[name]
     assert ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r) == expected
