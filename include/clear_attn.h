@@ -183,7 +183,7 @@ int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int
                            const float* gain, float norm_eps, const float* rope_y, const float* rope_x,
                            void* stream);
 
-/* ---- Tensors in another layout.  Callers that cannot spare a transposing copy - Q, K, V straight out of a
+/* ---- Tensors in another layout (the same operator as clear_attn_forward: Eq. 1 under the mask of Eq. 3).  Callers that cannot spare a transposing copy - Q, K, V straight out of a
  * projection as [B, N, H, head_dim], or slices of one packed [B, N, 3, H, head_dim] tensor, and O wanted the same
  * way - pass strides: `strides` points at 12 values, (batch, head, token) strides in elements for Q, K, V, O in this
  * order; element (b, h, n, c) of a tensor is at base + b*sb + h*sh + n*sn + c (channels contiguous).  bf16 contexts
