@@ -190,11 +190,17 @@ int clear_attn_qk_prologue(const void* X, void* Y, int B, int H, int n_text, int
  * only.  Every stride must be a multiple of 8 elements (base pointers 16-byte aligned as before), the token stride
  * >= head_dim, the others >= 0 (an input may repeat over heads or batch; O's must be > 0); K and V are addressed
  * with 32-bit byte offsets inside a head, so N * token stride * 2 must stay below 2^32; O's address range must not
- * overlap an input's.  Same results, bit for bit, as the plain layout.  The log-sum-exp, row-band and backward
- * entry points take the plain layout only. */
-int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
+ * overlap an input's.  Same results, bit for bit, as the plain layout.  lse of clear_attn_forward_strided: NULL, or
+ * where to write the log-sum-exp of clear_attn_forward_lse (always the plain [B, H, N] fp32 layout).  The row-band
+ * entry points take the plain layout only.
+ * clear_attn_backward_strided: clear_attn_backward with 24 stride values, for Q, K, V, O, dO, dQ, dK, dV in this order;
+ * the same rules, with Q, K, V, dO under the 32-bit limit and dQ, dK, dV in the place of O. */
+int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, float* lse,
                                const long long* strides, int B, int H, int n_text, int gridH, int gridW, int head_dim,
                                int r, void* stream);
+int clear_attn_backward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O,
+                                const void* dO, const float* lse, void* dQ, void* dK, void* dV, const long long* strides,
+                                int B, int H, int n_text, int gridH, int gridW, int head_dim, int r, void* stream);
 int clear_attn_forward_prologue_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
                                         const long long* strides, int B, int H, int n_text, int gridH, int gridW,
                                         int head_dim, int r, const float* q_gain, const float* k_gain, float norm_eps,

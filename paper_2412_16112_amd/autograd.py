@@ -33,23 +33,35 @@ def clear_context_cache():
 class ClearAttentionFunction(torch.autograd.Function):
     @staticmethod
     def forward(fctx, Q, K, V, n_text, gridH, gridW, r, mask_kind=ca.CLEAR_MASK_DISC, shift=0):
-        Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
+        # bf16 tensors go in with whatever batch / head / token strides they have (transposed views of a projection's
+        # [B, N, H, d] output included); only the channels must be contiguous
+        strided = Q.dtype == torch.bfloat16
+        fix = (lambda t: t if t.stride(-1) == 1 else t.contiguous()) if strided else (lambda t: t.contiguous())
+        Q, K, V = fix(Q), fix(K), fix(V)
         ctx = _context(Q.device, n_text, gridH, gridW, Q.shape[-1], r, ca._dtype_code(Q), mask_kind, shift)
         needs_grad = any(fctx.needs_input_grad[:3])
         with torch.cuda.device(Q.device):
-            if needs_grad:
+            if strided:
+                lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device) if needs_grad else None
+                O = ctx.forward_strided(Q, K, V, lse=lse)
+            elif needs_grad:
                 O, lse = ctx.forward_lse(Q, K, V)
-                fctx.save_for_backward(Q, K, V, O, lse)
-                fctx.clear_ctx = ctx
             else:
                 O = ctx.forward(Q, K, V)
+            if needs_grad:
+                fctx.save_for_backward(Q, K, V, O, lse)
+                fctx.clear_ctx = ctx
         return O
 
     @staticmethod
     def backward(fctx, dO):
         Q, K, V, O, lse = fctx.saved_tensors
+        dO = dO.to(Q.dtype)
         with torch.cuda.device(Q.device):
-            dQ, dK, dV = fctx.clear_ctx.backward(Q, K, V, O, dO.contiguous().to(Q.dtype), lse)
+            if Q.dtype == torch.bfloat16:
+                dQ, dK, dV = fctx.clear_ctx.backward_strided(Q, K, V, O, dO if dO.stride(-1) == 1 else dO.contiguous(), lse)
+            else:
+                dQ, dK, dV = fctx.clear_ctx.backward(Q, K, V, O, dO.contiguous(), lse)
         return dQ, dK, dV, None, None, None, None, None, None
 
 

@@ -23,7 +23,7 @@ EXPORTS = [
     "clear_attn_schedule_size", "clear_attn_schedule_copy", "clear_attn_executed_pairs",
     "clear_attn_measure_mfma_peak", "clear_attn_last_error",
     "clear_attn_forward_prologue", "clear_attn_reserve_prologue", "clear_attn_qk_prologue",
-    "clear_attn_forward_strided", "clear_attn_forward_prologue_strided",
+    "clear_attn_forward_strided", "clear_attn_forward_prologue_strided", "clear_attn_backward_strided",
 ]
 
 _lib = None
@@ -71,7 +71,8 @@ def lib():
         L.clear_attn_forward_prologue.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp, vp, f, vp, vp, f, vp]
         L.clear_attn_reserve_prologue.argtypes = [vp, i]
         L.clear_attn_qk_prologue.argtypes = [vp, vp, i, i, i, i, i, i, vp, f, vp, vp, vp]
-        L.clear_attn_forward_strided.argtypes = [vp, vp, vp, vp, vp, llp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_forward_strided.argtypes = [vp, vp, vp, vp, vp, vp, llp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_backward_strided.argtypes = [vp] * 10 + [llp] + [i] * 7 + [vp]
         L.clear_attn_forward_prologue_strided.argtypes = [vp, vp, vp, vp, vp, llp, i, i, i, i, i, i, i, vp, vp, f, vp, vp, f, vp]
         L.clear_attn_last_error.argtypes = [vp]
         L.clear_attn_last_error.restype = ctypes.c_char_p
@@ -201,7 +202,7 @@ class ClearAttn:
         return O
 
     def forward_strided(self, Q, K, V, O=None, stream=None, q_gain=None, k_gain=None, norm_eps=1e-6, rope_y=None, rope_x=None,
-                        logit_scale=None):
+                        logit_scale=None, lse=None):
         """clear_attn_forward_strided (or, with any prologue argument, clear_attn_forward_prologue_strided): Q, K, V, O are
         [B, H, N, head_dim] views with any batch / head / token strides and contiguous channels, e.g. transposed views
         of [B, N, H, head_dim] tensors or slices of a packed QKV tensor.  O defaults to a new tensor laid out like Q."""
@@ -226,9 +227,28 @@ class ClearAttn:
                                                              ptr(rope_x), 1.0 if logit_scale is None else logit_scale, ctypes.c_void_p(s)),
                    self._ctx)
         else:
-            _check(lib().clear_attn_forward_strided(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), strides, B, H,
+            _check(lib().clear_attn_forward_strided(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                                    None if lse is None else lse.data_ptr(), strides, B, H,
                                                     n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
+
+    def backward_strided(self, Q, K, V, O, dO, lse, stream=None):
+        """clear_attn_backward_strided: Q, K, V, O, dO are [B, H, N, head_dim] views with any batch / head / token strides
+        and contiguous channels; returns (dQ, dK, dV) laid out like Q, K, V."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = Q.shape
+        outs = [torch.empty_strided(t.shape, t.stride(), dtype=t.dtype, device=t.device) if min(t.stride()[:3]) > 0 else torch.empty_like(t)
+                for t in (Q, K, V)]
+        for t in (Q, K, V, O, dO, *outs):
+            if not (t.is_cuda and t.shape == Q.shape and t.dtype == Q.dtype and t.stride(3) == 1):
+                raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "tensors must be device tensors of one shape and dtype with contiguous channels")
+        strides = (ctypes.c_longlong * 24)(*[t.stride(k) for t in (Q, K, V, O, dO, *outs) for k in (0, 1, 2)])
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        _check(lib().clear_attn_backward_strided(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), lse.data_ptr(),
+                                                 outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(), strides, B, H, n_text, gridH, gridW,
+                                                 head_dim, r, ctypes.c_void_p(s)), self._ctx)
+        return tuple(outs)
 
     def forward_lse(self, Q, K, V, O=None, lse=None, stream=None):
         """clear_attn_forward_lse: returns (O, lse) with lse fp32 [B, H, N]."""

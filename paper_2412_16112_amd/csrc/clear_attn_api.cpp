@@ -545,13 +545,15 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
     return CLEAR_OK;
 }
 
-int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, const long long* strides, int B,
-                               int H, int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, float* lse,
+                               const long long* strides, int B, int H, int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
 {
     if (!strides) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides is NULL");
     FwdParams p;
     int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, strides);
     if (rc != CLEAR_OK) return rc;
+    if ((uintptr_t)lse & 3) return fail(ctx, CLEAR_ERR_INVALID_ARG, "lse must be 4-byte aligned");
+    p.lse = lse;
     hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
@@ -739,9 +741,9 @@ int clear_attn_reserve_backward(clear_attn_ctx* ctx, int BH)
     return CLEAR_OK;
 }
 
-int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O, const void* dO,
-                        const float* lse, void* dQ, void* dK, void* dV, int B, int H, int n_text, int gridH, int gridW,
-                        int head_dim, int r, void* stream)
+static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* lse,
+                         void* dQ, void* dK, void* dV, const long long* strides, int B, int H, int n_text, int gridH, int gridW,
+                         int head_dim, int r, void* stream)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV) return fail(ctx, CLEAR_ERR_INVALID_ARG, "NULL tensor pointer");
@@ -754,14 +756,33 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the backward pass is built for bf16 only");
 
     const long long N = (long long)n_text + (long long)gridH * gridW;
+    TensorStrides ts[8];  // Q, K, V, O, dO, dQ, dK, dV
+    for (int t = 0; t < 8; ++t) {
+        ts[t].sn = strides ? strides[3 * t + 2] : head_dim;
+        ts[t].sh = strides ? strides[3 * t + 1] : N * head_dim;
+        ts[t].sb = strides ? strides[3 * t] : (long long)H * N * head_dim;
+    }
+    if (strides) {
+        for (int t = 0; t < 8; ++t) {
+            const bool output = t >= 5;
+            if (ts[t].sn < head_dim || ts[t].sh < 0 || ts[t].sb < 0 || (output && (ts[t].sh <= 0 || (B > 1 && ts[t].sb <= 0))))
+                return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides: the token stride must be >= head_dim, the others >= 0 (> 0 for dQ, dK, dV)");
+            if ((ts[t].sn | ts[t].sh | ts[t].sb) & 7) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides must be multiples of 8 elements (16-byte rows)");
+        }
+        for (int t : {0, 1, 2, 4})  // the tensors staged as column tiles
+            if ((N - 1) * ts[t].sn * 2 + 2 * head_dim > 0xffffffffLL)
+                return fail(ctx, CLEAR_ERR_UNSUPPORTED, "Q, K, V, dO are addressed with 32-bit byte offsets inside one head: N * token stride * 2 must be < 2^32");
+    }
     {
-        // outputs must not overlap inputs or each other
-        const size_t bytes = (size_t)B * H * N * head_dim * 2;
+        // outputs must not overlap inputs or each other (compared by the address ranges the tensors span)
+        auto span = [&](const TensorStrides& st) { return (size_t)((B - 1) * st.sb + (H - 1) * st.sh + (N - 1) * st.sn + head_dim) * 2; };
         const void* all[8] = {dQ, dK, dV, Q, K, V, O, dO};
+        const int idx[8] = {5, 6, 7, 0, 1, 2, 3, 4};
         for (int a = 0; a < 3; ++a)
             for (int b = a + 1; b < 8; ++b) {
                 const uintptr_t a0 = (uintptr_t)all[a], b0 = (uintptr_t)all[b];
-                if (a0 < b0 + bytes && b0 < a0 + bytes) return fail(ctx, CLEAR_ERR_INVALID_ARG, "dQ, dK, dV must not overlap each other or an input");
+                if (a0 < b0 + span(ts[idx[b]]) && b0 < a0 + span(ts[idx[a]]))
+                    return fail(ctx, CLEAR_ERR_INVALID_ARG, "dQ, dK, dV must not overlap each other or an input");
             }
     }
     const int BH = B * H;
@@ -772,6 +793,7 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     memset(&p, 0, sizeof(p));
     p.Q = Q; p.K = K; p.V = V; p.dO = dO; p.lse = lse; p.delta = ctx->d_bwd_delta;
     p.dQ = dQ; p.dK = dK; p.dV = dV;
+    p.qs = ts[0]; p.ks = ts[1]; p.vs = ts[2]; p.os = ts[3]; p.dos = ts[4]; p.dqs = ts[5]; p.dks = ts[6]; p.dvs = ts[7];
     p.B = B; p.H = H; p.n_text = n_text; p.gridH = gridH; p.gridW = gridW; p.r2 = r * r;
     p.N = N;
     p.n_q_tiles = s.n_qty * s.n_qtx;
@@ -819,6 +841,21 @@ int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const
     }
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("backward launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
+}
+
+int clear_attn_backward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                        const float* lse, void* dQ, void* dK, void* dV, int B, int H, int n_text, int gridH, int gridW,
+                        int head_dim, int r, void* stream)
+{
+    return backward_impl(ctx, Q, K, V, O, dO, lse, dQ, dK, dV, nullptr, B, H, n_text, gridH, gridW, head_dim, r, stream);
+}
+
+int clear_attn_backward_strided(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                const float* lse, void* dQ, void* dK, void* dV, const long long* strides, int B, int H, int n_text,
+                                int gridH, int gridW, int head_dim, int r, void* stream)
+{
+    if (!strides) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides is NULL");
+    return backward_impl(ctx, Q, K, V, O, dO, lse, dQ, dK, dV, strides, B, H, n_text, gridH, gridW, head_dim, r, stream);
 }
 
 int clear_attn_forward_band(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,

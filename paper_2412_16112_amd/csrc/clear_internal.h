@@ -116,6 +116,7 @@ struct BwdParams {
     void* dQ;
     void* dK;
     void* dV;
+    TensorStrides qs, ks, vs, os, dos, dqs, dks, dvs;  // lse and delta are plain [B*H][N]
     int B, H, n_text, gridH, gridW, r2;
     long long N;
     int n_q_tiles, n_qtx;

@@ -102,11 +102,17 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         cH = (p.gridH - c_oy + stride - 1) / stride;
         cW = (p.gridW - c_ox + stride - 1) / stride;
     }
-    const long long head_off = (long long)bh * p.N * D;  // elements
-    const __bf16* const R1 = (const __bf16*)(MODE == kBwdQ ? p.Q : p.K) + head_off;
-    const __bf16* const R2 = (const __bf16*)(MODE == kBwdQ ? p.dO : p.V) + head_off;
-    const unsigned char* const C1 = (const unsigned char*)((const __bf16*)(MODE == kBwdQ ? p.K : p.Q) + head_off);
-    const unsigned char* const C2 = (const unsigned char*)((const __bf16*)(MODE == kBwdQ ? p.V : p.dO) + head_off);
+    const int batch = bh / p.H, head = bh % p.H;
+    auto head_of = [&](const void* ptr, const TensorStrides& st) { return (const __bf16*)ptr + batch * st.sb + head * st.sh; };
+    const TensorStrides& r1s = MODE == kBwdQ ? p.qs : p.ks;
+    const TensorStrides& r2s = MODE == kBwdQ ? p.dos : p.vs;
+    const TensorStrides& c1s = MODE == kBwdQ ? p.ks : p.qs;
+    const TensorStrides& c2s = MODE == kBwdQ ? p.vs : p.dos;
+    const __bf16* const R1 = head_of(MODE == kBwdQ ? p.Q : p.K, r1s);
+    const __bf16* const R2 = head_of(MODE == kBwdQ ? p.dO : p.V, r2s);
+    const unsigned char* const C1 = (const unsigned char*)head_of(MODE == kBwdQ ? p.K : p.Q, c1s);
+    const unsigned char* const C2 = (const unsigned char*)head_of(MODE == kBwdQ ? p.V : p.dO, c2s);
+    const unsigned c1_pitch = (unsigned)c1s.sn * 2, c2_pitch = (unsigned)c2s.sn * 2;  // bytes from one token row to the next
     const float* const lse = p.lse + (long long)bh * p.N;
     const float* const delta = p.delta + (long long)bh * p.N;
 
@@ -133,8 +139,8 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     bf16x8 r1f[KS], r2f[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        r1f[s] = *(const bf16x8*)(R1 + (long long)r_token * D + 8 * hh + 16 * s);
-        if (MODE != kBwdV) r2f[s] = *(const bf16x8*)(R2 + (long long)r_token * D + 8 * hh + 16 * s);
+        r1f[s] = *(const bf16x8*)(R1 + (long long)r_token * r1s.sn + 8 * hh + 16 * s);
+        if (MODE != kBwdV) r2f[s] = *(const bf16x8*)(R2 + (long long)r_token * r2s.sn + 8 * hh + 16 * s);
     }
     // lse in units of log2 (the exponentials are 2^x); dQ: this lane's query
     constexpr float LOG2E = 1.4426950408889634f;
@@ -205,9 +211,9 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
             const int ii = wave * NI + n;
             const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
             const int token = slot_token(a, b, row);
-            const unsigned voff = (unsigned)token * ROW_BYTES + (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
-            load_to_lds_16B(C1, voff, lds_tile + ii * 1024);
-            load_to_lds_16B(C2, voff, lds_tile + TILE_BYTES + ii * 1024);
+            const unsigned chunk_off = (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
+            load_to_lds_16B(C1, (unsigned)token * c1_pitch + chunk_off, lds_tile + ii * 1024);
+            load_to_lds_16B(C2, (unsigned)token * c2_pitch + chunk_off, lds_tile + TILE_BYTES + ii * 1024);
         }
     };
     float st_lse2 = 0.f, st_delta = 0.f;  // in flight: statistics of slot `lane` of tile `wave` of the next stage
@@ -401,7 +407,8 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
                 }
         }
     } else {
-        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdV ? p.dV : p.dK)) + head_off + (long long)r_token * D;
+        const TensorStrides& outs = MODE == kBwdQ ? p.dqs : (MODE == kBwdV ? p.dvs : p.dks);
+        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdV ? p.dV : p.dK)) + batch * outs.sb + head * outs.sh + (long long)r_token * outs.sn;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -412,7 +419,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
                 *(bf16x4*)(orow + 32 * db + 8 * g + 4 * hh) = v;
             }
         if constexpr (MODE == kBwdKV) {
-            __bf16* vrow = (__bf16*)p.dV + head_off + (long long)r_token * D;
+            __bf16* vrow = (__bf16*)p.dV + batch * p.dvs.sb + head * p.dvs.sh + (long long)r_token * p.dvs.sn;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -427,14 +434,19 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
 }
 
 // delta_i = dO_i . O_i for every row: D / 8 lanes per row (8 channels = 16 bytes each).
-__global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, const __bf16* dO, float* delta, long long rows)
+__global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, TensorStrides os, const __bf16* dO, TensorStrides dos, int H,
+                                                              long long N, float* delta, long long rows)
 {
+    auto offset = [&](long long row, const TensorStrides& st) {  // row = (b * H + h) * N + token
+        const long long bh = row / N, t = row % N;
+        return (bh / H) * st.sb + (bh % H) * st.sh + t * st.sn;
+    };
     const long long row = (long long)blockIdx.x * (256 / CHUNKS) + threadIdx.x / CHUNKS;
     const int part = threadIdx.x % CHUNKS;
     float s = 0.f;
     if (row < rows) {
-        const bf16x8 o = *(const bf16x8*)(O + row * D + 8 * part);
-        const bf16x8 g = *(const bf16x8*)(dO + row * D + 8 * part);
+        const bf16x8 o = *(const bf16x8*)(O + offset(row, os) + 8 * part);
+        const bf16x8 g = *(const bf16x8*)(dO + offset(row, dos) + 8 * part);
 #pragma unroll
         for (int j = 0; j < 8; ++j) s += (float)o[j] * (float)g[j];
     }
@@ -456,7 +468,8 @@ __global__ void __launch_bounds__(D) clear_bwd_reduce_kernel(const BwdParams p)
     for (int k = 0; k < p.n_splits; ++k)
         s += p.ws[((((long long)mode * p.B * p.H + bh) * p.n_splits + k) * p.n_text + q) * D + ch];
     __bf16* out = (__bf16*)(mode == kBwdQ ? p.dQ : (mode == kBwdK ? p.dK : p.dV));
-    out[((long long)bh * p.N + q) * D + ch] = (__bf16)s;
+    const TensorStrides& st = mode == kBwdQ ? p.dqs : (mode == kBwdK ? p.dks : p.dvs);
+    out[(bh / p.H) * st.sb + (bh % p.H) * st.sh + q * st.sn + ch] = (__bf16)s;
 }
 
 template <int MODE, bool LINROWS, int CODE>
@@ -494,7 +507,7 @@ hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta,
     if (all || phase == kBwdPhaseDelta) {
         const long long rows = (long long)BH * p.N;
         constexpr int rows_per_block = 256 / CHUNKS;
-        hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), dim3(256), 0, stream, (const __bf16*)O, (const __bf16*)p.dO, delta, rows);
+        hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), dim3(256), 0, stream, (const __bf16*)O, p.os, (const __bf16*)p.dO, p.dos, p.H, p.N, delta, rows);
         e = hipGetLastError();
     }
     const int nimg = BH * p.n_classes * p.n_q_tiles;

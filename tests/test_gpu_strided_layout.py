@@ -114,3 +114,48 @@ def test_stride_argument_checks():
         assert e.value.status == ca.CLEAR_ERR_UNSUPPORTED
     finally:
         ctx.destroy()
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_training_pair_in_token_major_storage(d):
+    """forward with log-sum-exp + backward on [B, N, H, d] storage: same bits as the plain layout."""
+    B, H, n_text, gh, gw, r = 2, 2, 40, 24, 28, 6
+    Q, K, V = make_qkv_shape(B, H, n_text, gh, gw, d, "bf16", seed=740 + d, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(741)
+    dO = torch.randn(Q.shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    ctx = ca.ClearAttn(n_text, gh, gw, d, r, ca.CLEAR_BF16)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        dQ, dK, dV = ctx.backward(Q, K, V, O, dO, lse)
+        Qs, Ks, Vs, dOs = (token_major(t) for t in (Q, K, V, dO))
+        lse_s = torch.empty_like(lse)
+        Os = ctx.forward_strided(Qs, Ks, Vs, lse=lse_s)
+        dQs, dKs, dVs = ctx.backward_strided(Qs, Ks, Vs, Os, dOs, lse_s)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    assert dQs.stride() == Qs.stride() and not dQs.is_contiguous()
+    assert torch.equal(O, Os.contiguous()) and torch.equal(lse, lse_s)
+    for a, b in ((dQ, dQs), (dK, dKs), (dV, dVs)):
+        assert torch.equal(a, b.contiguous())
+
+
+def test_autograd_takes_transposed_views():
+    from paper_2412_16112_amd.autograd import clear_attention, clear_context_cache
+    B, H, n_text, gh, gw, d, r = 1, 2, 16, 24, 24, 128, 5
+    Q, K, V = make_qkv_shape(B, H, n_text, gh, gw, d, "bf16", seed=750, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(751)
+    dO = torch.randn(Q.shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    leaves = [t.permute(0, 2, 1, 3).contiguous().requires_grad_(True) for t in (Q, K, V)]  # [B, N, H, d] parameters' outputs
+    try:
+        O = clear_attention(*(t.permute(0, 2, 1, 3) for t in leaves), n_text, gh, gw, r)
+        O.backward(dO)
+        torch.cuda.synchronize()
+    finally:
+        clear_context_cache()
+    q, k, v, go = (t[0, 0].float().cpu().numpy() for t in (Q, K, V, dO))
+    rQ, rK, rV = orc.backward(q, k, v, go, n_text, gh, gw, r)
+    for leaf, ref in zip(leaves, (rQ, rK, rV)):
+        got = leaf.grad.permute(0, 2, 1, 3)[0, 0].float().cpu().numpy()
+        mx, rms = error_metrics(got, ref)
+        assert mx <= TOL["bf16"][0] * np.abs(ref).max() and rms <= TOL["bf16"][1], (mx, rms)
