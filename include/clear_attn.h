@@ -21,7 +21,9 @@
  *
  * Errors: every function returns a clear_status; nothing throws or aborts; invalid arguments are
  * rejected before any device work.  clear_attn_last_error gives a human-readable reason.
- * Thread safety: a context may be used by one thread at a time; distinct contexts are independent.
+ * Thread safety: a context may be used by one thread at a time; distinct contexts are independent.  Calls on one
+ * context share its workspaces, so they must be ordered among themselves: enqueue them on one stream, or make the
+ * later call's stream wait for the earlier call; use one context per stream for concurrent calls.
  * All functions run on the current HIP device; a context belongs to the device current at create.
  * Streams: work is enqueued on the stream passed in and is complete when that stream has reached the end of
  * the call's work.  For small problems a forward call also uses a stream the context owns (default priority),
