@@ -490,11 +490,14 @@ hipError_t launch_bwd_code(const BwdParams& p, int nblk, hipStream_t stream)
 template <int MODE, bool LINROWS>
 hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
 {
-    if (LINROWS) return launch_bwd_code<MODE, LINROWS, kCodeDisc>(p, nblk, stream);
-    const int code = mask_code_of(p.mask_kind);
-    return code == kCodeDisc   ? launch_bwd_code<MODE, LINROWS, kCodeDisc>(p, nblk, stream)
-           : code == kCodeFull ? launch_bwd_code<MODE, LINROWS, kCodeFull>(p, nblk, stream)
-                               : launch_bwd_code<MODE, LINROWS, kCodeGeneric>(p, nblk, stream);
+    if constexpr (LINROWS) {
+        return launch_bwd_code<MODE, LINROWS, kCodeDisc>(p, nblk, stream);
+    } else {
+        const int code = mask_code_of(p.mask_kind);
+        return code == kCodeDisc   ? launch_bwd_code<MODE, LINROWS, kCodeDisc>(p, nblk, stream)
+               : code == kCodeFull ? launch_bwd_code<MODE, LINROWS, kCodeFull>(p, nblk, stream)
+                                   : launch_bwd_code<MODE, LINROWS, kCodeGeneric>(p, nblk, stream);
+    }
 }
 
 }  // namespace
