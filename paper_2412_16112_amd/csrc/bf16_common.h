@@ -38,7 +38,11 @@ constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
 #define CLEAR_TILES_PER_STAGE 2
 #endif
 constexpr int TPS = CLEAR_TILES_PER_STAGE;           // key tiles (K + V = 32 KB each) staged per barrier
-constexpr int NBUF = 2;                             // stage buffers: one being computed on, one being filled
+#ifndef CLEAR_NBUF
+#define CLEAR_NBUF 2
+#endif
+constexpr int NBUF = CLEAR_NBUF;                     // stage buffers: one being computed on, the others being filled
+__host__ __device__ constexpr int next_buf(int buf) { return buf + 1 == NBUF ? 0 : buf + 1; }
 constexpr int STAGE_BYTES = TPS * 2 * TILE_BYTES;
 constexpr float FAST_SUM_LIMIT = 1.0e30f;  // the fast pass is discarded when a query's sums leave [0, 1e30)
 constexpr float M_INIT = -1.0e30f;         // finite "no key seen yet" (keeps exp2 arguments free of inf - inf)

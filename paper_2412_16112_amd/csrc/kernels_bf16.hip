@@ -77,6 +77,14 @@ __device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
     ws.m_run = (ws.m_run == M_INIT) ? fmaxf(mx_pair, M_INIT) : ws.m_run;
 }
 
+// Loading waves: CLEAR_LOADER_WAVES extra waves per workgroup do nothing but issue the staging loads, one stage
+// ahead of the computing waves, which then never stall on the memory pipeline's issue queue.  0 = every
+// wave stages its share of each tile itself, right after the stage barrier.
+#ifndef CLEAR_LOADER_WAVES
+#define CLEAR_LOADER_WAVES 4
+#endif
+constexpr int kLoaderWaves = CLEAR_LOADER_WAVES;
+
 // Pins the instruction order: nothing is scheduled across this point.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -278,7 +286,7 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS]
 }
 
 template <int NWY, int NWX, bool TEXTQ, int CODE>
-__global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
+__global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <= 4 && kLoaderWaves == 0) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
 {
     constexpr int NW = NWY * NWX;
     constexpr int NI = kRowGroupsPerWave;  // 1 KB load instructions per wave per tile, for K and for V each
@@ -292,6 +300,13 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qi = lane & 31;   // query slot inside the wave's patch
     const int hh = lane >> 5;   // which half of the contraction slice this lane feeds
+    // waves NW .. NW + NLW - 1 only load; with NLW = 0 every wave loads its share (NI row groups per tile)
+    constexpr int NLW = kLoaderWaves;
+    static_assert(NLW > 0 || NBUF == 2, "without loading waves a stage is fetched while the one before it is computed");
+    constexpr int NI_L = NLW > 0 ? TILE_KEYS / ROWS_PER_LOAD / NLW : NI;
+    static_assert(NLW == 0 || NI_L * NLW * ROWS_PER_LOAD == TILE_KEYS, "the loading waves' instructions cover the tile's 64 rows exactly");
+    const bool loader = NLW > 0 && wave >= NW;
+    const int ldw = NLW > 0 ? wave - NW : wave;  // index among the waves that load
 
     // ---- workgroup -> (batch*head, query tile[, key split]); XCD-aware: workgroups are dealt
     // round-robin to the 8 XCDs, so give each XCD one contiguous range of the logical index.
@@ -364,7 +379,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     {
         const __bf16* qrow = Qh + (long long)q_token * p.qs.sn + 8 * hh;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qf[s] = *(const bf16x8*)(qrow + 16 * s);
+        for (int s = 0; s < KS; ++s)
+            if (!loader) qf[s] = *(const bf16x8*)(qrow + 16 * s);
     }
     const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
     const const_u64_ptr mask_tbl = (const_u64_ptr)p.mask_tbl;
@@ -414,9 +430,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     auto issue_tile = [&](int i, unsigned lds_tile) {
         int a, b;
         tile_origin(i, a, b);
-#pragma unroll
-        for (int n = 0; n < NI; ++n) {
-            const int ii = wave * NI + n;
+        auto load_row_group = [&](auto n_tag) __attribute__((always_inline)) {
+            const int ii = ldw * NI_L + decltype(n_tag)::value;
             const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
             int token;
             if (b < 0) {
@@ -430,7 +445,8 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             const unsigned chunk_off = (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
             load_to_lds_16B(Kh, (unsigned)token * k_pitch + chunk_off, lds_tile + ii * 1024);
             load_to_lds_16B(Vh, (unsigned)token * v_pitch + chunk_off, lds_tile + TILE_BYTES + ii * 1024);
-        }
+        };
+        static_for<NI_L>(load_row_group);  // (not a loop: one that contains inline asm is not unrolled)
     };
     // the same loads, not issued but written down (they ride in the compute pipeline of another tile)
     auto plan_tile = [&](int i, unsigned lds_tile) {
@@ -461,10 +477,69 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     };
     auto issue_stage = [&](int t, int buf) {  // the stage that starts at tile t goes to stage buffer buf
         const int len = stage_len(t);
-#pragma unroll
-        for (int j = 0; j < TPS; ++j)
+        auto load_tile = [&](auto j_tag) __attribute__((always_inline)) {
+            constexpr int j = decltype(j_tag)::value;
             if (j < len) issue_tile(t + j, lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
+        };
+        static_for<TPS>(load_tile);
     };
+
+    __shared__ int s_redo;  // set when the fast pass has to be repeated by the careful one
+    auto stage_sync = [&]() {
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    if (NLW > 0 && loader) {
+        // A loading wave walks the stage list like the computing waves, one barrier per stage, and stays one
+        // stage ahead: after the barrier that hands stage s over, everyone has left the other buffer, which it
+        // refills with stage s + 1.  Same barrier count as run_pass below, pass for pass.
+#ifdef CLEAR_LOADER_PRIO
+        __builtin_amdgcn_s_setprio(CLEAR_LOADER_PRIO);
+#endif
+        auto loader_pass = [&]() {
+            constexpr int PFD = NBUF - 1;        // stages in flight ahead of the one being computed
+            constexpr int LPS = TPS * 2 * NI_L;  // this wave's load instructions per full stage
+            static_assert(PFD == 1 || TPS == 1, "counting loads per stage needs stages of one size");
+            static_assert(PFD <= 3 && (PFD - 1) * LPS < 64, "the waits below are written out for up to three stages ahead");
+            int nx = 0, nbuf = 0, n_issued = 0;
+            for (int i = 0; i < PFD && nx < n_tiles; ++i) {
+                issue_stage(nx, nbuf);
+                nx += stage_len(nx);
+                nbuf = next_buf(nbuf);
+                ++n_issued;
+            }
+            int k = 0;
+            for (int t = 0; t < n_tiles; ++k) {
+                // stage k has landed once at most the loads of the stages issued after it are outstanding
+                const int ahead = n_issued - 1 - k;
+                if (PFD > 2 && ahead >= 2)
+                    wait_vmcnt<(PFD > 2 ? 2 * LPS : 0)>();
+                else if (PFD > 1 && ahead == 1)
+                    wait_vmcnt<(PFD > 1 ? LPS : 0)>();
+                else
+                    wait_vmcnt<0>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                t += stage_len(t);
+                if (nx < n_tiles) {
+                    issue_stage(nx, nbuf);
+                    nx += stage_len(nx);
+                    nbuf = next_buf(nbuf);
+                    ++n_issued;
+                }
+            }
+            wait_vmcnt<0>();
+        };
+        loader_pass();
+        __syncthreads();
+        if (s_redo != 0) {
+            __syncthreads();
+            loader_pass();
+            __syncthreads();
+        }
+        return;
+    }
 
     // ---- running softmax state: one query per lane (shared with lane ^ 32)
     WaveState ws;
@@ -487,14 +562,9 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
     // Stage hand-over: this wave's loads of the stage about to be computed have landed; after the barrier
     // so have everyone's, and every wave has left the other buffer, which is refilled with the next stage.
     int pf_tile = 0;  // first tile of the next stage to load
-    auto stage_sync = [&]() {
-        wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-    };
     auto begin_stage = [&](int buf) {
         stage_sync();
-        if (pf_tile < n_tiles) {
+        if (NLW == 0 && pf_tile < n_tiles) {
             issue_stage(pf_tile, buf ^ 1);
             pf_tile += stage_len(pf_tile);
         }
@@ -617,7 +687,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
         const TileLoads no_loads = {};
         // prologue: the first stage is in flight
         pf_tile = 0;
-        if (n_tiles > 0) {
+        if (NLW == 0 && n_tiles > 0) {
             issue_stage(0, 0);
             pf_tile = stage_len(0);
         }
@@ -636,7 +706,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                     careful_stage<CODE>(ws, qf, lo, si.tile_lds, si.cls0, si.cls1, si.linear, si.ma);
                 }
                 t += len;
-                buf ^= 1;
+                buf = next_buf(buf);
             }
         } else {
             // One loop per tile category (and per mode), so that every loop body has a single shape.  Each
@@ -647,7 +717,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             int t = 0;
 
             // whole linear tiles
-            for (; t < cb1 && adopting; t += TPS, buf ^= 1) {
+            for (; t < cb1 && adopting; t += TPS, buf = next_buf(buf)) {
                 begin_stage(buf);
 #pragma unroll 1
                 for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
@@ -658,10 +728,10 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             }
             // (the long key walk of the text-query kernel gains from loads that ride in the pipeline; the
             // image-query kernel, with its short lists and skipped tiles, is faster with the plain burst)
-            if (TEXTQ) {
-                for (; t < cb1; t += TPS, buf ^= 1) ride_stage(std::integral_constant<int, kMaskNone>{}, t, imin(TPS, cb1 - t), buf);
+            if (TEXTQ && NLW == 0) {
+                for (; t < cb1; t += TPS, buf = next_buf(buf)) ride_stage(std::integral_constant<int, kMaskNone>{}, t, imin(TPS, cb1 - t), buf);
             } else {
-                for (; t < cb1; t += TPS, buf ^= 1) {
+                for (; t < cb1; t += TPS, buf = next_buf(buf)) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
@@ -672,7 +742,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             }
             t = cb1;
             // the ragged linear tile: at most one, keep it simple
-            for (; t < cb2; t += TPS, buf ^= 1) {
+            for (; t < cb2; t += TPS, buf = next_buf(buf)) {
                 begin_stage(buf);
                 const TileInfo si = tile_info(t, buf, 0);
                 if (si.cls0 != kBlockSkip) {
@@ -683,7 +753,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             t = cb2;
             if constexpr (dense_image) {
                 // strided mask, tiles inside the class grid: every key of the tile is admitted for every query
-                for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
+                for (; t < cb3 && adopting; t += TPS, buf = next_buf(buf)) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
@@ -692,7 +762,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
-                for (; t < cb3; t += TPS, buf ^= 1) {
+                for (; t < cb3; t += TPS, buf = next_buf(buf)) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
@@ -704,7 +774,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
             if (!TEXTQ) {
                 // image tiles inside the grid (lane masks from the table); the strided variant has run them above
                 if constexpr (CODE != kCodeFull) {
-                for (; t < cb3 && adopting; t += TPS, buf ^= 1) {
+                for (; t < cb3 && adopting; t += TPS, buf = next_buf(buf)) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
@@ -713,7 +783,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
-                for (; t < cb3; t += TPS, buf ^= 1) {
+                for (; t < cb3; t += TPS, buf = next_buf(buf)) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
@@ -724,7 +794,7 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
                 }
                 t = cb3;
                 // image tiles cut by the border: few, keep them simple
-                for (; t < cb4; t += TPS, buf ^= 1) {
+                for (; t < cb4; t += TPS, buf = next_buf(buf)) {
                     begin_stage(buf);
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb4 - t); ++j) {
@@ -747,7 +817,6 @@ __global__ void __launch_bounds__(NWY* NWX * 64, (NWY * NWX <= 4) ? 2 : 1) clear
 
     // Fast pass first.  If any query of the workgroup met a score more than 2^FAST_HEADROOM_LOG2 above
     // its reference (in the exponent), the whole workgroup repeats the tile walk with the careful pass.
-    __shared__ int s_redo;
     if (tid == 0) s_redo = 0;  // ordered before any write below by the barriers of the stage loop
     const unsigned long long bad = run_pass(std::false_type{});
     if (bad != 0 && lane == 0) s_redo = 1;
@@ -853,7 +922,7 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(nblk), dim3(NWY * NWX * 64), smem, stream, p);
+    hipLaunchKernelGGL(kern, dim3(nblk), dim3((NWY * NWX + kLoaderWaves) * 64), smem, stream, p);
     return hipGetLastError();
 }
 
