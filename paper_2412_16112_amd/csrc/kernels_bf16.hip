@@ -14,8 +14,10 @@
 // A workgroup of NWY x NWX waves owns a (4*NWY) x (8*NWX) patch of image queries (or 32*NWY*NWX
 // text queries) and walks a list of 64-key tiles: the text keys, then the 8 x 8 image key tiles its
 // schedule row lists (Sec. 3.2: text keys for every query, image keys inside the radius-r disc).
-// K and V tiles are staged in LDS once per workgroup; every wave classifies each 32-key block
-// against its own 4 x 8 query patch and skips the blocks its disc cannot reach.
+// K and V tiles are staged in LDS once per workgroup, by four further waves that do nothing else
+// (one per SIMD, one stage ahead of the computing waves, one workgroup barrier per stage); every
+// computing wave classifies each 32-key block against its own 4 x 8 query patch and skips the blocks
+// its disc cannot reach.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -88,41 +90,6 @@ constexpr int kLoaderWaves = CLEAR_LOADER_WAVES;
 // Pins the instruction order: nothing is scheduled across this point.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// This wave's share of the staging loads of one tile: with 8 waves, 2 of the tile's 16 row groups (4 token
-// rows = 1 KB each) at head_dim 128, 1 of 8 (8 rows each) at head_dim 64, for K and for V.  Load k covers
-// row group k / 2, K for even k and V for odd k.
-constexpr int kRowGroupsPerWave = TILE_KEYS / ROWS_PER_LOAD / (kBf16NWY * kBf16NWX);
-constexpr int kTileLoads = 2 * kRowGroupsPerWave;
-struct TileLoads {
-    const void* ksrc;                  // the head's K and V arrays
-    const void* vsrc;
-    unsigned koff[kRowGroupsPerWave];  // per lane: byte offset of its 16-byte chunk in the K array ...
-    unsigned voff[kRowGroupsPerWave];  // ... and in the V array (the two may have different row pitches)
-    unsigned lds[kRowGroupsPerWave];   // LDS address of the row group in the tile's K half (V: + TILE_BYTES)
-};
-
-__device__ __forceinline__ void issue_tile_load(const TileLoads& tl, int k)
-{
-    load_to_lds_16B((k & 1) ? tl.vsrc : tl.ksrc, (k & 1) ? tl.voff[k >> 1] : tl.koff[k >> 1], tl.lds[k >> 1] + ((k & 1) ? TILE_BYTES : 0));
-}
-
-__device__ __forceinline__ void issue_tile_loads(const TileLoads& tl)
-{
-    static_assert(kTileLoads == 8 || kTileLoads == 4 || kTileLoads == 2, "written out: a loop around inline asm is not unrolled");
-    issue_tile_load(tl, 0);
-    issue_tile_load(tl, 1);
-    if constexpr (kTileLoads >= 4) {
-        issue_tile_load(tl, 2);
-        issue_tile_load(tl, 3);
-    }
-    if constexpr (kTileLoads >= 8) {
-        issue_tile_load(tl, 4);
-        issue_tile_load(tl, 5);
-        issue_tile_load(tl, 6);
-        issue_tile_load(tl, 7);
-    }
-}
-
 // f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}), in order.
 template <typename F, int... Is>
 __device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, Is...>)
@@ -150,13 +117,9 @@ __device__ __forceinline__ void static_for(F& f)
 // scores become -inf, its P zero), which keeps one code shape for every tile of a loop.
 // ADOPT = true while some query of the wave still has no reference maximum (the first tiles): the block
 // maxima are formed and adopted.  ADOPT = false afterwards: no maximum is needed at all.
-// RIDE = true: the wave's staging loads for one tile of the next stage (tl) are issued from inside the
-// pipeline, one every other slot from slot 1 on, instead of in a burst right after the barrier, when every
-// wave of the workgroup would be issuing loads and no matrix instruction.  No branch inside the pipeline:
-// all four always go out.
-template <int MASK, bool ADOPT, bool RIDE, int CODE>
+template <int MASK, bool ADOPT, int CODE>
 __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS], const LaneOffsets& lo,
-                                           unsigned tile_lds, const MaskArgs& ma, const TileLoads& tl)
+                                           unsigned tile_lds, const MaskArgs& ma)
 {
     constexpr int kb0 = 0;
     constexpr bool has1 = true;
@@ -200,8 +163,6 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS]
             else
                 op[(slot + PD) % RING] = v_operand(slot + PD);
         }
-        // a staging load for the next stage riding along (odd slots at the start)
-        if (RIDE && (slot & 1) && (slot >> 1) < kTileLoads) issue_tile_load(tl, slot >> 1);
         // matrix instruction of this slot
         constexpr int pv_i = slot >= PV0 ? slot - PV0 : 0, pv_db = pv_i % NDB, pv_s2 = (pv_i / NDB) & 1;
         if (slot < S1)
@@ -289,7 +250,7 @@ template <int NWY, int NWX, bool TEXTQ, int CODE>
 __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <= 4 && kLoaderWaves == 0) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
 {
     constexpr int NW = NWY * NWX;
-    constexpr int NI = kRowGroupsPerWave;  // 1 KB load instructions per wave per tile, for K and for V each
+    constexpr int NI = TILE_KEYS / ROWS_PER_LOAD / NW;  // 1 KB load instructions per wave per tile, for K and for V each, when every wave loads
     static_assert(NI * NW * ROWS_PER_LOAD == TILE_KEYS, "the waves' load instructions cover the tile's 64 rows exactly");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][K tile | V tile]
@@ -448,33 +409,6 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         };
         static_for<NI_L>(load_row_group);  // (not a loop: one that contains inline asm is not unrolled)
     };
-    // the same loads, not issued but written down (they ride in the compute pipeline of another tile)
-    auto plan_tile = [&](int i, unsigned lds_tile) {
-        TileLoads tl;
-        tl.ksrc = Kh;
-        tl.vsrc = Vh;
-        int a, b;
-        tile_origin(i, a, b);
-#pragma unroll
-        for (int n = 0; n < NI; ++n) {
-            const int ii = wave * NI + n;
-            const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
-            int token;
-            if (b < 0) {
-                token = imin(a + row, lin_limit - 1);
-                if (TEXTQ && token >= p.vkeys_text) token += p.vshift;
-            } else {
-                const int ky = imin(a + (row >> 3), kH - 1);
-                const int kx = imin(b + (row & 7), kW - 1);
-                token = p.n_text + (ky * stride + k_oy) * p.gridW + kx * stride + k_ox;
-            }
-            const unsigned chunk_off = (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
-            tl.koff[n] = (unsigned)token * k_pitch + chunk_off;
-            tl.voff[n] = (unsigned)token * v_pitch + chunk_off;
-            tl.lds[n] = lds_tile + ii * 1024;
-        }
-        return tl;
-    };
     auto issue_stage = [&](int t, int buf) {  // the stage that starts at tile t goes to stage buffer buf
         const int len = stage_len(t);
         auto load_tile = [&](auto j_tag) __attribute__((always_inline)) {
@@ -622,28 +556,6 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         return si;
     };
 
-    // Lean stage whose tiles carry the next stage's loads: tile j of this stage issues, from inside its
-    // pipeline, this wave's loads for slot j of the next stage (or at once, if the wave skips the tile).
-    // Where the next stage has no slot j the loads fetch a valid tile into a slot nothing reads.
-    auto ride_stage = [&](auto mask_tag, int t, int len, int buf) {
-        constexpr int MASK = decltype(mask_tag)::value;
-        stage_sync();
-        const int nx = pf_tile;
-        const int nx_len = pf_tile < n_tiles ? stage_len(pf_tile) : 0;
-        pf_tile += nx_len;
-#pragma unroll 1
-        for (int j = 0; j < len; ++j) {
-            const TileInfo si = tile_info(t + j, buf, j);
-            const TileLoads tl = plan_tile(imin(nx + j, n_tiles - 1), lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
-            if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip)
-                fast_stage<MASK, false, true, CODE>(ws, qf, lo, si.tile_lds, si.ma, tl);
-            else
-                issue_tile_loads(tl);
-        }
-#pragma unroll 1
-        for (int j = len; j < nx_len; ++j) issue_tile(nx + j, lds_base + (unsigned)(buf ^ 1) * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
-    };
-
     // Prologue of the block on the query row (RMS norm over the head's channels - this lane holds half of them,
     // lane ^ 32 the others -, rotary embedding for image queries, back to bf16).  Runs once, after the first
     // stage's loads have been issued, so that the wait for the row and for the tables overlaps them.
@@ -684,7 +596,6 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         ws.m_run = M_INIT;
         ws.l_run = 0.f;
         unsigned long long bad = 0;
-        const TileLoads no_loads = {};
         // prologue: the first stage is in flight
         pf_tile = 0;
         if (NLW == 0 && n_tiles > 0) {
@@ -722,22 +633,16 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
 #pragma unroll 1
                 for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
                     const TileInfo si = tile_info(t + j, buf, j);
-                    if (wave_has_queries) fast_stage<kMaskNone, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    if (wave_has_queries) fast_stage<kMaskNone, true, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                 }
                 adopting = wave_has_queries && still_adopting();
             }
-            // (the long key walk of the text-query kernel gains from loads that ride in the pipeline; the
-            // image-query kernel, with its short lists and skipped tiles, is faster with the plain burst)
-            if (TEXTQ && NLW == 0) {
-                for (; t < cb1; t += TPS, buf = next_buf(buf)) ride_stage(std::integral_constant<int, kMaskNone>{}, t, imin(TPS, cb1 - t), buf);
-            } else {
-                for (; t < cb1; t += TPS, buf = next_buf(buf)) {
-                    begin_stage(buf);
+            for (; t < cb1; t += TPS, buf = next_buf(buf)) {
+                begin_stage(buf);
 #pragma unroll 1
-                    for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
-                        const TileInfo si = tile_info(t + j, buf, j);
-                        if (wave_has_queries) fast_stage<kMaskNone, false, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
-                    }
+                for (int j = 0; j < imin(TPS, cb1 - t); ++j) {
+                    const TileInfo si = tile_info(t + j, buf, j);
+                    if (wave_has_queries) fast_stage<kMaskNone, false, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                 }
             }
             t = cb1;
@@ -746,7 +651,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
                 begin_stage(buf);
                 const TileInfo si = tile_info(t, buf, 0);
                 if (si.cls0 != kBlockSkip) {
-                    fast_stage<kMaskLinear, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                    fast_stage<kMaskLinear, true, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                     adopting = still_adopting();
                 }
             }
@@ -758,7 +663,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (wave_has_queries) fast_stage<kMaskNone, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (wave_has_queries) fast_stage<kMaskNone, true, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
@@ -767,7 +672,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (wave_has_queries) fast_stage<kMaskNone, false, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (wave_has_queries) fast_stage<kMaskNone, false, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                     }
                 }
             }
@@ -779,7 +684,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                     }
                     adopting = wave_has_queries && still_adopting();
                 }
@@ -788,7 +693,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                     }
                 }
                 }
@@ -799,7 +704,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
 #pragma unroll 1
                     for (int j = 0; j < imin(TPS, cb4 - t); ++j) {
                         const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true, false, CODE>(ws, qf, lo, si.tile_lds, si.ma, no_loads);
+                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskImage, true, CODE>(ws, qf, lo, si.tile_lds, si.ma);
                     }
                 }
             }
