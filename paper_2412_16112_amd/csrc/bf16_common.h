@@ -92,20 +92,18 @@ __device__ __forceinline__ void wait_vmcnt()
 
 // Query/key prologue on 8 consecutive channels (4 rotary pairs) of one token, in fp32: RMS-norm gain, then
 // the rotation by the sum of the row angle and the column angle (tables hold (cos, sin) per pair).
-// gain8 / ry8 / rx8 point at this chunk's 8 floats of the gain vector and of the token's two table rows.
-__device__ __forceinline__ void prologue_chunk(float (&x)[8], float inv_rms, const float* gain8, const float* ry8, const float* rx8)
+// g0, g1: this chunk's 8 gains; a0, a1 / b0, b1: its 8 floats of the token's row / column table rows.
+__device__ __forceinline__ void prologue_chunk_values(float (&x)[8], float inv_rms, bool has_gain, const f32x4& g0, const f32x4& g1,
+                                                      bool turn, const f32x4& a0, const f32x4& a1, const f32x4& b0, const f32x4& b1)
 {
-    if (gain8) {
-        const f32x4 g0 = *(const f32x4*)gain8, g1 = *(const f32x4*)(gain8 + 4);
+    if (has_gain) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             x[j] = x[j] * inv_rms * g0[j];
             x[4 + j] = x[4 + j] * inv_rms * g1[j];
         }
     }
-    if (ry8) {
-        const f32x4 a0 = *(const f32x4*)ry8, a1 = *(const f32x4*)(ry8 + 4);
-        const f32x4 b0 = *(const f32x4*)rx8, b1 = *(const f32x4*)(rx8 + 4);
+    if (turn) {
         const float cy[4] = {a0[0], a0[2], a1[0], a1[2]}, sy[4] = {a0[1], a0[3], a1[1], a1[3]};
         const float cx[4] = {b0[0], b0[2], b1[0], b1[2]}, sx[4] = {b0[1], b0[3], b1[1], b1[3]};
 #pragma unroll
@@ -117,6 +115,24 @@ __device__ __forceinline__ void prologue_chunk(float (&x)[8], float inv_rms, con
             x[2 * t + 1] = s * e + c * o;
         }
     }
+}
+// The same, fetching the chunk's table entries: gain8 / ry8 / rx8 point at its 8 floats of the gain vector and
+// of the token's two table rows (null: that step is skipped).
+__device__ __forceinline__ void prologue_chunk(float (&x)[8], float inv_rms, const float* gain8, const float* ry8, const float* rx8)
+{
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 g0 = zero, g1 = zero, a0 = zero, a1 = zero, b0 = zero, b1 = zero;
+    if (gain8) {
+        g0 = *(const f32x4*)gain8;
+        g1 = *(const f32x4*)(gain8 + 4);
+    }
+    if (ry8) {
+        a0 = *(const f32x4*)ry8;
+        a1 = *(const f32x4*)(ry8 + 4);
+        b0 = *(const f32x4*)rx8;
+        b1 = *(const f32x4*)(rx8 + 4);
+    }
+    prologue_chunk_values(x, inv_rms, gain8 != nullptr, g0, g1, ry8 != nullptr, a0, a1, b0, b1);
 }
 
 struct WaveState {

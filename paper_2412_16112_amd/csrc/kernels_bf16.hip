@@ -568,18 +568,38 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
             for (int j = 0; j < 8; ++j) ss += (float)qf[s][j] * (float)qf[s][j];
         ss = wave_pair_sum(ss);
         const float inv_rms = 1.0f / sqrtf(ss * (1.0f / D) + p.norm_eps);
+        const bool has_gain = p.q_gain != nullptr;
         const bool turn = !TEXTQ && p.rope_y;
-        const float* const ry = p.rope_y + (size_t)(imin(qy, qH - 1) * stride + q_oy) * D;
-        const float* const rx = p.rope_x + (size_t)(imin(qx, qW - 1) * stride + q_ox) * D;
+        // Table entries are fetched without branches, half of the chunks at a time, so that the loads of a half
+        // are in flight together (one memory round trip per half, not one per chunk).  A step that is switched
+        // off reads the other step's table instead (any D readable floats) and ignores what it read.
+        const float* const any_table = has_gain ? p.q_gain : p.rope_y;
+        const float* const ysrc = turn ? p.rope_y + (size_t)(imin(qy, qH - 1) * stride + q_oy) * D : any_table;
+        const float* const xsrc = turn ? p.rope_x + (size_t)(imin(qx, qW - 1) * stride + q_ox) * D : any_table;
+        constexpr int HALF = KS / 2;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int c0 = 16 * s + 8 * hh;
-            float x[8];
+        for (int h0 = 0; h0 < KS; h0 += HALF) {
+            f32x4 g[HALF][2], a[HALF][2], b[HALF][2];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) x[j] = (float)qf[s][j];
-            prologue_chunk(x, inv_rms, p.q_gain ? p.q_gain + c0 : nullptr, turn ? ry + c0 : nullptr, turn ? rx + c0 : nullptr);
+            for (int i = 0; i < HALF; ++i) {
+                const int c0 = 16 * (h0 + i) + 8 * hh;
+                g[i][0] = *(const f32x4*)(any_table + c0);
+                g[i][1] = *(const f32x4*)(any_table + c0 + 4);
+                a[i][0] = *(const f32x4*)(ysrc + c0);
+                a[i][1] = *(const f32x4*)(ysrc + c0 + 4);
+                b[i][0] = *(const f32x4*)(xsrc + c0);
+                b[i][1] = *(const f32x4*)(xsrc + c0 + 4);
+            }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) qf[s][j] = (__bf16)x[j];
+            for (int i = 0; i < HALF; ++i) {
+                const int s = h0 + i;
+                float x[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) x[j] = (float)qf[s][j];
+                prologue_chunk_values(x, inv_rms, has_gain, g[i][0], g[i][1], turn, a[i][0], a[i][1], b[i][0], b[i][1]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) qf[s][j] = (__bf16)x[j];
+            }
         }
     }
 
