@@ -428,9 +428,6 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         // A loading wave walks the stage list like the computing waves, one barrier per stage, and stays one
         // stage ahead: after the barrier that hands stage s over, everyone has left the other buffer, which it
         // refills with stage s + 1.  Same barrier count as run_pass below, pass for pass.
-#ifdef CLEAR_LOADER_PRIO
-        __builtin_amdgcn_s_setprio(CLEAR_LOADER_PRIO);
-#endif
         auto loader_pass = [&]() {
             constexpr int PFD = NBUF - 1;        // stages in flight ahead of the one being computed
             constexpr int LPS = TPS * 2 * NI_L;  // this wave's load instructions per full stage
