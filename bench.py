@@ -34,6 +34,8 @@ def main():
                     help="row-band mode: time ONE band of the workload cut into this many bands (one GPU's share of a "
                          "patch-parallel run; no second GPU is used)")
     ap.add_argument("--band", type=int, default=-1, help="which band (default: a middle one, halo on both sides)")
+    ap.add_argument("--halo-align", type=int, default=1,
+                    help="row-band mode: widen the top halo to a multiple of this many rows (16 = the query tile: the owned rows then start on a tile boundary)")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (dQ, dK, dV from dO and the forward pass's log-sum-exp) instead of the forward pass")
     ap.add_argument("--mask", default="disc", choices=["disc", "square", "swin", "strided"],
@@ -334,6 +336,8 @@ def bench_band(args, w, dev):
 
     band = args.band if args.band >= 0 else args.bands // 2
     y0, y1, ht, hb = ca.clear_attn_band_layout(w.gridH, w.r, args.bands, band)
+    if ht:
+        ht = min(y0, -(-ht // args.halo_align) * args.halo_align)
     rows = ht + (y1 - y0) + hb
     wl = dataclasses.replace(w, name="%s band %d/%d" % (w.name, band, args.bands), gridH=rows)
     Q, K, V = make_qkv(wl, dev)

@@ -14,14 +14,18 @@ from tests.parity_util import TOL, error_metrics
 pytestmark = pytest.mark.gpu
 
 
-def run_bands(Q, K, V, n_text, gridH, gridW, r, n_bands, mode):
-    """Returns O [B, H, N, d] assembled from n_bands band passes (each on its own local copy of the tokens)."""
+def run_bands(Q, K, V, n_text, gridH, gridW, r, n_bands, mode, halo_align=1):
+    """Returns O [B, H, N, d] assembled from n_bands band passes (each on its own local copy of the tokens).
+    halo_align > 1: the top halo is widened to a multiple of that many rows (more neighbour rows than the r - 1
+    the mask can reach, e.g. so that the owned rows start on a query-tile boundary)."""
     B, H, N, d = Q.shape
     dev = Q.device
     O = torch.zeros_like(Q)
     parts_o, parts_lse = [], []
     for band in range(n_bands):
         y0, y1, ht, hb = ca.clear_attn_band_layout(gridH, r, n_bands, band)
+        if ht:
+            ht = min(y0, -(-ht // halo_align) * halo_align)
         rows = slice(n_text + (y0 - ht) * gridW, n_text + (y1 + hb) * gridW)
         loc = [torch.cat([t[:, :, :n_text], t[:, :, rows]], dim=2).contiguous() for t in (Q, K, V)]
         Ol = torch.full_like(loc[0], float("nan"))
@@ -68,6 +72,17 @@ def test_bands_exact_equal_the_undivided_problem(dtype, n_text, gridH, gridW, d,
     ref = orc.attention(Q.float().cpu().numpy(), K.float().cpu().numpy(), V.float().cpu().numpy(), n_text, gridH, gridW, r)
     max_abs, rel_rms = error_metrics(O.float().cpu().numpy(), ref)
     assert max_abs <= TOL[dtype][0] and rel_rms <= TOL[dtype][1], (max_abs, rel_rms)
+
+
+def test_bands_with_a_tile_aligned_halo():
+    """A halo wider than r - 1 rows (here: widened to the 16 rows of a query tile) changes nothing: the extra
+    rows are out of every owned query's reach."""
+    n_text, gridH, gridW, d, r, H, n_bands = 64, 96, 40, 128, 8, 1, 3
+    Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, "bf16", seed=321, device="cuda:0")
+    O = run_bands(Q, K, V, n_text, gridH, gridW, r, n_bands, ca.CLEAR_MERGE_EXACT, halo_align=16)
+    ref = orc.attention(Q.float().cpu().numpy(), K.float().cpu().numpy(), V.float().cpu().numpy(), n_text, gridH, gridW, r)
+    max_abs, rel_rms = error_metrics(O.float().cpu().numpy(), ref)
+    assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
 
 
 @pytest.mark.parametrize("dtype,n_text,gridH,gridW,d,r,H,n_bands", [c for c in CASES if c[1] > 0])
