@@ -245,8 +245,10 @@ int clear_attn_band_layout(int gridH_total, int r, int n_bands, int band, int* y
 
 /* Forward pass of one band.  ctx, Q, K, V, O, B .. r, stream: as for clear_attn_forward, for the local grid.
  * Image queries: only the rows [own_y0, own_y1) of the local grid are computed and written to O (exactly
- * their output in the undivided problem when the halo holds the r - 1 neighbouring rows); halo rows of O
- * are left untouched, and so are the text rows.
+ * their output in the undivided problem when the halo holds the r - 1 neighbouring rows, or more of them: rows
+ * beyond r - 1 are out of every owned query's reach, and a top halo of a whole number of 16-row query tiles
+ * saves the workgroups that would straddle the first owned row); halo rows of O are left untouched, and so
+ * are the text rows.
  * Text queries: attend to the owned image rows and, if text_keys != 0, to the text keys; the softmax output
  * over those keys goes to text_o (device, fp32, [B, H, n_text, head_dim]) and the natural logarithm of the
  * softmax denominator sum_j exp(q.k_j / sqrt(head_dim)) to text_lse (device, fp32, [B, H, n_text]); both
