@@ -6,6 +6,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "block_class.h"
 #include "clear_internal.h"
 
@@ -304,6 +307,21 @@ __device__ __forceinline__ void pv_block(f32x16 (&oacc)[NDB], const TileAddr& ta
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
             oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db), pf[s2], oacc[db], 0, 0, 0);
+}
+
+// Pins the instruction order: nothing is scheduled across this point.
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}), in order.
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 }  // namespace

@@ -20,9 +20,6 @@
 // its disc cannot reach.
 #include <hip/hip_runtime.h>
 
-#include <type_traits>
-#include <utility>
-
 #include "bf16_common.h"
 #include "block_class.h"
 #include "clear_internal.h"
@@ -86,21 +83,6 @@ __device__ __forceinline__ void adopt_reference(WaveState& ws, float mx_pair)
 #define CLEAR_LOADER_WAVES 4
 #endif
 constexpr int kLoaderWaves = CLEAR_LOADER_WAVES;
-
-// Pins the instruction order: nothing is scheduled across this point.
-#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
-// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}), in order.
-template <typename F, int... Is>
-__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F& f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
 
 // Fast pass, one staged tile.  The reference maximum of a query never moves once set, so O is only
 // ever touched by the matrix pipeline and there is no data-dependent branch.

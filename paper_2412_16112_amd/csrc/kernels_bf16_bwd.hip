@@ -18,8 +18,8 @@
 // lse and delta belong to the query: a per-lane scalar for dQ, a per-column vector (staged next to the tile)
 // for dK and dV.  Text rows sum over every token: they are split along the columns into partial sums that a
 // small kernel adds up, like the text-query rows of the forward pass.  dK and dV of a key tile are produced
-// by one pass from one S and one dP (the separate modes remain for reference).  Plain block-by-block code, no
-// hand-ordered pipeline.
+// by one pass from one S and one dP (the separate modes remain for reference).  The dQ blocks are a hand-ordered
+// pipeline like the forward kernel's tiles (do_block_q); the dK / dV blocks are plain block-by-block code.
 #include <hip/hip_runtime.h>
 
 #include "bf16_common.h"
@@ -28,6 +28,9 @@
 
 #ifndef CLEAR_BWD_FUSED_KV
 #define CLEAR_BWD_FUSED_KV 1
+#endif
+#ifndef CLEAR_BWD_PIPELINED_Q
+#define CLEAR_BWD_PIPELINED_Q 1  // dQ blocks as a hand-ordered pipeline (0: the compiler's order, as for dK and dV)
 #endif
 
 #if CLEAR_HEAD_DIM == 64
@@ -301,6 +304,64 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         pv_block(acc, tt, blk, xf);
     };
 
+    // The same block for dQ (lse and delta are the lane's own scalars, 64 accumulator registers: there is room)
+    // as a hand-ordered pipeline in the manner of the forward kernel: 2 KS + 2 NDB matrix instructions in
+    // program order, each LDS operand read two slots ahead of the instruction that consumes it,
+    //   slots [0, KS)        S = K q^T
+    //   slots [KS, 2 KS)     dP = V dO^T            | mask, P = 2^(S c - lse) of the finished S
+    //   slots [2 KS, end)    dQ^T += K^T dS^T       | dS = P (dP - delta) first, in slot 2 KS
+    auto do_block_q = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma) __attribute__((always_inline)) {
+        constexpr int MASK = decltype(mask_tag)::value;
+        TileAddr t1, t2, tt;
+        t1.kb = tile_lds + lo.k0;
+        t2.kb = tile_lds + TILE_BYTES + lo.k0;
+        tt.vb0 = tile_lds + lo.v0;
+        tt.vb1 = tile_lds + (lo.v0 ^ V_HI);
+        t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = 0;
+        constexpr int S_END = KS, DP_END = 2 * KS, NSLOT = 2 * KS + 2 * NDB;
+        auto operand = [&](int slot) {
+            if (slot < S_END) return read_k_operand(t1, blk, slot);
+            if (slot < DP_END) return read_k_operand(t2, blk, slot - S_END);
+            const int i = slot - DP_END;  // s2-major, so that consecutive instructions write different accumulators
+            return read_v_operand(tt, blk, i / NDB, i % NDB);
+        };
+        constexpr int PD = 2, RING = PD + 2;
+        bf16x8 op[RING];
+#pragma unroll
+        for (int i = 0; i < PD; ++i) op[i] = operand(i);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 sc = zero, dp = zero;
+        bf16x8 xf[2];
+        auto run_slot = [&](auto slot_tag) __attribute__((always_inline)) {
+            constexpr int slot = decltype(slot_tag)::value;
+            if (slot + PD < NSLOT) op[(slot + PD) % RING] = operand(slot + PD);
+            if (slot == DP_END) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xf[r >> 3][r & 7] = (__bf16)(sc[r] * (dp[r] - delta_row));
+            }
+            if (slot < S_END)
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], r1f[slot], sc, 0, 0, 0);
+            else if (slot < DP_END)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], r2f[slot - S_END], dp, 0, 0, 0);
+            else {
+                constexpr int i = slot >= DP_END ? slot - DP_END : 0;
+                acc[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], xf[i / NDB], acc[i % NDB], 0, 0, 0);
+            }
+            if (slot == S_END) apply_mask<MASK, CODE>(sc, blk, ma);
+            // the exponentials of the finished scores, 16 / KS per slot under the dP products
+            constexpr int EPS = 16 / KS;
+            if (slot >= S_END && slot < DP_END) {
+#pragma unroll
+                for (int e = 0; e < EPS; ++e) {
+                    const int r = (slot - S_END) * EPS + e;
+                    sc[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], c, -lse2_row));
+                }
+            }
+            SCHED_FENCE();
+        };
+        static_for<NSLOT>(run_slot);
+    };
+
     int pf_tile = 0;
     int pend_len = 0;  // tiles of the stage whose statistics are in flight
     auto begin_stage = [&](int buf) {
@@ -353,8 +414,13 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         }
         const unsigned tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
         const float* tile_stats = stats + ((buf * TPS + j) * 2) * TILE_KEYS;
-        if (cls0 != kBlockSkip) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
-        if (cls1 != kBlockSkip) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
+        if constexpr (MODE == kBwdQ && CLEAR_BWD_PIPELINED_Q) {
+            if (cls0 != kBlockSkip) do_block_q(mask_tag, tile_lds, 0, ma);
+            if (cls1 != kBlockSkip) do_block_q(mask_tag, tile_lds, 1, ma);
+        } else {
+            if (cls0 != kBlockSkip) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
+            if (cls1 != kBlockSkip) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
+        }
     };
     auto run_category = [&](auto mask_tag, int& t, int end, int& buf) __attribute__((always_inline)) {
         for (; t < end; t += TPS, buf ^= 1) {
