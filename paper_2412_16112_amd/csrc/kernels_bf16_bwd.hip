@@ -19,7 +19,8 @@
 // for dK and dV.  Text rows sum over every token: they are split along the columns into partial sums that a
 // small kernel adds up, like the text-query rows of the forward pass.  dK and dV of a key tile are produced
 // by one pass from one S and one dP (the separate modes remain for reference).  The dQ blocks are a hand-ordered
-// pipeline like the forward kernel's tiles (do_block_q); the dK / dV blocks are plain block-by-block code.
+// pipeline like the forward kernel's tiles (do_block_q), and so are the dK / dV blocks at head_dim 64 (do_block_kv);
+// at head_dim 128 the dK / dV blocks are plain block-by-block code.
 #include <hip/hip_runtime.h>
 
 #include "bf16_common.h"
@@ -28,6 +29,9 @@
 
 #ifndef CLEAR_BWD_FUSED_KV
 #define CLEAR_BWD_FUSED_KV 1
+#endif
+#ifndef CLEAR_BWD_PIPELINED_KV
+#define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64)  // dK + dV blocks hand-ordered too where the registers allow it
 #endif
 #ifndef CLEAR_BWD_PIPELINED_Q
 #define CLEAR_BWD_PIPELINED_Q 1  // dQ blocks as a hand-ordered pipeline (0: the compiler's order, as for dK and dV)
@@ -362,6 +366,77 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         static_for<NSLOT>(run_slot);
     };
 
+    // The fused dK + dV block in the same manner, 2 KS + 4 NDB matrix instructions.  Used at head_dim 64 only: at
+    // 128 channels the kernel has no registers for the operand ring (tried: more spills, a slower pass).
+    //   slots [0, KS)            S = Q k^T
+    //   slots [KS, 2 KS)         dP = dO v^T          | mask, P = 2^(S c - lse) of the finished S
+    //   next 2 NDB slots         dV^T += dO^T P^T     | dS = P (dP - delta)
+    //   last 2 NDB slots         dK^T += Q^T dS^T
+    auto do_block_kv = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma, const float* tile_stats) __attribute__((always_inline)) {
+        constexpr int MASK = decltype(mask_tag)::value;
+        TileAddr t1, t2, tt, tv;
+        t1.kb = tile_lds + lo.k0;
+        t2.kb = tile_lds + TILE_BYTES + lo.k0;
+        tt.vb0 = tile_lds + lo.v0;
+        tt.vb1 = tile_lds + (lo.v0 ^ V_HI);
+        tv.vb0 = tile_lds + TILE_BYTES + lo.v0;
+        tv.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
+        t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = tv.kb = 0;
+        constexpr int S_END = KS, DP_END = 2 * KS, DV_END = DP_END + 2 * NDB, NSLOT = DV_END + 2 * NDB;
+        auto operand = [&](int slot) {
+            if (slot < S_END) return read_k_operand(t1, blk, slot);
+            if (slot < DP_END) return read_k_operand(t2, blk, slot - S_END);
+            if (slot < DV_END) return read_v_operand(tv, blk, (slot - DP_END) / NDB, (slot - DP_END) % NDB);
+            return read_v_operand(tt, blk, (slot - DV_END) / NDB, (slot - DV_END) % NDB);
+        };
+        constexpr int PD = 2, RING = PD + 2;
+        bf16x8 op[RING];
+#pragma unroll
+        for (int i = 0; i < PD; ++i) op[i] = operand(i);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 sc = zero, dp = zero;
+        bf16x8 pf[2], xf[2];
+        const float* const st = tile_stats + 32 * blk + 4 * hh;  // statistics of this lane's 16 columns: 4 groups of 4
+        constexpr int GS = KS / 4;  // slots per group of four columns under the dP products
+        static_assert(KS % 4 == 0 && 2 * NDB >= 4, "four column groups are spread over the dP slots and the first dV slots");
+        auto run_slot = [&](auto slot_tag) __attribute__((always_inline)) {
+            constexpr int slot = decltype(slot_tag)::value;
+            if (slot + PD < NSLOT) op[(slot + PD) % RING] = operand(slot + PD);
+            if (slot < S_END)
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], r1f[slot], sc, 0, 0, 0);
+            else if (slot < DP_END)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], r2f[slot - S_END], dp, 0, 0, 0);
+            else if (slot < DV_END) {
+                constexpr int i = slot >= DP_END && slot < DV_END ? slot - DP_END : 0;
+                acc_v[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf[i / NDB], acc_v[i % NDB], 0, 0, 0);
+            } else {
+                constexpr int i = slot >= DV_END ? slot - DV_END : 0;
+                acc[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], xf[i / NDB], acc[i % NDB], 0, 0, 0);
+            }
+            if (slot == S_END) apply_mask<MASK, CODE>(sc, blk, ma);
+            // P under the dP products: one group of four columns (one 16-byte read of their lse) every GS slots
+            if (slot >= S_END && slot < DP_END && (slot - S_END) % GS == 0) {
+                constexpr int g = slot >= S_END ? (slot - S_END) / GS : 0;
+                const f32x4 l2 = *(const f32x4*)(st + 8 * g);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) sc[4 * g + u] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[4 * g + u], c, -l2[u]));
+                if (g == 1 || g == 3) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) pf[g >> 1][u] = (__bf16)sc[8 * (g >> 1) + u];
+                }
+            }
+            // dS under the dV products, a group of four columns per slot from the second one on
+            if (slot > DP_END && slot <= DP_END + 4) {
+                constexpr int g = slot > DP_END ? slot - DP_END - 1 : 0;
+                const f32x4 dl = *(const f32x4*)(st + TILE_KEYS + 8 * g);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) xf[g >> 1][4 * (g & 1) + u] = (__bf16)(sc[4 * g + u] * (dp[4 * g + u] - dl[u]));
+            }
+            SCHED_FENCE();
+        };
+        static_for<NSLOT>(run_slot);
+    };
+
     int pf_tile = 0;
     int pend_len = 0;  // tiles of the stage whose statistics are in flight
     auto begin_stage = [&](int buf) {
@@ -417,6 +492,9 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         if constexpr (MODE == kBwdQ && CLEAR_BWD_PIPELINED_Q) {
             if (cls0 != kBlockSkip) do_block_q(mask_tag, tile_lds, 0, ma);
             if (cls1 != kBlockSkip) do_block_q(mask_tag, tile_lds, 1, ma);
+        } else if constexpr (MODE == kBwdKV && CLEAR_BWD_PIPELINED_KV) {
+            if (cls0 != kBlockSkip) do_block_kv(mask_tag, tile_lds, 0, ma, tile_stats);
+            if (cls1 != kBlockSkip) do_block_kv(mask_tag, tile_lds, 1, ma, tile_stats);
         } else {
             if (cls0 != kBlockSkip) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
             if (cls1 != kBlockSkip) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
