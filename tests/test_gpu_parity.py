@@ -215,3 +215,21 @@ def test_small_problem_on_a_side_stream_back_to_back():
         ref = orc.attention(Q, K, V, n_text, gh, gw, r)
         max_abs, rel_rms = error_metrics(O.float().cpu().numpy(), ref)
         assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
+
+
+def test_bf16_many_launches_give_the_same_bits():
+    """The staged tiles pass from the loading waves to the computing waves once per stage; a missed hand-over
+    would show as a run-to-run difference.  Thirty launches in a row, interleaved with a poisoned output."""
+    w = WORKLOADS["flux-1024"]
+    _announce("workload flux-1024, 30 launches")
+    Q, K, V = make_qkv(w, DEV)
+    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, ca.CLEAR_BF16)
+    try:
+        ref = ctx.forward(Q, K, V).clone()
+        O = torch.empty_like(ref)
+        for _ in range(30):
+            O.fill_(float("nan"))
+            ctx.forward(Q, K, V, O)
+            assert torch.equal(O.view(torch.int16), ref.view(torch.int16))
+    finally:
+        ctx.destroy()
