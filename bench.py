@@ -99,13 +99,21 @@ def main():
         step = lambda: ctx.forward(Q, K, V, O)
     for _ in range(args.warmup):
         step()
+    # Exactly `steps` timed calls between two synchronisations: `ms_per_step` is the wall-clock mean over them;
+    # a HIP event on the launch stream before and after every call gives the per-call times, whose median is
+    # reported beside it (the events are recorded on the stream the library launches on: torch's current one).
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    events[0].record()
+    for i in range(args.steps):
         step()
+        events[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_call_ms = sorted(events[i].elapsed_time(events[i + 1]) for i in range(args.steps))
+    ms_median = per_call_ms[len(per_call_ms) // 2] if len(per_call_ms) % 2 else 0.5 * (per_call_ms[len(per_call_ms) // 2 - 1] + per_call_ms[len(per_call_ms) // 2])
     if args.layout == "bnhd":
         O.copy_(Os)  # for the check against the oracle below
 
@@ -144,6 +152,7 @@ def main():
     result = {
         "metric": "local-attn useful TFLOP/s (4*sumM*d)", "value": useful_tflops, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": ms_median, "ms_per_step_min": per_call_ms[0], "ms_per_step_max": per_call_ms[-1],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": (w.name if args.mask == "disc" else "%s mask=%s shift=%d" % (w.name, args.mask, args.shift))
                                + ("" if args.layout == "bhnd" else " layout=[B,N,H,d]"),

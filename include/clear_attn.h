@@ -17,7 +17,10 @@
  *
  * Supported: dtype CLEAR_BF16 with head_dim 128 or 64 (MFMA path; fp32 accumulation, one round-to-nearest
  * -even to bf16 on output) and dtype CLEAR_F32 with head_dim 64 (plain fp32 accuracy path).
- * n_text >= 0, gridH, gridW >= 1, r >= 1, N < 2^31 / head_dim is NOT required (64-bit offsets).
+ * n_text >= 0, gridH, gridW >= 1 (at most 32767 each), r >= 1.  bf16 contexts need N < 2^24 (the kernels address
+ * one head with 32-bit byte offsets) and clear_attn_create refuses more with CLEAR_ERR_UNSUPPORTED, as it refuses
+ * a tile schedule of more than 2^31 - 1 (query tile, key tile) pairs (r close to the grid size on a large grid);
+ * fp32 contexts need N < 2^31.  Offsets across heads and batch items are 64-bit.
  *
  * Errors: every function returns a clear_status; nothing throws or aborts; invalid arguments are
  * rejected before any device work.  clear_attn_last_error gives a human-readable reason.
@@ -64,9 +67,13 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
 
 /*
  * Pre-sizes the workspace that the text-query rows need (partial results of the key-split dense
- * pass, Sec. 3.2 "each text query gathers from all text and image tokens") for batch*heads = BH.
+ * pass; text-query rows are dense over all tokens, Sec. 3.2, Eq. 3) for batch*heads = BH.
  * forward() calls this itself when it meets a larger B*H than any before, which allocates and
- * synchronises; call reserve first if forward must not allocate.  Returns CLEAR_ERR_ALLOC on failure.
+ * synchronises; call reserve first if forward must not allocate.  A forward call (any variant, backward
+ * included) that would have to grow a workspace while `stream` is being captured into a HIP graph returns
+ * CLEAR_ERR_INVALID_ARG instead and launches nothing: reserve beforehand, or make one eager call first; a
+ * small problem whose second stream no earlier call has created stays on `stream` alone under capture.
+ * Returns CLEAR_ERR_ALLOC on failure.
  */
 int clear_attn_reserve(clear_attn_ctx* ctx, int BH);
 

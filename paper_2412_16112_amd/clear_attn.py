@@ -148,6 +148,23 @@ def _dtype_code(t):
     raise ClearAttnError(CLEAR_ERR_UNSUPPORTED, "tensors must be bfloat16 or float32")
 
 
+def _check_plain(ref, named, what="tensors"):
+    """The plain-layout entry points read their tensors as packed [B, H, N, head_dim] arrays: every tensor in `named`
+    (name -> tensor, None entries skipped) must be a contiguous device tensor on ref's device with ref's shape and dtype."""
+    for name, t in named.items():
+        if t is None:
+            continue
+        if not (t.is_cuda and t.device == ref.device and t.is_contiguous() and t.dim() == 4 and t.dtype == ref.dtype and t.shape == ref.shape):
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "%s: %s must be a contiguous device tensor with the shape, dtype and device of Q "
+                                 "(use the *_strided entry points for transposed or sliced views)" % (what, name))
+
+
+def _check_f32(ref, name, t, shape):
+    import torch
+    if t is not None and not (t.is_cuda and t.device == ref.device and t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == tuple(shape)):
+        raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "%s must be a contiguous fp32 device tensor of shape %s" % (name, tuple(shape)))
+
+
 class ClearAttn:
     """Owns one clear_attn_ctx (clear_attn_create / clear_attn_forward / clear_attn_destroy)."""
 
@@ -168,14 +185,7 @@ class ClearAttn:
         """Q, K, V: contiguous device tensors [B, H, N, head_dim]; enqueues on `stream` (default: torch's current)."""
         import torch
         n_text, gridH, gridW, head_dim, r = self.shape
-        for t in (Q, K, V):
-            if not (t.is_cuda and t.is_contiguous() and t.dim() == 4 and t.dtype == Q.dtype and t.shape == Q.shape):
-                raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "Q, K, V must be contiguous device tensors of one shape and dtype")
-        if _dtype_code(Q) != self.dtype:
-            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor dtype differs from the context's")
-        B, H, N, d = Q.shape
-        if N != n_text + gridH * gridW or d != head_dim:
-            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape differs from the context's")
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O}, "forward")
         if O is None:
             O = torch.empty_like(Q)
         s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
@@ -183,14 +193,25 @@ class ClearAttn:
                                         n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
         return O
 
+    def _check_call(self, Q, named, what):
+        """Shape / dtype of Q against the context, then the plain-layout checks on every tensor of `named`."""
+        n_text, gridH, gridW, head_dim, r = self.shape
+        if Q.dim() != 4:
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "%s: Q must be [B, H, N, head_dim]" % what)
+        if _dtype_code(Q) != self.dtype:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor dtype differs from the context's")
+        B, H, N, d = Q.shape
+        if N != n_text + gridH * gridW or d != head_dim:
+            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape differs from the context's")
+        _check_plain(Q, named, what)
+        return B, H, N, d
+
     def forward_prologue(self, Q, K, V, O=None, q_gain=None, k_gain=None, norm_eps=1e-6, rope_y=None, rope_x=None, logit_scale=1.0,
                          stream=None):
         """clear_attn_forward_prologue: Q, K raw; gains fp32 [head_dim]; rope tables fp32 [grid, head_dim/2, 2]."""
         import torch
         n_text, gridH, gridW, head_dim, r = self.shape
-        B, H, N, d = Q.shape
-        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
-            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O}, "forward_prologue")
         _check_prologue_tables(Q.device, head_dim, gridH, gridW, (q_gain, k_gain), rope_y, rope_x)
         if O is None:
             O = torch.empty_like(Q)
@@ -254,9 +275,8 @@ class ClearAttn:
         """clear_attn_forward_lse: returns (O, lse) with lse fp32 [B, H, N]."""
         import torch
         n_text, gridH, gridW, head_dim, r = self.shape
-        B, H, N, d = Q.shape
-        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
-            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O}, "forward_lse")
+        _check_f32(Q, "lse", lse, (B, H, N))
         if O is None:
             O = torch.empty_like(Q)
         if lse is None:
@@ -270,10 +290,10 @@ class ClearAttn:
         """clear_attn_backward: returns (dQ, dK, dV)."""
         import torch
         n_text, gridH, gridW, head_dim, r = self.shape
-        B, H, N, d = Q.shape
-        for t in (K, V, O, dO):
-            if not (t.is_cuda and t.is_contiguous() and t.shape == Q.shape and t.dtype == Q.dtype):
-                raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "K, V, O, dO must be contiguous device tensors shaped and typed like Q")
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O, "dO": dO}, "backward")
+        if lse is None:
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "backward: lse (from forward_lse) is required")
+        _check_f32(Q, "lse", lse, (B, H, N))
         dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
         s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
         _check(lib().clear_attn_backward(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), lse.data_ptr(),
@@ -285,9 +305,11 @@ class ClearAttn:
         """clear_attn_forward_band on the context's (local) grid.  Returns (O, text_o, text_lse)."""
         import torch
         n_text, gridH, gridW, head_dim, r = self.shape
-        B, H, N, d = Q.shape
-        if N != n_text + gridH * gridW or d != head_dim or _dtype_code(Q) != self.dtype:
-            raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape or dtype differs from the context's")
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O}, "forward_band")
+        if O is None:
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "forward_band: O is required (rows outside the band are left as they are)")
+        _check_f32(Q, "text_o", text_o, (B, H, n_text, d))
+        _check_f32(Q, "text_lse", text_lse, (B, H, n_text))
         if n_text > 0:
             if text_o is None:
                 text_o = torch.empty((B, H, n_text, d), dtype=torch.float32, device=Q.device)
@@ -304,7 +326,9 @@ class ClearAttn:
         """Average milliseconds per launch of (image-query, text-query, merge) kernels; synchronises."""
         import torch
         n_text, gridH, gridW, head_dim, r = self.shape
-        B, H, N, d = Q.shape
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O}, "forward_profile")
+        if O is None:
+            raise ClearAttnError(CLEAR_ERR_INVALID_ARG, "forward_profile: O is required")
         s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
         ms = (ctypes.c_float * 3)()
         _check(lib().clear_attn_forward_profile(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H,

@@ -6,6 +6,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -308,6 +309,24 @@ __device__ __forceinline__ void pv_block(f32x16 (&oacc)[NDB], const TileAddr& ta
         for (int s2 = 0; s2 < 2; ++s2)
             oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db), pf[s2], oacc[db], 0, 0, 0);
 }
+
+// Raises a kernel's dynamic-LDS limit once per device (function attributes belong to the device's copy of the
+// kernel), safely from several host threads: one slot per kernel instantiation, which the caller keeps in a
+// function-local static.
+struct LdsLimitOnce {
+    static constexpr int kDevices = 64;
+    std::once_flag once[kDevices];
+    hipError_t result[kDevices] = {};
+    hipError_t ensure(const void* kernel, int bytes)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kDevices) return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        std::call_once(once[dev], [&] { result[dev] = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+        return result[dev];
+    }
+};
 
 // Pins the instruction order: nothing is scheduled across this point.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)

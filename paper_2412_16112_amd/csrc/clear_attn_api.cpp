@@ -49,10 +49,15 @@ struct clear_attn_ctx {
 
 static thread_local std::string g_create_error;
 
-static int fail(clear_attn_ctx* ctx, int code, const std::string& msg)
+// Whether work enqueued on `stream` is being recorded into a HIP graph (then nothing may allocate or synchronise).
+static bool stream_is_capturing(hipStream_t stream)
 {
-    if (ctx) ctx->err = msg; else g_create_error = msg;
-    return code;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
 }
 
 static int check_shape(int n_text, int gridH, int gridW, int r, std::string* why)
@@ -158,6 +163,8 @@ int clear_attn_schedule_host_masked(int gridH, int gridW, int r, int mask_kind, 
     if (mask_kind == CLEAR_MASK_STRIDED)
         return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the strided mask has no tile schedule on the raster grid: it runs as one dense problem per residue class");
     if (!n_q_tiles || !n_pairs) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "n_q_tiles / n_pairs is NULL");
+    if (schedule_pair_bound(gridH, gridW, r, q_tile_h, q_tile_w, k_tile_h, k_tile_w) > kMaxSchedulePairs)
+        return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the tile schedule would exceed 2^28 (query tile, key tile) pairs");
     const bool sizes_only = !row_ptr && !col_idx && !flags;
     if (!sizes_only && (!row_ptr || !col_idx || !flags)) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "row_ptr, col_idx and flags must be all NULL or all set");
     Schedule s;
@@ -238,6 +245,10 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
     // smallest class (extents rounded down).
     const int schedH = strided ? (gridH + r - 1) / r : gridH, schedW = strided ? (gridW + r - 1) / r : gridW;
     const int cutH = strided ? gridH / r : gridH, cutW = strided ? gridW / r : gridW;
+    if (schedule_pair_bound(schedH, schedW, strided ? schedH + schedW : r, qth, qtw, kth, ktw) > kMaxSchedulePairs) {
+        delete ctx;
+        return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the tile schedule would exceed 2^28 (query tile, key tile) pairs: r is too close to the size of a grid this large");
+    }
     try {
         if (strided)
             build_schedule(schedH, schedW, schedH + schedW, qth, qtw, kth, ktw, &ctx->sched, CLEAR_MASK_DISC, 0);
@@ -387,7 +398,7 @@ struct BandArgs {
 
 static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
                            int n_text, int gridH, int gridW, int head_dim, int r, const BandArgs* band, FwdParams* out,
-                           const long long* strides = nullptr)
+                           void* stream, const long long* strides = nullptr)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (!Q || !K || !V || !O) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be non-NULL");
@@ -483,11 +494,13 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
         p.band_lse = band->text_lse;
     }
     if (n_text > 0) {
-        int rc = clear_attn_reserve(ctx, BH);
-        if (rc != CLEAR_OK) return rc;
         const int per_block = ctx->dtype == CLEAR_BF16 ? bf16_text_queries_per_block() : f32_text_queries_per_block();
         p.n_tq_tiles = (n_text + per_block - 1) / per_block;
         choose_text_splits(p.NV, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
+        if (BH > ctx->ws_BH && stream_is_capturing((hipStream_t)stream))
+            return fail(ctx, CLEAR_ERR_INVALID_ARG, "the text-query workspace would have to grow while the stream is being captured: call clear_attn_reserve beforehand");
+        int rc = clear_attn_reserve(ctx, BH);
+        if (rc != CLEAR_OK) return rc;
         if (p.n_splits > ctx->ws_max_splits) return fail(ctx, CLEAR_ERR_HIP, "internal: split count exceeds workspace");
         p.ws_o = ctx->d_ws_o;
         p.ws_ml = ctx->d_ws_ml;
@@ -520,7 +533,10 @@ static hipError_t ensure_aux_stream(clear_attn_ctx* ctx)
 static hipError_t launch_all(clear_attn_ctx* ctx, const FwdParams& p, hipStream_t stream)
 {
     const long long image_wgs = (long long)p.B * p.H * p.n_classes * p.n_q_tiles_launch;
-    const bool beside = ctx->dtype == CLEAR_BF16 && p.n_text > 0 && image_wgs <= 8LL * ctx->num_cus;
+    // (under stream capture the second stream is used only if an earlier call has made it: creating it is not
+    // something a capture should see)
+    const bool beside = ctx->dtype == CLEAR_BF16 && p.n_text > 0 && image_wgs <= 8LL * ctx->num_cus &&
+                        (ctx->aux_stream != nullptr || !stream_is_capturing(stream));
     if (!beside) return launch(ctx, p, stream, kPhaseAll);
     hipError_t e = ensure_aux_stream(ctx);
     if (e != hipSuccess) return e;
@@ -538,7 +554,7 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
                        int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream);
     if (rc != CLEAR_OK) return rc;
     hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
@@ -550,7 +566,7 @@ int clear_attn_forward_strided(clear_attn_ctx* ctx, const void* Q, const void* K
 {
     if (!strides) return fail(ctx, CLEAR_ERR_INVALID_ARG, "strides is NULL");
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, strides);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream, strides);
     if (rc != CLEAR_OK) return rc;
     if ((uintptr_t)lse & 3) return fail(ctx, CLEAR_ERR_INVALID_ARG, "lse must be 4-byte aligned");
     p.lse = lse;
@@ -564,7 +580,7 @@ int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K
                                float* phase_ms)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream);
     if (rc != CLEAR_OK) return rc;
     if (!phase_ms || reps < 1 || reps > 256) return fail(ctx, CLEAR_ERR_INVALID_ARG, "phase_ms must be non-NULL and 1 <= reps <= 256");
     // The three kernels are timed inside the sequence they run in (image, text, merge, image, ...): timed
@@ -602,7 +618,7 @@ int clear_attn_forward_lse(clear_attn_ctx* ctx, const void* Q, const void* K, co
                            int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream);
     if (rc != CLEAR_OK) return rc;
     if (!lse || ((uintptr_t)lse & 3)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "lse must be non-NULL and 4-byte aligned");
     p.lse = lse;
@@ -670,7 +686,7 @@ static int forward_prologue_impl(clear_attn_ctx* ctx, const void* Q, const void*
                                  float norm_eps, const float* rope_y, const float* rope_x, float logit_scale, void* stream)
 {
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, strides);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream, strides);
     if (rc != CLEAR_OK) return rc;
     if (ctx->dtype != CLEAR_BF16) return fail(ctx, CLEAR_ERR_UNSUPPORTED, "the fused prologue is built for bf16 only");
     rc = check_prologue(ctx, head_dim, q_gain, k_gain, norm_eps, rope_y, rope_x);
@@ -684,6 +700,8 @@ static int forward_prologue_impl(clear_attn_ctx* ctx, const void* Q, const void*
     if (k_gain || rope_y) {
         // Every key row is staged by up to 36 workgroups, so its prologue runs once, ahead of the attention
         // kernels, into the context's buffer; the query rows are handled as each workgroup loads its own.
+        if (B * H > ctx->kpro_BH && stream_is_capturing((hipStream_t)stream))
+            return fail(ctx, CLEAR_ERR_INVALID_ARG, "the key buffer of the prologue would have to grow while the stream is being captured: call clear_attn_reserve_prologue beforehand");
         rc = clear_attn_reserve_prologue(ctx, B * H);
         if (rc != CLEAR_OK) return rc;
         const TensorStrides plain = {(long long)H * p.N * head_dim, p.N * head_dim, head_dim};  // the context's buffer
@@ -786,6 +804,8 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
             }
     }
     const int BH = B * H;
+    if (BH > ctx->bwd_BH && stream_is_capturing((hipStream_t)stream))
+        return fail(ctx, CLEAR_ERR_INVALID_ARG, "the backward workspace would have to grow while the stream is being captured: call clear_attn_reserve_backward beforehand");
     int rc = clear_attn_reserve_backward(ctx, BH);
     if (rc != CLEAR_OK) return rc;
     const Schedule& s = ctx->sched;
@@ -821,7 +841,7 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
     };
     hipError_t e = hipSuccess;
     const long long image_wgs = (long long)BH * p.n_classes * p.n_q_tiles;
-    if (image_wgs > 8LL * ctx->num_cus) {
+    if (image_wgs > 8LL * ctx->num_cus || (ctx->aux_stream == nullptr && stream_is_capturing((hipStream_t)stream))) {
         e = run((hipStream_t)stream, kBwdPhaseAll);
     } else {
         // Small problems (the 1024 x 1024 training shape): the dQ kernels and the dK/dV kernels are independent and
@@ -864,7 +884,7 @@ int clear_attn_forward_band(clear_attn_ctx* ctx, const void* Q, const void* K, c
 {
     const BandArgs band = {own_y0, own_y1, text_keys != 0, text_o, text_lse};
     FwdParams p;
-    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &band, &p);
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, &band, &p, stream);
     if (rc != CLEAR_OK) return rc;
     hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));

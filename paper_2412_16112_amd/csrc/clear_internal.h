@@ -35,6 +35,9 @@ struct Schedule {
 
 // Host-side integer geometry (schedule.cpp)
 void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s, int mask_kind = 0, int mask_shift = 0);
+// Upper bound, in 64 bits, on the (query tile, key tile) pairs build_schedule would list (it stores them with int indices).
+long long schedule_pair_bound(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw);
+constexpr long long kMaxSchedulePairs = 1LL << 28;  // 2.4 GB of host and device tables; create refuses more
 unsigned long long mask_count(int n_text, int gridH, int gridW, int r, int mask_kind = 0, int mask_shift = 0);
 // Pairs fed to the matrix pipeline per (batch, head) by the bf16 kernels (image pass + text-query pass).
 unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys);

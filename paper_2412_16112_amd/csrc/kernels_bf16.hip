@@ -820,12 +820,9 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 {
     const size_t smem = (size_t)NBUF * STAGE_BYTES;
     auto kern = clear_fwd_bf16_kernel<NWY, NWX, TEXTQ, CODE>;
-    static bool attr_set = false;  // the attribute is per function, set once per process
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;  // one per kernel instantiation
+    hipError_t e = lds_limit.ensure((const void*)kern, (int)smem);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(nblk), dim3((NWY * NWX + kLoaderWaves) * 64), smem, stream, p);
     return hipGetLastError();
 }
@@ -834,33 +831,6 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
 
 #if CLEAR_HEAD_DIM == 128
 int bf16_text_queries_per_block() { return kBf16NWY * kBf16NWX * kTextQueriesPerWave; }
-
-// Lane masks of the bf16 kernels for a (4 x 8 query patch, 4 x 8 key block) pair whose origins differ by
-// (4 dby, 8 dbx), |dby| <= ry, |dbx| <= rx: entry (dby + ry) * (2 rx + 1) + dbx + rx holds 16 words, one per
-// score register r; bit l is set iff lane l (query l % 32 of the patch, key slot 8 (r/4) + 4 (l/32) + r % 4
-// of the block) is admitted by the mask: Eq. 3, dx^2 + dy^2 < r^2, or the square window |dx| < r and |dy| < r
-// (the two kinds that depend on the offset alone).  Two more entries follow: all ones, all zeros.
-void build_bf16_mask_table(int r, int ry, int rx, int mask_kind, std::vector<unsigned long long>* tbl)
-{
-    const MaskSpec spec = {mask_kind, r, 0};
-    const long long r2 = (long long)r * r;
-    const int ncol = 2 * rx + 1;
-    tbl->assign((size_t)((2 * ry + 1) * ncol + 2) * 16, 0ull);
-    for (int dby = -ry; dby <= ry; ++dby)
-        for (int dbx = -rx; dbx <= rx; ++dbx) {
-            unsigned long long* e = tbl->data() + (size_t)((dby + ry) * ncol + dbx + rx) * 16;
-            for (int reg = 0; reg < 16; ++reg)
-                for (int l = 0; l < 64; ++l) {
-                    const int qi = l & 31, hh = l >> 5;
-                    const long long dy = 4 * dby + (reg >> 2) - (qi >> 3);
-                    const long long dx = 8 * dbx + 4 * hh + (reg & 3) - (qi & 7);
-                    const bool in_reach = dx > -r && dx < r && dy > -r && dy < r;  // (also keeps the products below in range)
-                    if (in_reach && (mask_kind == kMaskDisc ? dx * dx + dy * dy < r2 : mask_admits(spec, 0, 0, (int)dy, (int)dx))) e[reg] |= 1ull << l;
-                }
-        }
-    unsigned long long* ones = tbl->data() + tbl->size() - 32;
-    for (int reg = 0; reg < 16; ++reg) ones[reg] = ~0ull;
-}
 
 #endif  // CLEAR_HEAD_DIM == 128
 

@@ -620,12 +620,9 @@ template <int MODE, bool LINROWS, int CODE>
 hipError_t launch_bwd_code(const BwdParams& p, int nblk, hipStream_t stream)
 {
     auto kern = clear_bwd_bf16_kernel<MODE, LINROWS, CODE>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;  // one per kernel instantiation
+    hipError_t e = lds_limit.ensure((const void*)kern, BWD_LDS_BYTES);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(nblk), dim3(512), BWD_LDS_BYTES, stream, p);
     return hipGetLastError();
 }

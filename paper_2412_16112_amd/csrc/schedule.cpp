@@ -6,6 +6,7 @@
 namespace clear {
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline long long imin_ll(long long a, long long b) { return a < b ? a : b; }
 
 // Smallest |a - b| for a in [a0, a1], b in [b0, b1].
 static inline int interval_gap(int a0, int a1, int b0, int b1)
@@ -13,6 +14,24 @@ static inline int interval_gap(int a0, int a1, int b0, int b1)
     if (b0 > a1) return b0 - a1;
     if (a0 > b1) return a0 - b1;
     return 0;
+}
+
+long long schedule_pair_bound(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw)
+{
+    // per query tile: the rectangle of key tiles that come within r - 1 on each axis (what build_schedule scans)
+    const int n_qty = ceil_div(gridH, qth), n_qtx = ceil_div(gridW, qtw), n_kty = ceil_div(gridH, kth), n_ktx = ceil_div(gridW, ktw);
+    long long rows = 0, cols = 0;  // the count factorises over the two axes
+    for (int ty = 0; ty < n_qty; ++ty) {
+        const int qy0 = ty * qth, qy1 = imin(qy0 + qth, gridH) - 1;
+        const long long lo = imax(0, (int)(((long long)qy0 - (r - 1)) / kth) - 1), hi = imin(n_kty - 1, (int)imin_ll(((long long)qy1 + r - 1) / kth, n_kty));
+        rows += hi >= lo ? hi - lo + 1 : 0;
+    }
+    for (int tx = 0; tx < n_qtx; ++tx) {
+        const int qx0 = tx * qtw, qx1 = imin(qx0 + qtw, gridW) - 1;
+        const long long lo = imax(0, (int)(((long long)qx0 - (r - 1)) / ktw) - 1), hi = imin(n_ktx - 1, (int)imin_ll(((long long)qx1 + r - 1) / ktw, n_ktx));
+        cols += hi >= lo ? hi - lo + 1 : 0;
+    }
+    return rows * cols;
 }
 
 void build_schedule(int gridH, int gridW, int r, int qth, int qtw, int kth, int ktw, Schedule* s, int mask_kind, int mask_shift)
@@ -107,6 +126,33 @@ unsigned long long mask_count(int n_text, int gridH, int gridW, int r, int mask_
         }
     }
     return (unsigned long long)n_text * N + n_img * n_text + img;
+}
+
+// Lane masks of the bf16 kernels for a (4 x 8 query patch, 4 x 8 key block) pair whose origins differ by
+// (4 dby, 8 dbx), |dby| <= ry, |dbx| <= rx: entry (dby + ry) * (2 rx + 1) + dbx + rx holds 16 words, one per
+// score register r; bit l is set iff lane l (query l % 32 of the patch, key slot 8 (r/4) + 4 (l/32) + r % 4
+// of the block) is admitted by the mask: Eq. 3, dx^2 + dy^2 < r^2, or the square window |dx| < r and |dy| < r
+// (the two kinds that depend on the offset alone).  Two more entries follow: all ones, all zeros.
+void build_bf16_mask_table(int r, int ry, int rx, int mask_kind, std::vector<unsigned long long>* tbl)
+{
+    const MaskSpec spec = {mask_kind, r, 0};
+    const long long r2 = (long long)r * r;
+    const int ncol = 2 * rx + 1;
+    tbl->assign((size_t)((2 * ry + 1) * ncol + 2) * 16, 0ull);
+    for (int dby = -ry; dby <= ry; ++dby)
+        for (int dbx = -rx; dbx <= rx; ++dbx) {
+            unsigned long long* e = tbl->data() + (size_t)((dby + ry) * ncol + dbx + rx) * 16;
+            for (int reg = 0; reg < 16; ++reg)
+                for (int l = 0; l < 64; ++l) {
+                    const int qi = l & 31, hh = l >> 5;
+                    const long long dy = 4 * dby + (reg >> 2) - (qi >> 3);
+                    const long long dx = 8 * dbx + 4 * hh + (reg & 3) - (qi & 7);
+                    const bool in_reach = dx > -r && dx < r && dy > -r && dy < r;  // (also keeps the products below in range)
+                    if (in_reach && (mask_kind == kMaskDisc ? dx * dx + dy * dy < r2 : mask_admits(spec, 0, 0, (int)dy, (int)dx))) e[reg] |= 1ull << l;
+                }
+        }
+    unsigned long long* ones = tbl->data() + tbl->size() - 32;
+    for (int reg = 0; reg < 16; ++reg) ones[reg] = ~0ull;
 }
 
 unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys)

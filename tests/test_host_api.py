@@ -87,7 +87,7 @@ def test_schedule_other_tile_shapes_vs_oracle(qt, kt):
 
 
 @pytest.mark.slow
-@pytest.mark.parametrize("name", ["flux-2048-r16", "flux-4096-r32", "flux-4096-192x320-r32"])
+@pytest.mark.parametrize("name", ["flux-2048-r16", "flux-4096-r32", "flux-4096-192x320-r32", "flux-8k-r16"])
 def test_schedule_bit_exact_large(name):
     w = WORKLOADS[name]
     qth, qtw, kth, ktw = ca.clear_attn_tile_shape(128, ca.CLEAR_BF16)
