@@ -89,6 +89,22 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
                        void* stream);
 
 /*
+ * clear_attn_forward for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results as clear_attn_forward, but
+ * it calls no hipMalloc / hipFree and no allocating library routine: the key-split partial results of the
+ * text-query rows go to a static device array of the library (112 MiB per GPU, held until the process ends)
+ * instead of the context's workspace, and the call stays on `stream` alone (no second stream for small problems).
+ * A call whose partial results (B*H * key splits * n_text * (head_dim + 2) floats) do not fit the array returns
+ * CLEAR_ERR_UNSUPPORTED with the sizes in clear_attn_last_error, and launches nothing; the FLUX-8K shape (B*H = 24,
+ * 16 splits, 512 text tokens, head_dim 128: 102 MB) fits.  The context's device must be the current one.
+ * Every call on a GPU, from any context, shares that GPU's array: calls that overlap in time on one GPU race;
+ * order them on one stream or with events.  Nothing in the array has to be cleared between calls.
+ */
+int clear_attn_forward_noalloc(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
+                               int B, int H, int n_text, int gridH, int gridW, int head_dim, int r,
+                               void* stream);
+
+/*
  * Timing aid for benchmarks: same arguments and checks as clear_attn_forward, but runs `reps`
  * (1..256) forward passes back to back on `stream` with a HIP event between the kernels, and
  * SYNCHRONISES.  phase_ms[0..2] receive the average milliseconds per launch, inside that sequence,

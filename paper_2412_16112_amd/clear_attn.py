@@ -24,6 +24,7 @@ EXPORTS = [
     "clear_attn_measure_mfma_peak", "clear_attn_last_error",
     "clear_attn_forward_prologue", "clear_attn_reserve_prologue", "clear_attn_qk_prologue",
     "clear_attn_forward_strided", "clear_attn_forward_prologue_strided", "clear_attn_backward_strided",
+    "clear_attn_forward_noalloc",
 ]
 
 _lib = None
@@ -50,6 +51,7 @@ def lib():
         L.clear_attn_mask_count_masked.argtypes = [i, i, i, i, i, i, ullp]
         L.clear_attn_reserve.argtypes = [vp, i]
         L.clear_attn_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.clear_attn_forward_noalloc.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.clear_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp, i, ctypes.POINTER(ctypes.c_float)]
         L.clear_attn_destroy.argtypes = [vp]
         L.clear_attn_destroy.restype = None
@@ -205,6 +207,16 @@ class ClearAttn:
             raise ClearAttnError(CLEAR_ERR_MISMATCH, "tensor shape differs from the context's")
         _check_plain(Q, named, what)
         return B, H, N, d
+
+    def forward_noalloc(self, Q, K, V, O, stream=None):
+        """clear_attn_forward_noalloc: the forward pass without any device allocation (O is the caller's)."""
+        import torch
+        n_text, gridH, gridW, head_dim, r = self.shape
+        B, H, N, d = self._check_call(Q, {"Q": Q, "K": K, "V": V, "O": O}, "forward_noalloc")
+        s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+        _check(lib().clear_attn_forward_noalloc(self._ctx, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H,
+                                                n_text, gridH, gridW, head_dim, r, ctypes.c_void_p(s)), self._ctx)
+        return O
 
     def forward_prologue(self, Q, K, V, O=None, q_gain=None, k_gain=None, norm_eps=1e-6, rope_y=None, rope_x=None, logit_scale=1.0,
                          stream=None):

@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cstring>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -44,10 +45,43 @@ struct clear_attn_ctx {
     // keys after the prologue (clear_attn_forward_prologue), grown on demand
     int kpro_BH = 0;
     void* d_kpro = nullptr;        // [B*H][N][head_dim] bf16
+    void* scratch = nullptr;       // this device's copy of the static scratch array (clear_attn_forward_noalloc)
     std::string err;
 };
 
 static thread_local std::string g_create_error;
+
+// Scratch of the entry point that allocates nothing (clear_attn_forward_noalloc): the key-split partial results of
+// the text-query rows.  One copy per GPU, held from the first use of the library on that GPU until the process
+// ends.  On the host `scratch` only names the symbol: its address on the current device comes from
+// hipGetSymbolAddress (scratch_address below), and that pointer is what kernels and copies are given.
+constexpr size_t kScratchBytes = (size_t)112 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // per device, filled on first use with that device current
+
+// Device address of `scratch` on `device`, which must be the current device.
+static hipError_t scratch_address(int device, void** out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
+static int fail(clear_attn_ctx* ctx, int code, const std::string& msg)
+{
+    if (ctx) ctx->err = msg; else g_create_error = msg;
+    return code;
+}
 
 // Whether work enqueued on `stream` is being recorded into a HIP graph (then nothing may allocate or synchronise).
 static bool stream_is_capturing(hipStream_t stream)
@@ -339,6 +373,7 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
         e = hipGetDeviceProperties(&prop, ctx->device);
         if (e == hipSuccess && prop.multiProcessorCount > 0) ctx->num_cus = prop.multiProcessorCount;
     }
+    if (e == hipSuccess) e = scratch_address(ctx->device, &ctx->scratch);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_row_ptr, ctx->sched.row_ptr.size() * sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_col_idx, (k_col.size() + 1) * sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_n_plain, (n_plain.size() + 1) * sizeof(int));
@@ -398,7 +433,7 @@ struct BandArgs {
 
 static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
                            int n_text, int gridH, int gridW, int head_dim, int r, const BandArgs* band, FwdParams* out,
-                           void* stream, const long long* strides = nullptr)
+                           void* stream, const long long* strides = nullptr, bool noalloc = false)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
     if (!Q || !K || !V || !O) return fail(ctx, CLEAR_ERR_INVALID_ARG, "Q, K, V, O must be non-NULL");
@@ -497,13 +532,26 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
         const int per_block = ctx->dtype == CLEAR_BF16 ? bf16_text_queries_per_block() : f32_text_queries_per_block();
         p.n_tq_tiles = (n_text + per_block - 1) / per_block;
         choose_text_splits(p.NV, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
-        if (BH > ctx->ws_BH && stream_is_capturing((hipStream_t)stream))
-            return fail(ctx, CLEAR_ERR_INVALID_ARG, "the text-query workspace would have to grow while the stream is being captured: call clear_attn_reserve beforehand");
-        int rc = clear_attn_reserve(ctx, BH);
-        if (rc != CLEAR_OK) return rc;
-        if (p.n_splits > ctx->ws_max_splits) return fail(ctx, CLEAR_ERR_HIP, "internal: split count exceeds workspace");
-        p.ws_o = ctx->d_ws_o;
-        p.ws_ml = ctx->d_ws_ml;
+        if (noalloc) {
+            // partial outputs, then (maximum, denominator) pairs, both inside the static scratch array
+            const size_t rows = (size_t)BH * p.n_splits * n_text;
+            const size_t o_bytes = (rows * head_dim * sizeof(float) + 255) & ~(size_t)255, ml_bytes = rows * 2 * sizeof(float);
+            if (o_bytes + ml_bytes > kScratchBytes)
+                return fail(ctx, CLEAR_ERR_UNSUPPORTED,
+                            "clear_attn_forward_noalloc: the text-query partial results need " + std::to_string(o_bytes + ml_bytes) +
+                                " bytes, the static scratch array holds " + std::to_string(kScratchBytes) +
+                                " (B*H * key splits * n_text * (head_dim + 2) floats); use clear_attn_forward");
+            p.ws_o = (float*)ctx->scratch;
+            p.ws_ml = (float*)((unsigned char*)ctx->scratch + o_bytes);
+        } else {
+            if (BH > ctx->ws_BH && stream_is_capturing((hipStream_t)stream))
+                return fail(ctx, CLEAR_ERR_INVALID_ARG, "the text-query workspace would have to grow while the stream is being captured: call clear_attn_reserve beforehand");
+            int rc = clear_attn_reserve(ctx, BH);
+            if (rc != CLEAR_OK) return rc;
+            if (p.n_splits > ctx->ws_max_splits) return fail(ctx, CLEAR_ERR_HIP, "internal: split count exceeds workspace");
+            p.ws_o = ctx->d_ws_o;
+            p.ws_ml = ctx->d_ws_ml;
+        }
     }
     *out = p;
     return CLEAR_OK;
@@ -557,6 +605,25 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
     int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream);
     if (rc != CLEAR_OK) return rc;
     hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CLEAR_OK;
+}
+
+int clear_attn_forward_noalloc(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B, int H,
+                               int n_text, int gridH, int gridW, int head_dim, int r, void* stream)
+{
+    if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return fail(ctx, CLEAR_ERR_INVALID_ARG, "clear_attn_forward_noalloc: the context's device must be current (the scratch array is per device)");
+    if (!ctx->scratch) return fail(ctx, CLEAR_ERR_HIP, "internal: the scratch array has no address on this device");
+    FwdParams p;
+    int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream, nullptr, true);
+    if (rc != CLEAR_OK) return rc;
+    // One stream only: the second stream that clear_attn_forward gives small problems is created on demand.
+    // Nothing in the scratch array has to start at zero: the text-query kernel writes every (split, row) entry
+    // that the merge reads.
+    hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }

@@ -131,6 +131,7 @@ static void bands_and_argument_checks()
     EXPECT(clear_attn_last_error(nullptr) != nullptr);
     float dummy[4] = {0};
     EXPECT(clear_attn_forward(nullptr, dummy, dummy, dummy, dummy, 1, 1, 8, 16, 16, 128, 4, nullptr) == CLEAR_ERR_INVALID_ARG);
+    EXPECT(clear_attn_forward_noalloc(nullptr, dummy, dummy, dummy, dummy, 1, 1, 8, 16, 16, 128, 4, nullptr) == CLEAR_ERR_INVALID_ARG);
     EXPECT(clear_attn_reserve(nullptr, 1) == CLEAR_ERR_INVALID_ARG);
     const float* parts[1] = {dummy};
     EXPECT(clear_attn_merge_text(0, parts, parts, 1, 1, 8, 264, 128, CLEAR_MERGE_EXACT, dummy, CLEAR_BF16, nullptr) == CLEAR_ERR_INVALID_ARG);
