@@ -27,6 +27,7 @@ struct clear_attn_ctx {
     int* d_col_idx = nullptr;   // kernel order: tiles inside the grid first, border tiles last
     int* d_n_plain = nullptr;
     unsigned long long* d_mask_tbl = nullptr;
+    int* d_wave_desc = nullptr;  // per listed key tile and wave: mask-table entries of its blocks (bf16, with d_mask_tbl)
     int mask_ry = 0, mask_rx = 0;
     int num_cus = 256;
     // text-query workspace, grown on demand
@@ -367,6 +368,21 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
             return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the mask table");
         }
     }
+    std::vector<int> wave_desc;
+    if (!mask_tbl.empty()) {
+        // mask-table entries reach 16-bit indices only up to 65535; beyond that (r in the thousands) the kernels use arithmetic masks
+        const size_t entries = mask_tbl.size() / 16;
+        if (entries <= 0xffff && k_col.size() * (size_t)(kBf16NWY * kBf16NWX) * sizeof(int) <= ((size_t)256 << 20)) {
+            try {
+                build_wave_descriptors(ctx->sched, k_col, n_plain, ctx->mask_ry, ctx->mask_rx, &wave_desc);
+            } catch (const std::bad_alloc&) {
+                delete ctx;
+                return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the per-wave tile descriptors");
+            }
+        } else {
+            mask_tbl.clear();
+        }
+    }
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) {
         hipDeviceProp_t prop;
@@ -383,6 +399,10 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
     if (e == hipSuccess && !mask_tbl.empty()) {
         e = hipMalloc((void**)&ctx->d_mask_tbl, mask_tbl.size() * sizeof(unsigned long long));
         if (e == hipSuccess) e = hipMemcpy(ctx->d_mask_tbl, mask_tbl.data(), mask_tbl.size() * sizeof(unsigned long long), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess && !wave_desc.empty()) {
+        e = hipMalloc((void**)&ctx->d_wave_desc, wave_desc.size() * sizeof(int));
+        if (e == hipSuccess) e = hipMemcpy(ctx->d_wave_desc, wave_desc.data(), wave_desc.size() * sizeof(int), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -496,6 +516,7 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.col_idx = ctx->d_col_idx;
     p.n_plain = ctx->d_n_plain;
     p.mask_tbl = ctx->d_mask_tbl;
+    p.wave_desc = ctx->d_wave_desc;
     p.mask_ry = ctx->mask_ry;
     p.mask_rx = ctx->mask_rx;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
@@ -1003,6 +1024,7 @@ void clear_attn_destroy(clear_attn_ctx* ctx)
     if (ctx->d_col_idx) (void)hipFree(ctx->d_col_idx);
     if (ctx->d_n_plain) (void)hipFree(ctx->d_n_plain);
     if (ctx->d_mask_tbl) (void)hipFree(ctx->d_mask_tbl);
+    if (ctx->d_wave_desc) (void)hipFree(ctx->d_wave_desc);
     if (ctx->d_ws_o) (void)hipFree(ctx->d_ws_o);
     if (ctx->d_ws_ml) (void)hipFree(ctx->d_ws_ml);
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);

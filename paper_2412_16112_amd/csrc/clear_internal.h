@@ -68,6 +68,8 @@ struct FwdParams {
     const int* n_plain;  // per query tile: how many of its key tiles lie inside the grid
     const unsigned long long* mask_tbl;  // bf16 kernels: lane masks per relative block offset (may be null)
     int mask_ry, mask_rx;
+    const int* wave_desc;  // bf16 kernels, with mask_tbl: per listed key tile (kernel order) and wave of the workgroup, the mask-table
+                           // entries of the tile's two blocks (low / high 16 bits), or kWaveSkipsTile (see build_wave_descriptors)
     float scale_log2e;  // log2(e) / sqrt(head_dim)
     // text-query pass: dense rows split along the keys, partial results merged afterwards
     int n_tq_tiles;   // text query tiles per head
@@ -106,6 +108,14 @@ hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_bf16_d64(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);
 int bf16_text_queries_per_block();
+// What each wave of a bf16 workgroup does with each listed key tile that lies inside the grid (those are masked from the
+// table): desc[e * waves + w] for entry e of the kernel-order tile list `k_col` (origins row << 16 | col) and wave w
+// (patch row w / 2, patch column w % 2 of the query tile) = table entry of block 0 | table entry of block 1 << 16,
+// where a block that is wholly admitted takes the all-ones entry and one out of reach the all-zeros entry; or
+// kWaveSkipsTile when neither block can be reached.  Entries of tiles cut by the border hold kWaveSkipsTile (not used).
+constexpr int kWaveSkipsTile = -1;
+void build_wave_descriptors(const Schedule& s, const std::vector<int>& k_col, const std::vector<int>& n_plain, int mask_ry, int mask_rx,
+                            std::vector<int>* desc);
 void build_bf16_mask_table(int r, int ry, int rx, int mask_kind, std::vector<unsigned long long>* tbl);
 int f32_text_queries_per_block();
 // Backward pass (kernels_bf16_bwd.hip).

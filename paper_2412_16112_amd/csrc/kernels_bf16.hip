@@ -535,6 +535,32 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         return si;
     };
 
+    // Image tiles inside the grid, lane masks from the table: what this wave does with each of them was worked out
+    // on the host when the context was made (one word per tile and wave: the table entries of the tile's two
+    // blocks, or kWaveSkipsTile), so the tile loop neither classifies nor computes mask addresses.  The words of
+    // a stage are fetched before its barrier, whose wait hides their latency.
+    const const_int_ptr wave_desc = (const_int_ptr)p.wave_desc;
+    struct TableStage {
+        int d[TPS];
+    };
+    auto table_stage = [&](int t) {
+        TableStage ts;
+#pragma unroll
+        for (int j = 0; j < TPS; ++j) {
+            const int e = imin(t + j, cb3 - 1) - n_lin_tiles;  // (a stage may end early: its last word is read twice)
+            const int d = wave_desc[(long long)(csr_begin + e) * NW + wave];
+            ts.d[j] = (t + j < cb3 && wave_has_queries) ? d : kWaveSkipsTile;
+        }
+        return ts;
+    };
+    auto stage_tile_lds = [&](int buf, int j) { return lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES); };
+    auto table_mask_args = [&](int d) {
+        MaskArgs ma;
+        ma.row[0] = mask_tbl + 16 * (d & 0xffff);
+        ma.row[1] = mask_tbl + 16 * ((unsigned)d >> 16);
+        return ma;
+    };
+
     // Prologue of the block on the query row (RMS norm over the head's channels - this lane holds half of them,
     // lane ^ 32 the others -, rotary embedding for image queries, back to bf16).  Runs once, after the first
     // stage's loads have been issued, so that the wait for the row and for the tables overlaps them.
@@ -679,21 +705,19 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
                 // image tiles inside the grid (lane masks from the table); the strided variant has run them above
                 if constexpr (CODE != kCodeFull) {
                 for (; t < cb3 && adopting; t += TPS, buf = next_buf(buf)) {
+                    const TableStage ts = table_stage(t);
                     begin_stage(buf);
-#pragma unroll 1
-                    for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
-                        const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, true, CODE>(ws, qf, lo, si.tile_lds, si.ma);
-                    }
+#pragma unroll
+                    for (int j = 0; j < TPS; ++j)
+                        if (ts.d[j] != kWaveSkipsTile) fast_stage<kMaskTable, true, CODE>(ws, qf, lo, stage_tile_lds(buf, j), table_mask_args(ts.d[j]));
                     adopting = wave_has_queries && still_adopting();
                 }
                 for (; t < cb3; t += TPS, buf = next_buf(buf)) {
+                    const TableStage ts = table_stage(t);
                     begin_stage(buf);
-#pragma unroll 1
-                    for (int j = 0; j < imin(TPS, cb3 - t); ++j) {
-                        const TileInfo si = tile_info(t + j, buf, j);
-                        if (si.cls0 != kBlockSkip || si.cls1 != kBlockSkip) fast_stage<kMaskTable, false, CODE>(ws, qf, lo, si.tile_lds, si.ma);
-                    }
+#pragma unroll
+                    for (int j = 0; j < TPS; ++j)
+                        if (ts.d[j] != kWaveSkipsTile) fast_stage<kMaskTable, false, CODE>(ws, qf, lo, stage_tile_lds(buf, j), table_mask_args(ts.d[j]));
                 }
                 }
                 t = cb3;

@@ -155,6 +155,35 @@ void build_bf16_mask_table(int r, int ry, int rx, int mask_kind, std::vector<uns
     for (int reg = 0; reg < 16; ++reg) ones[reg] = ~0ull;
 }
 
+void build_wave_descriptors(const Schedule& s, const std::vector<int>& k_col, const std::vector<int>& n_plain, int mask_ry, int mask_rx,
+                            std::vector<int>* desc)
+{
+    const int nwy = s.qth / kWaveQH, nwx = s.qtw / kWaveQW, waves = nwy * nwx;
+    const MaskSpec spec = {s.mask_kind, s.r, s.mask_shift};
+    const int ncol = 2 * mask_rx + 1;
+    const int ones = (2 * mask_ry + 1) * ncol, zeros = ones + 1;
+    desc->assign(k_col.size() * (size_t)waves, kWaveSkipsTile);
+    for (size_t qt = 0; qt + 1 < s.row_ptr.size(); ++qt) {
+        const int qy0 = (int)(qt / s.n_qtx) * s.qth, qx0 = (int)(qt % s.n_qtx) * s.qtw;
+        for (int e = s.row_ptr[qt]; e < s.row_ptr[qt] + n_plain[qt]; ++e) {
+            const int ta = k_col[e] >> 16, tb = k_col[e] & 0xffff;
+            for (int w = 0; w < waves; ++w) {
+                const int wy0 = qy0 + (w / nwx) * kWaveQH, wx0 = qx0 + (w % nwx) * kWaveQW;
+                int idx[2];
+                bool any = false;
+                for (int kb = 0; kb < 2; ++kb) {
+                    const int cls = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH * kb, tb, kKeyBlockH, kKeyBlockW,
+                                                              s.gridH, s.gridW);
+                    any |= cls != kBlockSkip;
+                    const int dby = ((ta - wy0) >> 2) + kb, dbx = (tb - wx0) >> 3;  // relative block offset in blocks (exact: both are aligned)
+                    idx[kb] = cls == kBlockPartial ? (dby + mask_ry) * ncol + dbx + mask_rx : (cls == kBlockFull ? ones : zeros);
+                }
+                if (any) (*desc)[(size_t)e * waves + w] = idx[0] | (idx[1] << 16);
+            }
+        }
+    }
+}
+
 unsigned long long executed_pairs_bf16(const Schedule& s, int n_text, int text_split_keys)
 {
     (void)text_split_keys;  // splits are multiples of the 64-key stage: the block count does not depend on them
