@@ -907,6 +907,7 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
     p.n_q_tiles = s.n_qty * s.n_qtx;
     p.n_qtx = s.n_qtx;
     p.row_ptr = ctx->d_row_ptr; p.col_idx = ctx->d_col_idx; p.n_plain = ctx->d_n_plain; p.mask_tbl = ctx->d_mask_tbl;
+    p.wave_desc = ctx->d_wave_desc;
     p.mask_ry = ctx->mask_ry; p.mask_rx = ctx->mask_rx;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
     p.n_classes = 1; p.stride = 1; p.stride_rx = p.stride_ry = 0;

@@ -138,6 +138,7 @@ struct BwdParams {
     const int* n_plain;
     const unsigned long long* mask_tbl;
     int mask_ry, mask_rx;
+    const int* wave_desc;  // as in FwdParams (rows and columns swap roles for dK and dV; the masks with a table are symmetric)
     int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift
     int n_classes, stride, stride_rx, stride_ry;  // strided mask, as in FwdParams (otherwise 1, 1, 0, 0)
     float scale_log2e;  // log2(e) / sqrt(head_dim)

@@ -450,7 +450,36 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
             pf_tile += pend_len;
         }
     };
+    const const_int_ptr wave_desc = (const_int_ptr)p.wave_desc;
+    // Runs the reachable blocks of one staged tile (one code shape per block product, whichever mode).
+    auto run_blocks = [&](auto mask_tag, bool run0, bool run1, const MaskArgs& ma, int buf, int j) __attribute__((always_inline)) {
+        const unsigned tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
+        const float* tile_stats = stats + ((buf * TPS + j) * 2) * TILE_KEYS;
+        if constexpr (MODE == kBwdQ && CLEAR_BWD_PIPELINED_Q) {
+            if (run0) do_block_q(mask_tag, tile_lds, 0, ma);
+            if (run1) do_block_q(mask_tag, tile_lds, 1, ma);
+        } else if constexpr (MODE == kBwdKV && CLEAR_BWD_PIPELINED_KV) {
+            if (run0) do_block_kv(mask_tag, tile_lds, 0, ma, tile_stats);
+            if (run1) do_block_kv(mask_tag, tile_lds, 1, ma, tile_stats);
+        } else {
+            if (run0) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
+            if (run1) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
+        }
+    };
     auto run_tile = [&](auto mask_tag, int t, int buf, int j) __attribute__((always_inline)) {
+        if constexpr (decltype(mask_tag)::value == kMaskTable) {
+            // image tiles inside the grid: what this wave does with the tile was worked out on the host (the mask-table
+            // entries of its two blocks, the all-zeros entry for a block out of reach, or kWaveSkipsTile)
+            const int d = wave_desc[(long long)(csr_begin + t - n_lin_tiles) * NW + wave];
+            if (d == kWaveSkipsTile || !wave_has_rows) return;
+            const int zeros = (2 * p.mask_ry + 1) * (2 * p.mask_rx + 1) + 1;
+            const int i0 = d & 0xffff, i1 = (int)((unsigned)d >> 16);
+            MaskArgs ma;
+            ma.row[0] = mask_tbl + 16 * i0;
+            ma.row[1] = mask_tbl + 16 * i1;
+            run_blocks(mask_tag, i0 != zeros, i1 != zeros, ma, buf, j);
+            return;
+        }
         int ta, tb;
         tile_origin(t, ta, tb);
         const bool linear = tb < 0;
@@ -487,18 +516,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
             ma.row[0] = mask_tbl + 16 * i0;
             ma.row[1] = mask_tbl + 16 * i1;
         }
-        const unsigned tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
-        const float* tile_stats = stats + ((buf * TPS + j) * 2) * TILE_KEYS;
-        if constexpr (MODE == kBwdQ && CLEAR_BWD_PIPELINED_Q) {
-            if (cls0 != kBlockSkip) do_block_q(mask_tag, tile_lds, 0, ma);
-            if (cls1 != kBlockSkip) do_block_q(mask_tag, tile_lds, 1, ma);
-        } else if constexpr (MODE == kBwdKV && CLEAR_BWD_PIPELINED_KV) {
-            if (cls0 != kBlockSkip) do_block_kv(mask_tag, tile_lds, 0, ma, tile_stats);
-            if (cls1 != kBlockSkip) do_block_kv(mask_tag, tile_lds, 1, ma, tile_stats);
-        } else {
-            if (cls0 != kBlockSkip) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
-            if (cls1 != kBlockSkip) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
-        }
+        run_blocks(mask_tag, cls0 != kBlockSkip, cls1 != kBlockSkip, ma, buf, j);
     };
     auto run_category = [&](auto mask_tag, int& t, int end, int& buf) __attribute__((always_inline)) {
         for (; t < end; t += TPS, buf ^= 1) {
