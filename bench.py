@@ -132,15 +132,19 @@ def main():
     sum_m_image_rows = sum_m - w.n_text * w.N
     img_flop = 4.0 * sum_m_image_rows * w.head_dim * BH
     img_ms = phase_ms[0]
-    traffic = None
+    # HBM-side bytes of the dominant kernel: counter readings of separate rocprofv3 runs (FETCH_SIZE, then WRITE_SIZE), kept
+    # with the commit they were taken at; stale once that kernel changes, which is why the commit is printed beside them
+    traffic, traffic_at = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(w.name if args.mask == "disc" else "", {}).get("image_query_kernel_bytes_per_launch")
+            entry = json.load(f).get(w.name if args.mask == "disc" else "", {})
+        traffic, traffic_at = entry.get("image_query_kernel_bytes_per_launch"), entry.get("measured_at")
     roofline = {
         "bound": "mfma", "kernel": "clear_fwd_bf16_kernel<image queries>",
         "achieved": img_flop / (img_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "frac": img_flop / (img_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+        "frac": img_flop / (img_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_measured_at_commit": traffic_at,
+        "traffic_over_algorithmic": (traffic / (w.B * w.H * 2.0 * (w.N + w.gridH * w.gridW) * w.head_dim * 2.0)) if traffic else None,
         "kernel_ms": {"image_query": phase_ms[0], "text_query": phase_ms[1], "text_merge": phase_ms[2]},
     }
 
