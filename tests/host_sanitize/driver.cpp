@@ -1,8 +1,9 @@
 // Host-side entry points of the library run under the host sanitizers (AddressSanitizer + UndefinedBehaviorSanitizer),
 // on a machine without a GPU: the schedule builder on ragged, thin, tiny and large shapes and every mask kind, the
-// lattice counts, the lane-mask tables, the band layout, and the argument checks of the calls that need a device
+// lattice counts, the lane-mask tables, the per-wave tile descriptors, the band layout, and the argument checks of the calls that need a device
 // (each must return an error code before any launch).  Results are cross-checked where a second way to get them
 // exists; the point of the run is that no sanitizer report appears.  Exit code 0 = clean.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
@@ -104,6 +105,74 @@ static void mask_tables()
         }
 }
 
+// The per-wave tile descriptors the kernels follow against the classification they replace and against the count of
+// executed pairs the library reports: every wave that runs a tile runs both of its 32-key blocks.
+static void wave_descriptors()
+{
+    using namespace clear;
+    const int shapes[][4] = {{64, 64, 16, 512}, {40, 56, 8, 300}, {33, 17, 9, 0}, {128, 128, 16, 70}, {24, 40, 100, 5}, {7, 5, 1, 8}, {96, 96, 32, 512}};
+    for (const auto& sh : shapes)
+        for (int kind : {CLEAR_MASK_DISC, CLEAR_MASK_SQUARE}) {
+            const int gh = sh[0], gw = sh[1], r = sh[2], n_text = sh[3];
+            Schedule sc;
+            build_schedule(gh, gw, r, kBf16QTileH, kBf16QTileW, kKeyTileH, kKeyTileW, &sc, kind, 0);
+            // kernel order of the tile lists: tiles inside the grid first (any order will do here), then the cut ones
+            std::vector<int> k_col(sc.col_idx.size()), n_plain(sc.row_ptr.size() - 1, 0);
+            auto cut = [&](int id) { return (id / sc.n_ktx + 1) * sc.kth > gh || (id % sc.n_ktx + 1) * sc.ktw > gw; };
+            auto origin = [&](int id) { return ((id / sc.n_ktx) * sc.kth) << 16 | ((id % sc.n_ktx) * sc.ktw); };
+            for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt) {
+                int w = sc.row_ptr[qt];
+                for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                    if (!cut(sc.col_idx[e])) k_col[(size_t)w++] = origin(sc.col_idx[e]);
+                n_plain[qt] = w - sc.row_ptr[qt];
+                for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                    if (cut(sc.col_idx[e])) k_col[(size_t)w++] = origin(sc.col_idx[e]);
+            }
+            const int ry = std::min((r + 2) / 4, (gh + 3) / 4), rx = std::min((r + 6) / 8, (gw + 7) / 8);
+            const int ncol = 2 * rx + 1, ones = (2 * ry + 1) * ncol, zeros = ones + 1;
+            std::vector<int> desc;
+            build_wave_descriptors(sc, k_col, n_plain, ry, rx, &desc);
+            const int waves = kBf16NWY * kBf16NWX;
+            EXPECT(desc.size() == k_col.size() * (size_t)waves);
+            const MaskSpec spec = {kind, r, 0};
+            unsigned long long run_tiles = 0;  // (wave, tile) pairs that are run: plain tiles from the descriptors, cut tiles classified here
+            for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt)
+                for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                    for (int w = 0; w < waves; ++w) {
+                        const int wy0 = (int)(qt / sc.n_qtx) * sc.qth + (w / kBf16NWX) * kWaveQH, wx0 = (int)(qt % sc.n_qtx) * sc.qtw + (w % kBf16NWX) * kWaveQW;
+                        const int ta = k_col[(size_t)e] >> 16, tb = k_col[(size_t)e] & 0xffff;
+                        const int c0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, gh, gw);
+                        const int c1 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, gh, gw);
+                        const bool any = c0 != kBlockSkip || c1 != kBlockSkip;
+                        const int d = desc[(size_t)e * waves + w];
+                        if (e < sc.row_ptr[qt] + n_plain[qt]) {
+                            EXPECT((d != kWaveSkipsTile) == any);
+                            if (d != kWaveSkipsTile) {
+                                const int i0 = d & 0xffff, i1 = (int)((unsigned)d >> 16);
+                                EXPECT((i0 == zeros) == (c0 == kBlockSkip) && (i0 == ones) == (c0 == kBlockFull));
+                                EXPECT((i1 == zeros) == (c1 == kBlockSkip) && (i1 == ones) == (c1 == kBlockFull));
+                                EXPECT(i0 >= 0 && i0 <= zeros && i1 >= 0 && i1 <= zeros);
+                                if (c0 == kBlockPartial) EXPECT(i0 == (((ta - wy0) >> 2) + ry) * ncol + ((tb - wx0) >> 3) + rx);
+                            }
+                        } else {
+                            EXPECT(d == kWaveSkipsTile);  // cut tiles are classified in the kernel
+                        }
+                        if (wy0 < gh && wx0 < gw) run_tiles += any;
+                    }
+            // executed pairs of the library: 2 blocks x 1024 pairs per run tile, the text tiles of every wave with queries, the text-query pass
+            sc.mask_kind = kind;
+            unsigned long long text_tile_runs = 0;
+            for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt)
+                for (int w = 0; w < waves; ++w) {
+                    const int wy0 = (int)(qt / sc.n_qtx) * sc.qth + (w / kBf16NWX) * kWaveQH, wx0 = (int)(qt % sc.n_qtx) * sc.qtw + (w % kBf16NWX) * kWaveQW;
+                    if (wy0 < gh && wx0 < gw) text_tile_runs += (unsigned long long)((n_text + 63) / 64);
+                }
+            const long long N = n_text + (long long)gh * gw;
+            const unsigned long long text_query = (unsigned long long)((n_text + 31) / 32) * 2ull * (unsigned long long)((N + 63) / 64);
+            EXPECT(executed_pairs_bf16(sc, n_text, 0) == (2ull * (run_tiles + text_tile_runs) + text_query) * 1024ull);
+        }
+}
+
 static void bands_and_argument_checks()
 {
     int y0, y1, ht, hb;
@@ -144,6 +213,7 @@ int main()
     schedules();
     counts();
     mask_tables();
+    wave_descriptors();
     bands_and_argument_checks();
     if (failures) {
         std::printf("%d check(s) failed\n", failures);
