@@ -269,14 +269,19 @@ int clear_attn_band_layout(int gridH_total, int r, int n_bands, int band, int* y
 /* Forward pass of one band.  ctx, Q, K, V, O, B .. r, stream: as for clear_attn_forward, for the local grid.
  * Image queries: only the rows [own_y0, own_y1) of the local grid are computed and written to O (exactly
  * their output in the undivided problem when the halo holds the r - 1 neighbouring rows, or more of them: rows
- * beyond r - 1 are out of every owned query's reach, and a top halo of a whole number of 16-row query tiles
- * saves the workgroups that would straddle the first owned row); halo rows of O are left untouched, and so
- * are the text rows.
+ * beyond r - 1 are out of every owned query's reach); halo rows of O are left untouched, and so are the text
+ * rows.  The query tiles start at own_y0 itself, so no workgroup straddles the first owned row (bf16, disc mask,
+ * own_y0 >= r - 1 as the halo of an inner band gives it; a band at the top of the image with fewer rows above
+ * own_y0, the other masks and fp32 keep the tiles of the local grid, which start at row 0).  When own_y0 is not a
+ * multiple of the query-tile height, the first call with that own_y0 (mod the tile height) builds tile lists of
+ * its own: it allocates and waits for their upload, and is refused with CLEAR_ERR_INVALID_ARG while the stream is
+ * being captured; later calls reuse them.
  * Text queries: attend to the owned image rows and, if text_keys != 0, to the text keys; the softmax output
  * over those keys goes to text_o (device, fp32, [B, H, n_text, head_dim]) and the natural logarithm of the
  * softmax denominator sum_j exp(q.k_j / sqrt(head_dim)) to text_lse (device, fp32, [B, H, n_text]); both
  * caller-owned, required when n_text > 0.  Combine the bands' results with clear_attn_merge_text.
- * Never synchronises; allocates only if the text workspace has to grow (see clear_attn_reserve). */
+ * Apart from that first call: never synchronises; allocates only if the text workspace has to grow (see
+ * clear_attn_reserve). */
 int clear_attn_forward_band(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V, void* O, int B,
                             int H, int n_text, int gridH, int gridW, int head_dim, int r, int own_y0,
                             int own_y1, int text_keys, float* text_o, float* text_lse, void* stream);

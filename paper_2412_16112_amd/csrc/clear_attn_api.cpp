@@ -18,10 +18,8 @@
 
 using namespace clear;
 
-struct clear_attn_ctx {
-    int n_text = 0, gridH = 0, gridW = 0, head_dim = 0, r = 0, dtype = 0;
-    int mask_kind = 0, mask_shift = 0;
-    int device = 0;
+// Tile lists of one raster and their copies on the device.
+struct TileTables {
     Schedule sched;
     int* d_row_ptr = nullptr;
     int* d_col_idx = nullptr;   // kernel order: tiles inside the grid first, border tiles last
@@ -29,6 +27,26 @@ struct clear_attn_ctx {
     unsigned long long* d_mask_tbl = nullptr;
     int* d_wave_desc = nullptr;  // per listed key tile and wave: mask-table entries of its blocks (bf16, with d_mask_tbl)
     int mask_ry = 0, mask_rx = 0;
+    void release()
+    {
+        if (d_row_ptr) (void)hipFree(d_row_ptr);
+        if (d_col_idx) (void)hipFree(d_col_idx);
+        if (d_n_plain) (void)hipFree(d_n_plain);
+        if (d_mask_tbl) (void)hipFree(d_mask_tbl);
+        if (d_wave_desc) (void)hipFree(d_wave_desc);
+        d_row_ptr = d_col_idx = d_n_plain = d_wave_desc = nullptr;
+        d_mask_tbl = nullptr;
+    }
+};
+
+struct clear_attn_ctx {
+    int n_text = 0, gridH = 0, gridW = 0, head_dim = 0, r = 0, dtype = 0;
+    int mask_kind = 0, mask_shift = 0;
+    int device = 0;
+    TileTables t;  // tile lists of the context's grid
+    // Row bands whose first owned row is not a multiple of the query tile height: tile lists of the grid moved down
+    // by 1 .. tile height - 1 rows, so that a tile row starts at the first owned row (built on first use).
+    TileTables* band_t[kBf16QTileH > kF32QTileH ? kBf16QTileH : kF32QTileH] = {};
     int num_cus = 256;
     // text-query workspace, grown on demand
     int ws_BH = 0;         // capacity in (batch*head) units
@@ -153,6 +171,145 @@ static void choose_text_splits(long long N, int BH, int n_tq_tiles, int num_cus,
     *n_splits = (int)((N + keys - 1) / keys);
 }
 
+// Builds the tile lists of a gridH x gridW raster for the kernels of (head_dim, dtype, mask) and copies them to the
+// current device.  Returns CLEAR_OK, or an error code with *why set (the caller releases `t`).
+static int build_tile_tables(int gridH, int gridW, int head_dim, int r, int dtype, int mask_kind, int shift, TileTables* t, std::string* why)
+{
+    const bool strided = mask_kind == CLEAR_MASK_STRIDED;
+    int qth, qtw, kth, ktw;
+    clear_attn_tile_shape(head_dim, dtype, &qth, &qtw, &kth, &ktw);
+    // Strided: the tile lists describe one residue class, a (gridH / r) x (gridW / r) grid (rounded up) on which
+    // every query tile meets every key tile; tiles count as inside the grid only if they are so for the
+    // smallest class (extents rounded down).
+    const int schedH = strided ? (gridH + r - 1) / r : gridH, schedW = strided ? (gridW + r - 1) / r : gridW;
+    const int cutH = strided ? gridH / r : gridH, cutW = strided ? gridW / r : gridW;
+    if (schedule_pair_bound(schedH, schedW, strided ? schedH + schedW : r, qth, qtw, kth, ktw) > kMaxSchedulePairs) {
+        *why = "the tile schedule would exceed 2^28 (query tile, key tile) pairs: r is too close to the size of a grid this large";
+        return CLEAR_ERR_UNSUPPORTED;
+    }
+    try {
+        if (strided)
+            build_schedule(schedH, schedW, schedH + schedW, qth, qtw, kth, ktw, &t->sched, CLEAR_MASK_DISC, 0);
+        else
+            build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &t->sched, mask_kind, shift);
+    } catch (const std::bad_alloc&) {
+        *why = "out of host memory building the schedule";
+        return CLEAR_ERR_ALLOC;
+    }
+    // kernel-side tile lists: per query tile, the origins (row << 16 | col) of its key tiles, those inside the
+    // grid first (mirror pairs adjacent), border tiles last
+    std::vector<int> k_col(t->sched.col_idx.size()), n_plain(t->sched.row_ptr.size() - 1, 0);
+    {
+        const Schedule& sc = t->sched;
+        auto cut = [&](int id) {
+            const int ty = id / sc.n_ktx, tx = id % sc.n_ktx;
+            return (ty + 1) * sc.kth > cutH || (tx + 1) * sc.ktw > cutW;
+        };
+        auto origin = [&](int id) { return ((id / sc.n_ktx) * sc.kth) << 16 | ((id % sc.n_ktx) * sc.ktw); };
+        std::vector<int> plain, used;
+        for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt) {
+            // Tiles inside the grid, reordered so that each stage (two consecutive tiles) holds a tile and its
+            // point mirror through the centre of the query tile: what one wave's disc misses of the pair,
+            // the wave sharing its SIMD tends to reach, which evens out the work between barriers.
+            plain.clear();
+            for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                if (!cut(sc.col_idx[e])) plain.push_back(sc.col_idx[e]);
+            used.assign(plain.size(), 0);
+            const int qy0 = (int)(qt / sc.n_qtx) * sc.qth, qx0 = (int)(qt % sc.n_qtx) * sc.qtw;
+            int w = sc.row_ptr[qt];
+            std::vector<int> single;
+            for (size_t i = 0; i < plain.size(); ++i) {
+                if (used[i]) continue;
+                used[i] = 1;
+                const int ky = (plain[i] / sc.n_ktx) * sc.kth, kx = (plain[i] % sc.n_ktx) * sc.ktw;
+                const int my = 2 * qy0 + sc.qth - sc.kth - ky, mx = 2 * qx0 + sc.qtw - sc.ktw - kx;
+                int partner = -1;
+                if (my >= 0 && mx >= 0 && my % sc.kth == 0 && mx % sc.ktw == 0) {
+                    const int mid = (my / sc.kth) * sc.n_ktx + mx / sc.ktw;
+                    for (size_t j = i + 1; j < plain.size(); ++j)
+                        if (!used[j] && plain[j] == mid) { partner = (int)j; break; }
+                }
+                if (partner >= 0) {
+                    used[partner] = 1;
+                    k_col[w++] = origin(plain[i]);
+                    k_col[w++] = origin(plain[partner]);
+                } else {
+                    single.push_back(plain[i]);
+                }
+            }
+            for (int id : single) k_col[w++] = origin(id);
+            n_plain[qt] = w - sc.row_ptr[qt];
+            for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
+                if (cut(sc.col_idx[e])) k_col[w++] = origin(sc.col_idx[e]);
+        }
+    }
+    std::vector<unsigned long long> mask_tbl;
+    if (dtype == CLEAR_BF16 && (mask_kind == CLEAR_MASK_DISC || mask_kind == CLEAR_MASK_SQUARE)) {
+        // (masks that depend on the offset between the tokens alone; Swin windows take the arithmetic element mask)
+        // relative block offsets that a non-empty (patch, block) pair can have
+        t->mask_ry = std::min((r + 2) / 4, (gridH + 3) / 4);
+        t->mask_rx = std::min((r + 6) / 8, (gridW + 7) / 8);
+        const size_t entries = (size_t)(2 * t->mask_ry + 1) * (2 * t->mask_rx + 1) + 2;
+        if (entries * 128 <= (64u << 20)) {  // beyond 64 MB the kernels fall back to arithmetic masks
+            try {
+                build_bf16_mask_table(r, t->mask_ry, t->mask_rx, mask_kind, &mask_tbl);
+            } catch (const std::bad_alloc&) {
+                *why = "out of host memory building the mask table";
+                return CLEAR_ERR_ALLOC;
+            }
+        }
+    }
+    if (dtype == CLEAR_BF16 && mask_kind == CLEAR_MASK_SWIN && r % 8 == 0 && shift % 8 == 0) {
+        // Windows whose edges fall on multiples of 8: a 4 x 8 query patch and a 4 x 8 key block each lie in one
+        // window, so inside the grid a block is either wholly admitted or out of reach.  The table then only
+        // needs its all-ones and all-zeros entries (the entry for offset (0, 0) in front of them is never used).
+        t->mask_ry = t->mask_rx = 0;
+        try {
+            build_bf16_mask_table(r, 0, 0, mask_kind, &mask_tbl);
+        } catch (const std::bad_alloc&) {
+            *why = "out of host memory building the mask table";
+            return CLEAR_ERR_ALLOC;
+        }
+    }
+    std::vector<int> wave_desc;
+    if (!mask_tbl.empty()) {
+        // mask-table entries reach 16-bit indices only up to 65535; beyond that (r in the thousands) the kernels use arithmetic masks
+        const size_t entries = mask_tbl.size() / 16;
+        if (entries <= 0xffff && k_col.size() * (size_t)(kBf16NWY * kBf16NWX) * sizeof(int) <= ((size_t)256 << 20)) {
+            try {
+                build_wave_descriptors(t->sched, k_col, n_plain, t->mask_ry, t->mask_rx, &wave_desc);
+            } catch (const std::bad_alloc&) {
+                *why = "out of host memory building the per-wave tile descriptors";
+                return CLEAR_ERR_ALLOC;
+            }
+        } else {
+            mask_tbl.clear();
+        }
+    }
+    hipError_t e = hipSuccess;
+    if (e == hipSuccess) e = hipMalloc((void**)&t->d_row_ptr, t->sched.row_ptr.size() * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&t->d_col_idx, (k_col.size() + 1) * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&t->d_n_plain, (n_plain.size() + 1) * sizeof(int));
+    if (e == hipSuccess) e = hipMemcpy(t->d_row_ptr, t->sched.row_ptr.data(), t->sched.row_ptr.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !k_col.empty()) e = hipMemcpy(t->d_col_idx, k_col.data(), k_col.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !n_plain.empty()) e = hipMemcpy(t->d_n_plain, n_plain.data(), n_plain.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !mask_tbl.empty()) {
+        e = hipMalloc((void**)&t->d_mask_tbl, mask_tbl.size() * sizeof(unsigned long long));
+        if (e == hipSuccess) e = hipMemcpy(t->d_mask_tbl, mask_tbl.data(), mask_tbl.size() * sizeof(unsigned long long), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess && !wave_desc.empty()) {
+        e = hipMalloc((void**)&t->d_wave_desc, wave_desc.size() * sizeof(int));
+        if (e == hipSuccess) e = hipMemcpy(t->d_wave_desc, wave_desc.data(), wave_desc.size() * sizeof(int), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        *why = std::string("HIP error building the tile lists: ") + hipGetErrorString(e);
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? CLEAR_ERR_ALLOC : CLEAR_ERR_HIP;
+    }
+    return CLEAR_OK;
+}
+
 extern "C" {
 
 int clear_attn_mask_count(int n_text, int gridH, int gridW, int r, unsigned long long* sumM)
@@ -273,115 +430,10 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
     ctx->n_text = n_text; ctx->gridH = gridH; ctx->gridW = gridW;
     ctx->head_dim = head_dim; ctx->r = r; ctx->dtype = dtype;
     ctx->mask_kind = mask_kind; ctx->mask_shift = shift;
-    int qth, qtw, kth, ktw;
-    clear_attn_tile_shape(head_dim, dtype, &qth, &qtw, &kth, &ktw);
-    // Strided: the tile lists describe one residue class, a (gridH / r) x (gridW / r) grid (rounded up) on which
-    // every query tile meets every key tile; tiles count as inside the grid only if they are so for the
-    // smallest class (extents rounded down).
-    const int schedH = strided ? (gridH + r - 1) / r : gridH, schedW = strided ? (gridW + r - 1) / r : gridW;
-    const int cutH = strided ? gridH / r : gridH, cutW = strided ? gridW / r : gridW;
-    if (schedule_pair_bound(schedH, schedW, strided ? schedH + schedW : r, qth, qtw, kth, ktw) > kMaxSchedulePairs) {
-        delete ctx;
-        return fail(nullptr, CLEAR_ERR_UNSUPPORTED, "the tile schedule would exceed 2^28 (query tile, key tile) pairs: r is too close to the size of a grid this large");
-    }
-    try {
-        if (strided)
-            build_schedule(schedH, schedW, schedH + schedW, qth, qtw, kth, ktw, &ctx->sched, CLEAR_MASK_DISC, 0);
-        else
-            build_schedule(gridH, gridW, r, qth, qtw, kth, ktw, &ctx->sched, mask_kind, shift);
-    } catch (const std::bad_alloc&) {
-        delete ctx;
-        return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the schedule");
-    }
-    // kernel-side tile lists: per query tile, the origins (row << 16 | col) of its key tiles, those inside the
-    // grid first (mirror pairs adjacent), border tiles last
-    std::vector<int> k_col(ctx->sched.col_idx.size()), n_plain(ctx->sched.row_ptr.size() - 1, 0);
-    {
-        const Schedule& sc = ctx->sched;
-        auto cut = [&](int id) {
-            const int ty = id / sc.n_ktx, tx = id % sc.n_ktx;
-            return (ty + 1) * sc.kth > cutH || (tx + 1) * sc.ktw > cutW;
-        };
-        auto origin = [&](int id) { return ((id / sc.n_ktx) * sc.kth) << 16 | ((id % sc.n_ktx) * sc.ktw); };
-        std::vector<int> plain, used;
-        for (size_t qt = 0; qt + 1 < sc.row_ptr.size(); ++qt) {
-            // Tiles inside the grid, reordered so that each stage (two consecutive tiles) holds a tile and its
-            // point mirror through the centre of the query tile: what one wave's disc misses of the pair,
-            // the wave sharing its SIMD tends to reach, which evens out the work between barriers.
-            plain.clear();
-            for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
-                if (!cut(sc.col_idx[e])) plain.push_back(sc.col_idx[e]);
-            used.assign(plain.size(), 0);
-            const int qy0 = (int)(qt / sc.n_qtx) * sc.qth, qx0 = (int)(qt % sc.n_qtx) * sc.qtw;
-            int w = sc.row_ptr[qt];
-            std::vector<int> single;
-            for (size_t i = 0; i < plain.size(); ++i) {
-                if (used[i]) continue;
-                used[i] = 1;
-                const int ky = (plain[i] / sc.n_ktx) * sc.kth, kx = (plain[i] % sc.n_ktx) * sc.ktw;
-                const int my = 2 * qy0 + sc.qth - sc.kth - ky, mx = 2 * qx0 + sc.qtw - sc.ktw - kx;
-                int partner = -1;
-                if (my >= 0 && mx >= 0 && my % sc.kth == 0 && mx % sc.ktw == 0) {
-                    const int mid = (my / sc.kth) * sc.n_ktx + mx / sc.ktw;
-                    for (size_t j = i + 1; j < plain.size(); ++j)
-                        if (!used[j] && plain[j] == mid) { partner = (int)j; break; }
-                }
-                if (partner >= 0) {
-                    used[partner] = 1;
-                    k_col[w++] = origin(plain[i]);
-                    k_col[w++] = origin(plain[partner]);
-                } else {
-                    single.push_back(plain[i]);
-                }
-            }
-            for (int id : single) k_col[w++] = origin(id);
-            n_plain[qt] = w - sc.row_ptr[qt];
-            for (int e = sc.row_ptr[qt]; e < sc.row_ptr[qt + 1]; ++e)
-                if (cut(sc.col_idx[e])) k_col[w++] = origin(sc.col_idx[e]);
-        }
-    }
-    std::vector<unsigned long long> mask_tbl;
-    if (dtype == CLEAR_BF16 && (mask_kind == CLEAR_MASK_DISC || mask_kind == CLEAR_MASK_SQUARE)) {
-        // (masks that depend on the offset between the tokens alone; Swin windows take the arithmetic element mask)
-        // relative block offsets that a non-empty (patch, block) pair can have
-        ctx->mask_ry = std::min((r + 2) / 4, (gridH + 3) / 4);
-        ctx->mask_rx = std::min((r + 6) / 8, (gridW + 7) / 8);
-        const size_t entries = (size_t)(2 * ctx->mask_ry + 1) * (2 * ctx->mask_rx + 1) + 2;
-        if (entries * 128 <= (64u << 20)) {  // beyond 64 MB the kernels fall back to arithmetic masks
-            try {
-                build_bf16_mask_table(r, ctx->mask_ry, ctx->mask_rx, mask_kind, &mask_tbl);
-            } catch (const std::bad_alloc&) {
-                delete ctx;
-                return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the mask table");
-            }
-        }
-    }
-    if (dtype == CLEAR_BF16 && mask_kind == CLEAR_MASK_SWIN && r % 8 == 0 && shift % 8 == 0) {
-        // Windows whose edges fall on multiples of 8: a 4 x 8 query patch and a 4 x 8 key block each lie in one
-        // window, so inside the grid a block is either wholly admitted or out of reach.  The table then only
-        // needs its all-ones and all-zeros entries (the entry for offset (0, 0) in front of them is never used).
-        ctx->mask_ry = ctx->mask_rx = 0;
-        try {
-            build_bf16_mask_table(r, 0, 0, mask_kind, &mask_tbl);
-        } catch (const std::bad_alloc&) {
-            delete ctx;
-            return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the mask table");
-        }
-    }
-    std::vector<int> wave_desc;
-    if (!mask_tbl.empty()) {
-        // mask-table entries reach 16-bit indices only up to 65535; beyond that (r in the thousands) the kernels use arithmetic masks
-        const size_t entries = mask_tbl.size() / 16;
-        if (entries <= 0xffff && k_col.size() * (size_t)(kBf16NWY * kBf16NWX) * sizeof(int) <= ((size_t)256 << 20)) {
-            try {
-                build_wave_descriptors(ctx->sched, k_col, n_plain, ctx->mask_ry, ctx->mask_rx, &wave_desc);
-            } catch (const std::bad_alloc&) {
-                delete ctx;
-                return fail(nullptr, CLEAR_ERR_ALLOC, "out of host memory building the per-wave tile descriptors");
-            }
-        } else {
-            mask_tbl.clear();
-        }
+    rc = build_tile_tables(gridH, gridW, head_dim, r, dtype, mask_kind, shift, &ctx->t, &why);
+    if (rc != CLEAR_OK) {
+        clear_attn_destroy(ctx);
+        return fail(nullptr, rc, why);
     }
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) {
@@ -390,20 +442,6 @@ int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gr
         if (e == hipSuccess && prop.multiProcessorCount > 0) ctx->num_cus = prop.multiProcessorCount;
     }
     if (e == hipSuccess) e = scratch_address(ctx->device, &ctx->scratch);
-    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_row_ptr, ctx->sched.row_ptr.size() * sizeof(int));
-    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_col_idx, (k_col.size() + 1) * sizeof(int));
-    if (e == hipSuccess) e = hipMalloc((void**)&ctx->d_n_plain, (n_plain.size() + 1) * sizeof(int));
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_row_ptr, ctx->sched.row_ptr.data(), ctx->sched.row_ptr.size() * sizeof(int), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !k_col.empty()) e = hipMemcpy(ctx->d_col_idx, k_col.data(), k_col.size() * sizeof(int), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !n_plain.empty()) e = hipMemcpy(ctx->d_n_plain, n_plain.data(), n_plain.size() * sizeof(int), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !mask_tbl.empty()) {
-        e = hipMalloc((void**)&ctx->d_mask_tbl, mask_tbl.size() * sizeof(unsigned long long));
-        if (e == hipSuccess) e = hipMemcpy(ctx->d_mask_tbl, mask_tbl.data(), mask_tbl.size() * sizeof(unsigned long long), hipMemcpyHostToDevice);
-    }
-    if (e == hipSuccess && !wave_desc.empty()) {
-        e = hipMalloc((void**)&ctx->d_wave_desc, wave_desc.size() * sizeof(int));
-        if (e == hipSuccess) e = hipMemcpy(ctx->d_wave_desc, wave_desc.data(), wave_desc.size() * sizeof(int), hipMemcpyHostToDevice);
-    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         std::string msg = std::string("HIP error in create: ") + hipGetErrorString(e);
@@ -439,6 +477,31 @@ int clear_attn_reserve(clear_attn_ctx* ctx, int BH)
     }
     ctx->ws_BH = BH;
     ctx->ws_max_splits = splits;
+    return CLEAR_OK;
+}
+
+// Tile lists of the context's grid moved down by y_shift rows (row bands; see prepare_forward), built on first use.
+static int band_tile_tables(clear_attn_ctx* ctx, int y_shift, hipStream_t stream, const TileTables** out)
+{
+    TileTables*& slot = ctx->band_t[y_shift];
+    if (!slot) {
+        if (stream_is_capturing(stream))
+            return fail(ctx, CLEAR_ERR_INVALID_ARG, "the tile lists of this band's first owned row would have to be built while the stream is being captured: make one call with the same own_y0 beforehand");
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+            return fail(ctx, CLEAR_ERR_INVALID_ARG, "the context's device must be current");
+        TileTables* t = new (std::nothrow) TileTables;
+        if (!t) return fail(ctx, CLEAR_ERR_ALLOC, "out of host memory");
+        std::string why;
+        const int rc = build_tile_tables(ctx->gridH + y_shift, ctx->gridW, ctx->head_dim, ctx->r, ctx->dtype, ctx->mask_kind, ctx->mask_shift, t, &why);
+        if (rc != CLEAR_OK) {
+            t->release();
+            delete t;
+            return fail(ctx, rc, why);
+        }
+        slot = t;
+    }
+    *out = slot;
     return CLEAR_OK;
 }
 
@@ -499,7 +562,21 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
         if (n_text > 0 && (((uintptr_t)band->text_o | (uintptr_t)band->text_lse) & 3)) return fail(ctx, CLEAR_ERR_INVALID_ARG, "text_o and text_lse must be 4-byte aligned");
     }
     const int BH = B * H;
-    const Schedule& s = ctx->sched;
+    // A band whose first owned row is not on the query-tile lattice takes tile lists of the grid moved down by y_shift
+    // rows, so that a tile row starts at that row and no workgroup straddles the cut (an owned range starting at row
+    // 15 would otherwise launch five tile rows for four).  The rows above the grid are not masked, so every owned
+    // query's reach (r - 1 rows) must stay inside the grid: own_y0 >= r - 1, which the halo of an inner band gives.
+    const TileTables* tt = &ctx->t;
+    int y_shift = 0;
+    if (band && ctx->dtype == CLEAR_BF16 && ctx->mask_kind == CLEAR_MASK_DISC) {
+        const int qth = ctx->t.sched.qth, rem = band->own_y0 % qth;
+        if (rem != 0 && band->own_y0 >= r - 1 && gridH + qth - rem <= 32767) {
+            y_shift = qth - rem;
+            int rc = band_tile_tables(ctx, y_shift, (hipStream_t)stream, &tt);
+            if (rc != CLEAR_OK) return rc;
+        }
+    }
+    const Schedule& s = tt->sched;
     const long long n_q_tiles = (long long)s.n_qty * s.n_qtx;
     if (n_q_tiles * BH > 0x7fffffffLL) return fail(ctx, CLEAR_ERR_INVALID_ARG, "too many workgroups: B*H*query tiles must fit in 31 bits");
 
@@ -512,13 +589,14 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.n_q_tiles = (int)n_q_tiles;
     p.n_qtx = s.n_qtx;
     p.n_ktx = s.n_ktx;
-    p.row_ptr = ctx->d_row_ptr;
-    p.col_idx = ctx->d_col_idx;
-    p.n_plain = ctx->d_n_plain;
-    p.mask_tbl = ctx->d_mask_tbl;
-    p.wave_desc = ctx->d_wave_desc;
-    p.mask_ry = ctx->mask_ry;
-    p.mask_rx = ctx->mask_rx;
+    p.row_ptr = tt->d_row_ptr;
+    p.col_idx = tt->d_col_idx;
+    p.n_plain = tt->d_n_plain;
+    p.mask_tbl = tt->d_mask_tbl;
+    p.wave_desc = tt->d_wave_desc;
+    p.mask_ry = tt->mask_ry;
+    p.mask_rx = tt->mask_rx;
+    p.y_shift = y_shift;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
     p.n_classes = 1; p.stride = 1; p.stride_rx = p.stride_ry = 0;
     if (ctx->mask_kind == CLEAR_MASK_STRIDED) {
@@ -537,9 +615,9 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.vkeys_text = 0x7fffffff;
     p.vshift = 0;
     if (band) {
-        p.own_y0 = band->own_y0;
-        p.own_y1 = band->own_y1;
-        const int ty0 = band->own_y0 / s.qth, ty1 = (band->own_y1 + s.qth - 1) / s.qth;  // tile rows that hold owned rows
+        p.own_y0 = band->own_y0 + y_shift;  // in tile coordinates
+        p.own_y1 = band->own_y1 + y_shift;
+        const int ty0 = p.own_y0 / s.qth, ty1 = (p.own_y1 + s.qth - 1) / s.qth;  // tile rows that hold owned rows
         p.qt_begin = ty0 * s.n_qtx;
         p.n_q_tiles_launch = (ty1 - ty0) * s.n_qtx;
         // keys of the text queries: [the text keys,] then the owned image rows
@@ -896,7 +974,7 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
         return fail(ctx, CLEAR_ERR_INVALID_ARG, "the backward workspace would have to grow while the stream is being captured: call clear_attn_reserve_backward beforehand");
     int rc = clear_attn_reserve_backward(ctx, BH);
     if (rc != CLEAR_OK) return rc;
-    const Schedule& s = ctx->sched;
+    const Schedule& s = ctx->t.sched;
     BwdParams p;
     memset(&p, 0, sizeof(p));
     p.Q = Q; p.K = K; p.V = V; p.dO = dO; p.lse = lse; p.delta = ctx->d_bwd_delta;
@@ -906,9 +984,9 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
     p.N = N;
     p.n_q_tiles = s.n_qty * s.n_qtx;
     p.n_qtx = s.n_qtx;
-    p.row_ptr = ctx->d_row_ptr; p.col_idx = ctx->d_col_idx; p.n_plain = ctx->d_n_plain; p.mask_tbl = ctx->d_mask_tbl;
-    p.wave_desc = ctx->d_wave_desc;
-    p.mask_ry = ctx->mask_ry; p.mask_rx = ctx->mask_rx;
+    p.row_ptr = ctx->t.d_row_ptr; p.col_idx = ctx->t.d_col_idx; p.n_plain = ctx->t.d_n_plain; p.mask_tbl = ctx->t.d_mask_tbl;
+    p.wave_desc = ctx->t.d_wave_desc;
+    p.mask_ry = ctx->t.mask_ry; p.mask_rx = ctx->t.mask_rx;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;
     p.n_classes = 1; p.stride = 1; p.stride_rx = p.stride_ry = 0;
     if (ctx->mask_kind == CLEAR_MASK_STRIDED) {
@@ -1021,11 +1099,13 @@ int clear_attn_merge_text(int n_parts, const float* const* text_o, const float* 
 void clear_attn_destroy(clear_attn_ctx* ctx)
 {
     if (!ctx) return;
-    if (ctx->d_row_ptr) (void)hipFree(ctx->d_row_ptr);
-    if (ctx->d_col_idx) (void)hipFree(ctx->d_col_idx);
-    if (ctx->d_n_plain) (void)hipFree(ctx->d_n_plain);
-    if (ctx->d_mask_tbl) (void)hipFree(ctx->d_mask_tbl);
-    if (ctx->d_wave_desc) (void)hipFree(ctx->d_wave_desc);
+    ctx->t.release();
+    for (TileTables*& bt : ctx->band_t)
+        if (bt) {
+            bt->release();
+            delete bt;
+            bt = nullptr;
+        }
     if (ctx->d_ws_o) (void)hipFree(ctx->d_ws_o);
     if (ctx->d_ws_ml) (void)hipFree(ctx->d_ws_ml);
     if (ctx->d_bwd_delta) (void)hipFree(ctx->d_bwd_delta);
@@ -1041,7 +1121,7 @@ int clear_attn_schedule_size(const clear_attn_ctx* ctx, int* q_tile_h, int* q_ti
                              int* n_q_tiles, long long* n_pairs)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
-    const Schedule& s = ctx->sched;
+    const Schedule& s = ctx->t.sched;
     if (q_tile_h) *q_tile_h = s.qth;
     if (q_tile_w) *q_tile_w = s.qtw;
     if (k_tile_h) *k_tile_h = s.kth;
@@ -1054,7 +1134,7 @@ int clear_attn_schedule_size(const clear_attn_ctx* ctx, int* q_tile_h, int* q_ti
 int clear_attn_schedule_copy(const clear_attn_ctx* ctx, int* row_ptr, int* col_idx, unsigned char* flags)
 {
     if (!ctx) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "ctx is NULL");
-    const Schedule& s = ctx->sched;
+    const Schedule& s = ctx->t.sched;
     if (row_ptr) memcpy(row_ptr, s.row_ptr.data(), s.row_ptr.size() * sizeof(int));
     if (col_idx) memcpy(col_idx, s.col_idx.data(), s.col_idx.size() * sizeof(int));
     if (flags) memcpy(flags, s.flags.data(), s.flags.size());
@@ -1065,9 +1145,9 @@ int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pai
 {
     if (!ctx || !pairs_per_head) return fail(nullptr, CLEAR_ERR_INVALID_ARG, "NULL argument");
     if (ctx->mask_kind == CLEAR_MASK_STRIDED)
-        *pairs_per_head = executed_pairs_bf16_strided(ctx->sched, ctx->n_text, ctx->gridH, ctx->gridW, ctx->r, ctx->mask_shift);
+        *pairs_per_head = executed_pairs_bf16_strided(ctx->t.sched, ctx->n_text, ctx->gridH, ctx->gridW, ctx->r, ctx->mask_shift);
     else
-        *pairs_per_head = (ctx->dtype == CLEAR_BF16) ? executed_pairs_bf16(ctx->sched, ctx->n_text, 0) : executed_pairs_f32(ctx->sched, ctx->n_text);
+        *pairs_per_head = (ctx->dtype == CLEAR_BF16) ? executed_pairs_bf16(ctx->t.sched, ctx->n_text, 0) : executed_pairs_f32(ctx->t.sched, ctx->n_text);
     return CLEAR_OK;
 }
 

@@ -78,7 +78,7 @@ struct FwdParams {
     float* ws_o;      // [B*H][n_splits][n_text][head_dim] un-normalised partial outputs
     float* ws_ml;     // [B*H][n_splits][n_text][2]        running max (raw logit) and denominator
     // Row-band mode (one band of image rows with its halo; Sec. 3.4).  Whole grid: own_y0 = 0, own_y1 = gridH,
-    // qt_begin = 0, n_q_tiles_launch = n_q_tiles, NV = N, vkeys_text = INT_MAX, vshift = 0, band_o = null.
+    // qt_begin = 0, n_q_tiles_launch = n_q_tiles, NV = N, vkeys_text = INT_MAX, vshift = 0, y_shift = 0, band_o = null.
     int own_y0, own_y1;    // image rows whose queries are computed; the other rows are halo: keys only
     int qt_begin;          // first query tile launched (tile rows covering the owned rows)
     int n_q_tiles_launch;  // query tiles launched per (batch, head)
@@ -86,6 +86,7 @@ struct FwdParams {
     long long NV;
     int vkeys_text;
     int vshift;
+    int y_shift;      // tile coordinates (own_y0, own_y1, the tile lists) = image row + y_shift; the grid then spans rows [y_shift, y_shift + gridH)
     float* band_o;    // when set, the text merge writes fp32 softmax outputs [B*H][n_text][head_dim] here ...
     float* band_lse;  // ... and the natural log of the softmax denominators [B*H][n_text] here, not O's text rows
     int mask_kind, mask_r, mask_shift;  // MaskKind, radius / window size, Swin shift

@@ -265,8 +265,11 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
     // token (y * stride + oy, x * stride + ox) of the raster.  Plain masks: both are the raster itself.
     // Strided mask: the workgroup belongs to one residue class of the queries, (q_oy, q_ox) = (y % stride,
     // x % stride), and reads the keys of the class moved by (stride_ry, stride_rx).
+    // Row bands may move the grid down by y_shift rows in these coordinates (so that a query tile starts at the first
+    // owned row): grid rows then start at y_shift, and only where a token's address is formed is the shift taken off.
     int stride = 1, q_oy = 0, q_ox = 0, k_oy = 0, k_ox = 0;
-    int qH = p.gridH, qW = p.gridW, kH = p.gridH, kW = p.gridW;
+    const int y_shift = TEXTQ ? 0 : p.y_shift;
+    int qH = p.gridH + y_shift, qW = p.gridW, kH = p.gridH + y_shift, kW = p.gridW;
     if (TEXTQ) {
         split = vid % p.n_splits;
         const int t = vid / p.n_splits;
@@ -314,7 +317,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         // (row-band mode: only the rows [own_y0, own_y1) carry queries; the halo rows are keys only)
         q_valid = qy < qH && qx < qW && qy >= p.own_y0 && qy < p.own_y1;
         wave_has_queries = wy0 < qH && wx0 < qW && wy0 < p.own_y1 && wy0 + kWaveQH > p.own_y0;
-        q_token = p.n_text + (imin(qy, qH - 1) * stride + q_oy) * p.gridW + imin(qx, qW - 1) * stride + q_ox;
+        q_token = p.n_text + (imax(imin(qy, qH - 1) - y_shift, 0) * stride + q_oy) * p.gridW + imin(qx, qW - 1) * stride + q_ox;
     }
 
     // Q^T as MFMA B operand: KS contraction steps of 16 channels; this lane supplies channels 16*s + 8*hh .. +7
@@ -381,7 +384,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
                 token = imin(a + row, lin_limit - 1);
                 if (TEXTQ && token >= p.vkeys_text) token += p.vshift;  // position in the key list -> token
             } else {
-                const int ky = imin(a + (row >> 3), kH - 1);
+                const int ky = imax(imin(a + (row >> 3), kH - 1) - y_shift, 0);  // (rows above the grid: out of every owned query's reach)
                 const int kx = imin(b + (row & 7), kW - 1);
                 token = p.n_text + (ky * stride + k_oy) * p.gridW + kx * stride + k_ox;
             }
@@ -506,12 +509,12 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
             si.cls0 = classify_full_block(wy0, wx0, qH, qW, ta, tb, kKeyBlockH, kKeyBlockW, kH, kW);
             si.cls1 = classify_full_block(wy0, wx0, qH, qW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, kH, kW);
         } else if (CODE == kCodeDisc) {
-            si.cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
-            si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW, p.r2);
+            si.cls0 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, kH, kW, p.r2);
+            si.cls1 = classify_image_block(wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, kH, kW, p.r2);
         } else {
             const MaskSpec spec = {p.mask_kind, p.mask_r, p.mask_shift};
-            si.cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
-            si.cls1 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
+            si.cls0 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta, tb, kKeyBlockH, kKeyBlockW, kH, kW);
+            si.cls1 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, kH, kW);
         }
         si.tile_lds = lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES);
         si.ma.hh = hh;
@@ -579,7 +582,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         // are in flight together (one memory round trip per half, not one per chunk).  A step that is switched
         // off reads the other step's table instead (any D readable floats) and ignores what it read.
         const float* const any_table = has_gain ? p.q_gain : p.rope_y;
-        const float* const ysrc = turn ? p.rope_y + (size_t)(imin(qy, qH - 1) * stride + q_oy) * D : any_table;
+        const float* const ysrc = turn ? p.rope_y + (size_t)(imax(imin(qy, qH - 1) - y_shift, 0) * stride + q_oy) * D : any_table;
         const float* const xsrc = turn ? p.rope_x + (size_t)(imin(qx, qW - 1) * stride + q_ox) * D : any_table;
         constexpr int HALF = KS / 2;
 #pragma unroll
@@ -800,7 +803,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
             const int oy = wy0 + (row >> 3), ox = wx0 + (row & 7);
             const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane % CHUNKS) * 16);
             if (oy < qH && ox < qW && oy >= p.own_y0 && oy < p.own_y1) {
-                __bf16* orow = (__bf16*)p.O + batch * p.os.sb + head * p.os.sh + ((long long)p.n_text + (long long)(oy * stride + q_oy) * p.gridW + ox * stride + q_ox) * p.os.sn;
+                __bf16* orow = (__bf16*)p.O + batch * p.os.sb + head * p.os.sh + ((long long)p.n_text + (long long)((oy - y_shift) * stride + q_oy) * p.gridW + ox * stride + q_ox) * p.os.sn;
                 *(f32x4*)(orow + (lane % CHUNKS) * 8) = chunk;
             }
         }

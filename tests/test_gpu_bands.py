@@ -85,6 +85,49 @@ def test_bands_with_a_tile_aligned_halo():
     assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
 
 
+def _one_band_vs_oracle(ctx, Q, K, V, n_text, gridH, gridW, r, y0, y1, top):
+    """Runs rows [y0, y1) of the undivided problem as a band whose local grid starts `top` rows above y0 and ends at
+    the bottom halo; returns (max_abs, rel_rms) of the owned rows against the oracle of the undivided problem."""
+    hb = min(r - 1, gridH - y1)
+    rows = slice(n_text + (y0 - top) * gridW, n_text + (y1 + hb) * gridW)
+    loc = [torch.cat([t[:, :, :n_text], t[:, :, rows]], dim=2).contiguous() for t in (Q, K, V)]
+    Ol = torch.full_like(loc[0], float("nan"))
+    ctx.forward_band(loc[0], loc[1], loc[2], Ol, top, top + (y1 - y0), True)
+    torch.cuda.synchronize()
+    own = Ol[0, :, n_text + top * gridW: n_text + (top + y1 - y0) * gridW].float().cpu().numpy()
+    assert np.isfinite(own).all()
+    assert torch.isnan(Ol[:, :, n_text:n_text + top * gridW].float()).all()
+    assert torch.isnan(Ol[:, :, n_text + (top + y1 - y0) * gridW:].float()).all()
+    idx = np.arange(n_text + y0 * gridW, n_text + y1 * gridW)
+    ref = np.stack([orc.attention_rows(*(t[0, h].float().cpu().numpy() for t in (Q, K, V)), idx, n_text, gridH, gridW, r)
+                    for h in range(Q.shape[1])])
+    return error_metrics(own, ref)
+
+
+def test_band_starting_off_the_tile_lattice():
+    """Owned ranges whose first row is not a multiple of the 16-row query tile.  On one context: r - 1 or more halo
+    rows above (the tile lists are then moved so that a tile row starts at the first owned row: two different moves,
+    the first one used again, ranges ending on and inside a tile).  On another: fewer than r - 1 rows above because
+    the image ends there (the tile lists of the grid as it is)."""
+    n_text, gridH, gridW, d, r, H = 40, 88, 40, 128, 8, 2
+    Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, "bf16", seed=77, device="cuda:0")
+    # every local grid has top + (y1 - y0) + 7 = 46 rows; the first owned local row is 7 or 10
+    ctx = ca.ClearAttn(n_text, 46, gridW, d, r, ca.CLEAR_BF16)
+    try:
+        for y0, y1, top in [(23, 55, 7), (26, 55, 10), (23, 55, 7), (42, 71, 10)]:
+            max_abs, rel_rms = _one_band_vs_oracle(ctx, Q, K, V, n_text, gridH, gridW, r, y0, y1, top)
+            assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (y0, y1, top, max_abs, rel_rms)
+    finally:
+        ctx.destroy()
+    # the band at the top of the image, queries from row 5 on: only 5 rows above, fewer than r - 1
+    ctx = ca.ClearAttn(n_text, 5 + 21 + 7, gridW, d, r, ca.CLEAR_BF16)
+    try:
+        max_abs, rel_rms = _one_band_vs_oracle(ctx, Q, K, V, n_text, gridH, gridW, r, 5, 26, 5)
+        assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
+    finally:
+        ctx.destroy()
+
+
 @pytest.mark.parametrize("dtype,n_text,gridH,gridW,d,r,H,n_bands", [c for c in CASES if c[1] > 0])
 def test_bands_average_is_eq7(dtype, n_text, gridH, gridW, d, r, H, n_bands):
     Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, dtype, seed=200 + n_bands, device="cuda:0")
