@@ -24,6 +24,7 @@ struct TileTables {
     int* d_row_ptr = nullptr;
     int* d_col_idx = nullptr;   // kernel order: tiles inside the grid first, border tiles last
     int* d_n_plain = nullptr;
+    int* d_qt_order = nullptr;   // bf16: the order in which a head's query tiles are dealt to the workgroups (see build_tile_tables)
     unsigned long long* d_mask_tbl = nullptr;
     int* d_wave_desc = nullptr;  // per listed key tile and wave: mask-table entries of its blocks (bf16, with d_mask_tbl)
     int mask_ry = 0, mask_rx = 0;
@@ -32,9 +33,10 @@ struct TileTables {
         if (d_row_ptr) (void)hipFree(d_row_ptr);
         if (d_col_idx) (void)hipFree(d_col_idx);
         if (d_n_plain) (void)hipFree(d_n_plain);
+        if (d_qt_order) (void)hipFree(d_qt_order);
         if (d_mask_tbl) (void)hipFree(d_mask_tbl);
         if (d_wave_desc) (void)hipFree(d_wave_desc);
-        d_row_ptr = d_col_idx = d_n_plain = d_wave_desc = nullptr;
+        d_row_ptr = d_col_idx = d_n_plain = d_qt_order = d_wave_desc = nullptr;
         d_mask_tbl = nullptr;
     }
 };
@@ -286,7 +288,32 @@ static int build_tile_tables(int gridH, int gridW, int head_dim, int r, int dtyp
             mask_tbl.clear();
         }
     }
+    // Order of a head's query tiles over its workgroups.  An XCD (32 CUs, one workgroup each, one 4 MB L2) works through
+    // a contiguous range of that order, so the tiles in flight on it are 32 consecutive entries.  Row by row on a wide
+    // grid they are a 1 x 32 strip of tiles, whose keys - 16 + 2 (r - 1) rows across 512 columns - the next strip
+    // needs again but finds evicted.  Dealt out in blocks of 2 x 16 tiles, strips of 16 tile columns taken top to
+    // bottom, the tiles in flight form a more compact patch: a quarter fewer L2 misses at a 512 x 512 grid (18.9 ->
+    // 14.1 GB per launch of 24 heads), same time.  Grids up to 16 tiles wide keep the plain order (no table).
+    constexpr int kOrderRows = 2, kOrderCols = 16;
+    std::vector<int> qt_order;
+    if (dtype == CLEAR_BF16 && !strided && t->sched.n_qtx > kOrderCols) {
+        const Schedule& sc = t->sched;
+        try {
+            qt_order.reserve((size_t)sc.n_qty * sc.n_qtx);
+            for (int bx = 0; bx < sc.n_qtx; bx += kOrderCols)
+                for (int by = 0; by < sc.n_qty; by += kOrderRows)
+                    for (int ty = by; ty < std::min(by + kOrderRows, sc.n_qty); ++ty)
+                        for (int tx = bx; tx < std::min(bx + kOrderCols, sc.n_qtx); ++tx) qt_order.push_back(ty * sc.n_qtx + tx);
+        } catch (const std::bad_alloc&) {
+            *why = "out of host memory building the query-tile order";
+            return CLEAR_ERR_ALLOC;
+        }
+    }
     hipError_t e = hipSuccess;
+    if (e == hipSuccess && !qt_order.empty()) {
+        e = hipMalloc((void**)&t->d_qt_order, qt_order.size() * sizeof(int));
+        if (e == hipSuccess) e = hipMemcpy(t->d_qt_order, qt_order.data(), qt_order.size() * sizeof(int), hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = hipMalloc((void**)&t->d_row_ptr, t->sched.row_ptr.size() * sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&t->d_col_idx, (k_col.size() + 1) * sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&t->d_n_plain, (n_plain.size() + 1) * sizeof(int));
@@ -592,6 +619,7 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     p.row_ptr = tt->d_row_ptr;
     p.col_idx = tt->d_col_idx;
     p.n_plain = tt->d_n_plain;
+    p.qt_order = band ? nullptr : tt->d_qt_order;  // (a band launches a range of tile rows)
     p.mask_tbl = tt->d_mask_tbl;
     p.wave_desc = tt->d_wave_desc;
     p.mask_ry = tt->mask_ry;

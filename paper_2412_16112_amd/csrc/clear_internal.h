@@ -66,6 +66,7 @@ struct FwdParams {
     const int* row_ptr;  // device CSR
     const int* col_idx;  // per query tile: key tile origins (row << 16 | col), tiles inside the grid first (ascending), then the ones cut by the border
     const int* n_plain;  // per query tile: how many of its key tiles lie inside the grid
+    const int* qt_order;  // bf16 image-query kernel, whole-grid launches: the query tile that the i-th workgroup of a head takes (null: i)
     const unsigned long long* mask_tbl;  // bf16 kernels: lane masks per relative block offset (may be null)
     int mask_ry, mask_rx;
     const int* wave_desc;  // bf16 kernels, with mask_tbl: per listed key tile (kernel order) and wave of the workgroup, the mask-table

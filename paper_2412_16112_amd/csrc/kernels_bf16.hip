@@ -277,6 +277,7 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
         bh = t / p.n_tq_tiles;
     } else {
         qt = p.qt_begin + vid % p.n_q_tiles_launch;
+        if (p.qt_order) qt = ((const_int_ptr)p.qt_order)[qt];  // the order in which a head's query tiles are dealt out
         bh = vid / p.n_q_tiles_launch;
         if (CODE == kCodeFull) {
             const int cls = bh % p.n_classes;

@@ -65,6 +65,7 @@ def test_f32_small_cases(B, H, n_text, gh, gw, r):
     (1, 1, 1, 1, 1, 3),
     (1, 2, 512, 48, 48, 16),   # FLUX-like text length, several query tiles, r = 16
     (1, 1, 64, 40, 72, 8),
+    (1, 2, 24, 40, 300, 6),    # more than 16 query tiles across: the tiles are dealt to the workgroups in 2 x 16 blocks
 ])
 def test_bf16_small_cases(B, H, n_text, gh, gw, r):
     _run_full_compare(B, H, n_text, gh, gw, 128, r, "bf16", seed=200 + gh)
