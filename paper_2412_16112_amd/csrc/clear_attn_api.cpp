@@ -1012,7 +1012,7 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
     p.N = N;
     p.n_q_tiles = s.n_qty * s.n_qtx;
     p.n_qtx = s.n_qtx;
-    p.row_ptr = ctx->t.d_row_ptr; p.col_idx = ctx->t.d_col_idx; p.n_plain = ctx->t.d_n_plain; p.mask_tbl = ctx->t.d_mask_tbl;
+    p.row_ptr = ctx->t.d_row_ptr; p.col_idx = ctx->t.d_col_idx; p.n_plain = ctx->t.d_n_plain; p.qt_order = ctx->t.d_qt_order; p.mask_tbl = ctx->t.d_mask_tbl;
     p.wave_desc = ctx->t.d_wave_desc;
     p.mask_ry = ctx->t.mask_ry; p.mask_rx = ctx->t.mask_rx;
     p.mask_kind = ctx->mask_kind; p.mask_r = r; p.mask_shift = ctx->mask_shift;

@@ -138,6 +138,7 @@ struct BwdParams {
     const int* row_ptr;
     const int* col_idx;
     const int* n_plain;
+    const int* qt_order;  // as in FwdParams
     const unsigned long long* mask_tbl;
     int mask_ry, mask_rx;
     const int* wave_desc;  // as in FwdParams (rows and columns swap roles for dK and dV; the masks with a table are symmetric)

@@ -87,6 +87,7 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
         bh = t / p.n_tq_tiles;
     } else {
         rt = vid % p.n_q_tiles;
+        if (p.qt_order) rt = ((const_int_ptr)p.qt_order)[rt];  // the order in which a head's row tiles are dealt out
         bh = vid / p.n_q_tiles;
     }
     // Image rows live on an rH x rW grid and image columns on a cH x cW grid; grid point (y, x) is image token
