@@ -63,9 +63,12 @@ CASES = [
     ("bf16", 37, 50, 19, 128, 6, 1, 7),     # uneven bands, ragged tiles everywhere
     ("bf16", 0, 48, 32, 128, 8, 1, 3),      # no text tokens
 ]
+# (head_dim 64 only against the undivided problem: its flatter softmax rows leave Eq. 7 too close to the exact merge
+# for the test of the average to tell them apart)
+CASES_D64 = [("bf16", 24, 40, 24, 64, 8, 2, 2)]
 
 
-@pytest.mark.parametrize("dtype,n_text,gridH,gridW,d,r,H,n_bands", CASES)
+@pytest.mark.parametrize("dtype,n_text,gridH,gridW,d,r,H,n_bands", CASES + CASES_D64)
 def test_bands_exact_equal_the_undivided_problem(dtype, n_text, gridH, gridW, d, r, H, n_bands):
     Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, dtype, seed=100 + n_bands, device="cuda:0")
     O = run_bands(Q, K, V, n_text, gridH, gridW, r, n_bands, ca.CLEAR_MERGE_EXACT)
