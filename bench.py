@@ -99,18 +99,23 @@ def main():
         step = lambda: ctx.forward(Q, K, V, O)
     for _ in range(args.warmup):
         step()
-    # Exactly `steps` timed calls between two synchronisations: `ms_per_step` is the wall-clock mean over them;
-    # a HIP event on the launch stream before and after every call gives the per-call times, whose median is
-    # reported beside it (the events are recorded on the stream the library launches on: torch's current one).
-    events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    # Exactly `steps` timed calls between two synchronisations: `ms_per_step` is the wall-clock mean over them.
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    # Then the same calls once more with a HIP event on the launch stream before and after each (the stream the
+    # library launches on: torch's current one): the median, minimum and maximum of the per-call times are reported
+    # beside the mean.  (The events stay out of the loop above: between calls of a tenth of a millisecond they
+    # cost a tenth of the call.)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     events[0].record()
     for i in range(args.steps):
         step()
         events[i + 1].record()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     per_call_ms = sorted(events[i].elapsed_time(events[i + 1]) for i in range(args.steps))
     ms_median = per_call_ms[len(per_call_ms) // 2] if len(per_call_ms) % 2 else 0.5 * (per_call_ms[len(per_call_ms) // 2 - 1] + per_call_ms[len(per_call_ms) // 2])
@@ -118,7 +123,7 @@ def main():
         O.copy_(Os)  # for the check against the oracle below
 
     # per-kernel durations, HIP events on the launch stream
-    phase_ms = ctx.forward_profile(Q, K, V, O, reps=max(3, args.steps))
+    phase_ms = ctx.forward_profile(Q, K, V, O, reps=min(256, max(3, args.steps)))
 
     BH = w.B * w.H
     sum_m = ca.clear_attn_mask_count_masked(w.n_text, w.gridH, w.gridW, w.r, mask_kind, args.shift)

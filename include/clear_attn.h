@@ -71,8 +71,9 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
  * forward() calls this itself when it meets a larger B*H than any before, which allocates and
  * synchronises; call reserve first if forward must not allocate.  A forward call (any variant, backward
  * included) that would have to grow a workspace while `stream` is being captured into a HIP graph returns
- * CLEAR_ERR_INVALID_ARG instead and launches nothing: reserve beforehand, or make one eager call first; a
- * small problem whose second stream no earlier call has created stays on `stream` alone under capture.
+ * CLEAR_ERR_INVALID_ARG instead and launches nothing: reserve beforehand, or make one eager call first (the
+ * backward pass of a small problem, which runs its independent kernels on a second stream of the context, stays
+ * on `stream` alone under capture if no earlier call has created that stream).
  * Returns CLEAR_ERR_ALLOC on failure.
  */
 int clear_attn_reserve(clear_attn_ctx* ctx, int BH);
@@ -93,7 +94,7 @@ int clear_attn_forward(clear_attn_ctx* ctx, const void* Q, const void* K, const 
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results as clear_attn_forward, but
  * it calls no hipMalloc / hipFree and no allocating library routine: the key-split partial results of the
  * text-query rows go to a static device array of the library (112 MiB per GPU, held until the process ends)
- * instead of the context's workspace, and the call stays on `stream` alone (no second stream for small problems).
+ * instead of the context's workspace.
  * A call whose partial results (B*H * key splits * n_text * (head_dim + 2) floats) do not fit the array returns
  * CLEAR_ERR_UNSUPPORTED with the sizes in clear_attn_last_error, and launches nothing; the FLUX-8K shape (B*H = 24,
  * 16 splits, 512 text tokens, head_dim 128: 102 MB) fits.  The context's device must be the current one.

@@ -59,8 +59,8 @@ struct clear_attn_ctx {
     int bwd_BH = 0;
     float* d_bwd_delta = nullptr;  // [B*H][N]
     float* d_bwd_ws = nullptr;     // [3][B*H][max splits][n_text][head_dim]
-    // second stream and fork / join events for small problems, where the image-query kernel leaves CUs idle that
-    // the text-query kernels can use (created on first use; default stream priority)
+    // second stream and fork / join events of the backward pass of small problems, whose independent kernels then run
+    // side by side (created on first use; default stream priority)
     hipStream_t aux_stream = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // keys after the prologue (clear_attn_forward_prologue), grown on demand
@@ -148,23 +148,33 @@ static int max_text_splits(long long N)
 
 // Splits for a given batch*heads: at least two workgroups per CU when the keys allow it, and a workgroup
 // count that fills whole rounds of the CUs (a partial last round idles most of the chip).
-static void choose_text_splits(long long N, int BH, int n_tq_tiles, int num_cus, int* n_splits, int* split_keys)
+// `together`: the text-query workgroups go out in one launch with the image-query ones (launch_all) and fill the CUs
+// that those leave idle, so whole rounds do not matter; what then costs is the number of splits (partial results
+// written, read back and merged) and the length of a text-query workgroup when it is the last to finish: one round
+// of workgroups at most, of at least 2 048 keys each.  (Measured over 1 - 32 splits, 24 heads: 2 splits at a 64 x 64
+// grid and 5 at 128 x 128 and 256 x 256 beat the whole-rounds choice of 5, 16 and 16 by 6 %, 8 % and 2 %.)
+static void choose_text_splits(long long N, int BH, int n_tq_tiles, int num_cus, bool together, int* n_splits, int* split_keys)
 {
     const int max_s = max_text_splits(N);
     const long long units = (long long)BH * n_tq_tiles;
     int best = 1;
     double best_score = -1.0;
-    for (int s = 1; s <= max_s; ++s) {
-        long long keys = (N + s - 1) / s;
-        keys = ((keys + kKeyTileKeys - 1) / kKeyTileKeys) * kKeyTileKeys;
-        const long long real = (N + keys - 1) / keys;  // splits that actually hold keys
-        const long long wgs = units * real;
-        const long long rounds = (wgs + num_cus - 1) / num_cus;
-        double score = (double)wgs / (double)(rounds * num_cus);  // fraction of the rounds that is busy
-        if (wgs < 2LL * num_cus) score *= 0.5;                    // too few workgroups to hide a workgroup's start-up
-        if (score > best_score + 1e-9) {
-            best_score = score;
-            best = s;
+    if (together && units < num_cus) {
+        best = (int)std::min<long long>(max_s, num_cus / units);
+        while (best > 1 && N / best < 2048) --best;
+    } else {
+        for (int s = 1; s <= max_s; ++s) {
+            long long keys = (N + s - 1) / s;
+            keys = ((keys + kKeyTileKeys - 1) / kKeyTileKeys) * kKeyTileKeys;
+            const long long real = (N + keys - 1) / keys;  // splits that actually hold keys
+            const long long wgs = units * real;
+            const long long rounds = (wgs + num_cus - 1) / num_cus;
+            double score = (double)wgs / (double)(rounds * num_cus);  // fraction of the rounds that is busy
+            if (wgs < 2LL * num_cus) score *= 0.5;                    // too few workgroups to hide a workgroup's start-up
+            if (score > best_score + 1e-9) {
+                best_score = score;
+                best = s;
+            }
         }
     }
     long long keys = (N + best - 1) / best;
@@ -507,6 +517,13 @@ int clear_attn_reserve(clear_attn_ctx* ctx, int BH)
     return CLEAR_OK;
 }
 
+// Whether a forward call sends its image-query and text-query workgroups out in one launch (see launch_all).
+static bool launches_together(const clear_attn_ctx* ctx, const FwdParams& p)
+{
+    const long long image_wgs = (long long)p.B * p.H * p.n_classes * p.n_q_tiles_launch;
+    return ctx->dtype == CLEAR_BF16 && p.n_text > 0 && image_wgs <= 64LL * ctx->num_cus;
+}
+
 // Tile lists of the context's grid moved down by y_shift rows (row bands; see prepare_forward), built on first use.
 static int band_tile_tables(clear_attn_ctx* ctx, int y_shift, hipStream_t stream, const TileTables** out)
 {
@@ -658,7 +675,7 @@ static int prepare_forward(clear_attn_ctx* ctx, const void* Q, const void* K, co
     if (n_text > 0) {
         const int per_block = ctx->dtype == CLEAR_BF16 ? bf16_text_queries_per_block() : f32_text_queries_per_block();
         p.n_tq_tiles = (n_text + per_block - 1) / per_block;
-        choose_text_splits(p.NV, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
+        choose_text_splits(p.NV, BH, p.n_tq_tiles, ctx->num_cus, launches_together(ctx, p), &p.n_splits, &p.split_keys);
         if (noalloc) {
             // partial outputs, then (maximum, denominator) pairs, both inside the static scratch array
             const size_t rows = (size_t)BH * p.n_splits * n_text;
@@ -700,28 +717,18 @@ static hipError_t ensure_aux_stream(clear_attn_ctx* ctx)
 }
 
 // A whole forward pass.  The image-query rows and the text-query rows are independent (they read Q, K, V and
-// write disjoint rows of O).  When the image-query kernel has fewer than a few workgroups per CU - small images -
-// its rounds leave CUs idle, so the text-query kernel and its merge run beside it on a second stream, forked
-// from and joined to the caller's stream with events (measured: 9 % faster at a 64 x 64 grid, 5 - 7 % at
-// 128 x 128).  Large problems keep one stream: there the chip is power-limited and the two kernels side by side
-// are slower than one after the other (1 % at 256 x 256, 3 - 4 % at 512 x 512).
+// write disjoint rows of O).  Up to 64 image-query workgroups per CU the two go out as one launch, image-query
+// workgroups first: the text-query workgroups then fill the CUs that the last round of image-query workgroups
+// leaves idle, and a launch is saved.  Measured against one launch after the other (bit-identical output): 12 %
+// faster at a 64 x 64 grid, 5 % at 128 x 128, 0.5 % at 256 x 256, 7 % at head_dim 64 on 256 x 256 with 38 heads;
+// at 512 x 512 x 24 heads (96 workgroups per CU) 0.6 % slower, so the largest problems keep two launches.  (An
+// earlier version ran the text-query kernels on a second stream beside the image-query kernel: slower than this
+// at every size, and a stream and two events to create.)
 static hipError_t launch_all(clear_attn_ctx* ctx, const FwdParams& p, hipStream_t stream)
 {
-    const long long image_wgs = (long long)p.B * p.H * p.n_classes * p.n_q_tiles_launch;
-    // (under stream capture the second stream is used only if an earlier call has made it: creating it is not
-    // something a capture should see)
-    const bool beside = ctx->dtype == CLEAR_BF16 && p.n_text > 0 && image_wgs <= 8LL * ctx->num_cus &&
-                        (ctx->aux_stream != nullptr || !stream_is_capturing(stream));
-    if (!beside) return launch(ctx, p, stream, kPhaseAll);
-    hipError_t e = ensure_aux_stream(ctx);
-    if (e != hipSuccess) return e;
-    e = hipEventRecord(ctx->ev_fork, stream);
-    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0);
-    if (e == hipSuccess) e = launch(ctx, p, ctx->aux_stream, kPhaseTextQuery);
-    if (e == hipSuccess) e = launch(ctx, p, ctx->aux_stream, kPhaseTextMerge);
-    if (e == hipSuccess) e = hipEventRecord(ctx->ev_join, ctx->aux_stream);
-    if (e == hipSuccess) e = launch(ctx, p, stream, kPhaseImage);
-    if (e == hipSuccess) e = hipStreamWaitEvent(stream, ctx->ev_join, 0);
+    if (!launches_together(ctx, p)) return launch(ctx, p, stream, kPhaseAll);
+    hipError_t e = launch(ctx, p, stream, kPhaseImageAndTextQuery);
+    if (e == hipSuccess) e = launch(ctx, p, stream, kPhaseTextMerge);
     return e;
 }
 
@@ -747,10 +754,9 @@ int clear_attn_forward_noalloc(clear_attn_ctx* ctx, const void* Q, const void* K
     FwdParams p;
     int rc = prepare_forward(ctx, Q, K, V, O, B, H, n_text, gridH, gridW, head_dim, r, nullptr, &p, stream, nullptr, true);
     if (rc != CLEAR_OK) return rc;
-    // One stream only: the second stream that clear_attn_forward gives small problems is created on demand.
     // Nothing in the scratch array has to start at zero: the text-query kernel writes every (split, row) entry
     // that the merge reads.
-    hipError_t e = launch(ctx, p, (hipStream_t)stream, kPhaseAll);
+    hipError_t e = launch_all(ctx, p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, CLEAR_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return CLEAR_OK;
 }
@@ -1028,7 +1034,7 @@ static int backward_impl(clear_attn_ctx* ctx, const void* Q, const void* K, cons
     if (n_text > 0) {
         const int per_block = bf16_text_queries_per_block();
         p.n_tq_tiles = (n_text + per_block - 1) / per_block;
-        choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, &p.n_splits, &p.split_keys);
+        choose_text_splits(N, BH, p.n_tq_tiles, ctx->num_cus, false, &p.n_splits, &p.split_keys);
         p.ws = ctx->d_bwd_ws;
     }
     auto run = [&](hipStream_t st, int phase) {

@@ -105,7 +105,8 @@ struct FwdParams {
 
 // Launchers (kernels_bf16.hip, kernels_f32.hip).  Each returns the first HIP error met.
 // phase: kPhaseAll, or one of the three kernels of a forward pass (used to time them one by one).
-enum Phase : int { kPhaseAll = -1, kPhaseImage = 0, kPhaseTextQuery = 1, kPhaseTextMerge = 2 };
+// kPhaseImageAndTextQuery (bf16 only): the first two in one launch.
+enum Phase : int { kPhaseAll = -1, kPhaseImage = 0, kPhaseTextQuery = 1, kPhaseTextMerge = 2, kPhaseImageAndTextQuery = 3 };
 hipError_t launch_bf16_d128(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_bf16_d64(const FwdParams& p, hipStream_t stream, int phase);
 hipError_t launch_f32_d64(const FwdParams& p, hipStream_t stream, int phase);

@@ -27,6 +27,7 @@
 #if CLEAR_HEAD_DIM == 64
 // second compilation of this file: its own kernel and launcher names
 #define clear_fwd_bf16_kernel clear_fwd_bf16_d64_kernel
+#define clear_fwd_bf16_both_kernel clear_fwd_bf16_d64_both_kernel
 #define launch_bf16 launch_bf16_d64
 #else
 #define launch_bf16 launch_bf16_d128
@@ -228,8 +229,9 @@ __device__ __forceinline__ void fast_stage(WaveState& ws, const bf16x8 (&qf)[KS]
     ws.l_run += sum;
 }
 
+// One workgroup of a forward launch: workgroup `bid` of `nblk` (image-query rows, or with TEXTQ the text-query rows).
 template <int NWY, int NWX, bool TEXTQ, int CODE>
-__global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <= 4 && kLoaderWaves == 0) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
+__device__ __forceinline__ void clear_fwd_bf16_workgroup(const FwdParams& p, const int bid, const int nblk)
 {
     constexpr int NW = NWY * NWX;
     constexpr int NI = TILE_KEYS / ROWS_PER_LOAD / NW;  // 1 KB load instructions per wave per tile, for K and for V each, when every wave loads
@@ -255,7 +257,6 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
     // round-robin to the 8 XCDs, so give each XCD one contiguous range of the logical index.
     int vid;
     {
-        const int nblk = gridDim.x, bid = blockIdx.x;
         const int xcd = bid & 7, idx = bid >> 3;
         const int q = nblk >> 3, rem = nblk & 7;
         vid = xcd * q + imin(xcd, rem) + idx;
@@ -811,6 +812,25 @@ __global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <=
     }
 }
 
+template <int NWY, int NWX, bool TEXTQ, int CODE>
+__global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, (NWY * NWX <= 4 && kLoaderWaves == 0) ? 2 : 1) clear_fwd_bf16_kernel(const FwdParams p)
+{
+    clear_fwd_bf16_workgroup<NWY, NWX, TEXTQ, CODE>(p, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Image-query and text-query rows in one launch: workgroups [0, n_image) are the image-query ones, the rest the
+// text-query ones.  For problems of a few rounds of workgroups, where the image-query launch alone leaves CUs idle
+// at its end and a launch of its own for the text-query rows costs more than it computes.
+template <int NWY, int NWX, int CODE>
+__global__ void __launch_bounds__((NWY * NWX + kLoaderWaves) * 64, 1) clear_fwd_bf16_both_kernel(const FwdParams p, const int n_image)
+{
+    const int bid = (int)blockIdx.x;
+    if (bid < n_image)
+        clear_fwd_bf16_workgroup<NWY, NWX, false, CODE>(p, bid, n_image);
+    else
+        clear_fwd_bf16_workgroup<NWY, NWX, true, kCodeDisc>(p, bid - n_image, (int)gridDim.x - n_image);
+}
+
 // Combines the key-split partial results of the text-query rows: with m the largest running
 // maximum, O = sum_i 2^{(m_i - m) c} O_i / sum_i 2^{(m_i - m) c} l_i.
 template <typename OutT>
@@ -855,6 +875,18 @@ hipError_t launch_fwd(const FwdParams& p, int nblk, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int NWY, int NWX, int CODE>
+hipError_t launch_fwd_both(const FwdParams& p, int n_image, int n_text_wgs, hipStream_t stream)
+{
+    const size_t smem = (size_t)NBUF * STAGE_BYTES;
+    auto kern = clear_fwd_bf16_both_kernel<NWY, NWX, CODE>;
+    static LdsLimitOnce lds_limit;  // one per kernel instantiation
+    hipError_t e = lds_limit.ensure((const void*)kern, (int)smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(n_image + n_text_wgs), dim3((NWY * NWX + kLoaderWaves) * 64), smem, stream, p, n_image);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 #if CLEAR_HEAD_DIM == 128
@@ -866,6 +898,13 @@ hipError_t launch_bf16(const FwdParams& p, hipStream_t stream, int phase)
 {
     const int BH = p.B * p.H;
     hipError_t e = hipSuccess;
+    if (phase == kPhaseImageAndTextQuery) {
+        const int n_image = BH * p.n_classes * p.n_q_tiles_launch, n_text_wgs = p.n_text > 0 ? BH * p.n_tq_tiles * p.n_splits : 0;
+        const int code = mask_code_of(p.mask_kind);
+        return code == kCodeDisc   ? launch_fwd_both<kBf16NWY, kBf16NWX, kCodeDisc>(p, n_image, n_text_wgs, stream)
+               : code == kCodeFull ? launch_fwd_both<kBf16NWY, kBf16NWX, kCodeFull>(p, n_image, n_text_wgs, stream)
+                                   : launch_fwd_both<kBf16NWY, kBf16NWX, kCodeGeneric>(p, n_image, n_text_wgs, stream);
+    }
     if (phase == kPhaseAll || phase == kPhaseImage) {
         const int nblk = BH * p.n_classes * p.n_q_tiles_launch;
         const int code = mask_code_of(p.mask_kind);  // one kernel per family of image masks

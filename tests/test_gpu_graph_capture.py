@@ -1,7 +1,7 @@
-"""The forward pass inside a HIP graph: captured once (after a warm-up call has created the context's workspaces and
-its second stream), replayed several times with the program's own eager work and synchronisations in between, every
-replay checked against the eager result.  Covers the small-problem path (text-query kernels forked onto the
-context's own stream inside the capture) and the one-stream path."""
+"""The forward pass inside a HIP graph: captured once (after a warm-up call has created the context's workspaces),
+replayed several times with the program's own eager work and synchronisations in between, every replay checked
+against the eager result.  Covers the small-problem path (image-query and text-query rows in one launch) and the
+path of one launch after the other."""
 import pytest
 import torch
 
@@ -13,8 +13,8 @@ DEV = "cuda:0"
 
 
 @pytest.mark.parametrize("n_text,gh,gw,r,H", [
-    (96, 32, 40, 8, 2),     # few workgroups: the forward call forks onto the context's second stream
-    (64, 160, 160, 8, 24),  # many workgroups: one stream
+    (96, 32, 40, 8, 2),     # few workgroups: image-query and text-query rows in one launch
+    (64, 544, 544, 8, 24),  # more than 64 workgroups per CU: one launch after the other
 ])
 def test_forward_replays_from_a_graph(n_text, gh, gw, r, H):
     d = 128
@@ -22,7 +22,7 @@ def test_forward_replays_from_a_graph(n_text, gh, gw, r, H):
     Q, K, V = make_qkv_shape(1, H, n_text, gh, gw, d, "bf16", seed=800 + gh, device=DEV)
     O = torch.empty_like(Q)
     try:
-        ctx.forward(Q, K, V, O)  # warm-up: allocates the workspace, creates the second stream, sets kernel attributes
+        ctx.forward(Q, K, V, O)  # warm-up: allocates the workspace, sets kernel attributes
         torch.cuda.synchronize()
         eager = O.clone()
         graph = torch.cuda.CUDAGraph()
