@@ -71,9 +71,8 @@ int clear_attn_create(clear_attn_ctx** out, int n_text, int gridH, int gridW, in
  * forward() calls this itself when it meets a larger B*H than any before, which allocates and
  * synchronises; call reserve first if forward must not allocate.  A forward call (any variant, backward
  * included) that would have to grow a workspace while `stream` is being captured into a HIP graph returns
- * CLEAR_ERR_INVALID_ARG instead and launches nothing: reserve beforehand, or make one eager call first (the
- * backward pass of a small problem, which runs its independent kernels on a second stream of the context, stays
- * on `stream` alone under capture if no earlier call has created that stream).
+ * CLEAR_ERR_INVALID_ARG instead and launches nothing: reserve beforehand, or make one eager call first.  Every
+ * call launches on `stream` alone.
  * Returns CLEAR_ERR_ALLOC on failure.
  */
 int clear_attn_reserve(clear_attn_ctx* ctx, int BH);

@@ -153,7 +153,8 @@ struct BwdParams {
 };
 // phase: kBwdPhaseAll, or one kernel of the pass: delta first; the image-row and text-row kernels are independent
 // of each other; the reduction of the text-row partial sums comes after the two text-row kernels.
-enum BwdPhase : int { kBwdPhaseAll = -1, kBwdPhaseDelta = 0, kBwdPhaseImageQ = 1, kBwdPhaseImageKV = 2, kBwdPhaseTextQ = 3, kBwdPhaseTextKV = 4, kBwdPhaseReduce = 5 };
+// kBwdPhaseFour: the four kernels between delta and the reduction in one launch.
+enum BwdPhase : int { kBwdPhaseAll = -1, kBwdPhaseDelta = 0, kBwdPhaseImageQ = 1, kBwdPhaseImageKV = 2, kBwdPhaseTextQ = 3, kBwdPhaseTextKV = 4, kBwdPhaseReduce = 5, kBwdPhaseFour = 6 };
 hipError_t launch_bf16_d128_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream, int phase);
 hipError_t launch_bf16_d64_backward(const BwdParams& p, const void* O, float* delta, hipStream_t stream, int phase);
 

@@ -42,6 +42,7 @@
 #define clear_bwd_bf16_kernel clear_bwd_bf16_d64_kernel
 #define clear_bwd_delta_kernel clear_bwd_delta_d64_kernel
 #define clear_bwd_reduce_kernel clear_bwd_reduce_d64_kernel
+#define clear_bwd_bf16_all_kernel clear_bwd_bf16_d64_all_kernel
 #define launch_bf16_backward launch_bf16_d64_backward
 #else
 #define launch_bf16_backward launch_bf16_d128_backward
@@ -55,8 +56,9 @@ enum BwdMode : int { kBwdQ = 0, kBwdK = 1, kBwdV = 2, kBwdKV = 3 };
 constexpr int STATS_BYTES = TILE_KEYS * 2 * 4;                           // per staged tile: lse2 and delta of its 64 columns
 constexpr int BWD_LDS_BYTES = NBUF * STAGE_BYTES + NBUF * TPS * STATS_BYTES;
 
+// One workgroup of a backward launch: workgroup `bid` of `nblk`.
 template <int MODE, bool LINROWS, int CODE>
-__global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams p)
+__device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, const int bid, const int nblk)
 {
     constexpr int NWY = kBf16NWY, NWX = kBf16NWX, NW = NWY * NWX;
     constexpr int NI = TILE_KEYS / ROWS_PER_LOAD / NW;  // 1 KB load instructions per wave per tile, for each of the two tiles
@@ -74,7 +76,6 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     // ---- workgroup -> (batch*head, row tile[, column split]); XCD-aware like the forward kernel
     int vid;
     {
-        const int nblk = gridDim.x, bid = blockIdx.x;
         const int xcd = bid & 7, idx = bid >> 3;
         const int q = nblk >> 3, rem = nblk & 7;
         vid = xcd * q + imin(xcd, rem) + idx;
@@ -596,6 +597,28 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
     }
 }
 
+template <int MODE, bool LINROWS, int CODE>
+__global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams p)
+{
+    clear_bwd_bf16_workgroup<MODE, LINROWS, CODE>(p, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// The four independent kernels of a backward pass in one launch, longest workgroups first: [0, n_image) dK and dV of
+// the image keys, [n_image, 2 n_image) dQ of the image queries, then n_text_wgs workgroups for dK and dV of the text
+// keys and as many for dQ of the text queries.  For problems of a few rounds of workgroups, where four launches on two
+// streams leave CUs idle between them.
+template <int CODE>
+__global__ void __launch_bounds__(512, 1) clear_bwd_bf16_all_kernel(const BwdParams p, const int n_image, const int n_text_wgs)
+{
+    int bid = (int)blockIdx.x;
+    if (bid < n_image) return clear_bwd_bf16_workgroup<kBwdKV, false, CODE>(p, bid, n_image);
+    bid -= n_image;
+    if (bid < n_image) return clear_bwd_bf16_workgroup<kBwdQ, false, CODE>(p, bid, n_image);
+    bid -= n_image;
+    if (bid < n_text_wgs) return clear_bwd_bf16_workgroup<kBwdKV, true, kCodeDisc>(p, bid, n_text_wgs);
+    clear_bwd_bf16_workgroup<kBwdQ, true, kCodeDisc>(p, bid - n_text_wgs, n_text_wgs);
+}
+
 // delta_i = dO_i . O_i for every row: D / 8 lanes per row (8 channels = 16 bytes each).
 __global__ void __launch_bounds__(256) clear_bwd_delta_kernel(const __bf16* O, TensorStrides os, const __bf16* dO, TensorStrides dos, int H,
                                                               long long N, float* delta, long long rows)
@@ -646,6 +669,17 @@ hipError_t launch_bwd_code(const BwdParams& p, int nblk, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int CODE>
+hipError_t launch_bwd_all(const BwdParams& p, int n_image, int n_text_wgs, hipStream_t stream)
+{
+    auto kern = clear_bwd_bf16_all_kernel<CODE>;
+    static LdsLimitOnce lds_limit;  // one per kernel instantiation
+    hipError_t e = lds_limit.ensure((const void*)kern, BWD_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(2 * n_image + 2 * n_text_wgs), dim3(512), BWD_LDS_BYTES, stream, p, n_image, n_text_wgs);
+    return hipGetLastError();
+}
+
 // One kernel per family of image masks for the image rows; text rows meet every token and need none.
 template <int MODE, bool LINROWS>
 hipError_t launch_bwd(const BwdParams& p, int nblk, hipStream_t stream)
@@ -674,6 +708,15 @@ hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta,
         e = hipGetLastError();
     }
     const int nimg = BH * p.n_classes * p.n_q_tiles;
+#if CLEAR_BWD_FUSED_KV
+    if (phase == kBwdPhaseFour) {
+        const int nlin4 = p.n_text > 0 ? BH * p.n_tq_tiles * p.n_splits : 0;
+        const int code = mask_code_of(p.mask_kind);
+        return code == kCodeDisc   ? launch_bwd_all<kCodeDisc>(p, nimg, nlin4, stream)
+               : code == kCodeFull ? launch_bwd_all<kCodeFull>(p, nimg, nlin4, stream)
+                                   : launch_bwd_all<kCodeGeneric>(p, nimg, nlin4, stream);
+    }
+#endif
     if (e == hipSuccess && (all || phase == kBwdPhaseImageQ)) e = launch_bwd<kBwdQ, false>(p, nimg, stream);
     if (e == hipSuccess && (all || phase == kBwdPhaseImageKV)) {
 #if CLEAR_BWD_FUSED_KV

@@ -113,6 +113,30 @@ def test_backward_flux_2048_sampled():
     check_grad("dV", dV[0, 0].float().cpu().numpy()[cols], rV)
 
 
+@pytest.mark.slow
+def test_backward_many_workgroups_sampled():
+    """96 heads on a 224 x 224 grid: more than 64 image workgroups per CU, where the backward pass sends its four
+    kernels out one after the other and the forward pass its two (smaller problems share one launch).  Sampled rows
+    and columns of the first and the last head."""
+    n_text, gridH, gridW, r, H = 64, 224, 224, 8, 96
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, H, seed=29)
+    rng = np.random.default_rng(7)
+    N = Q.shape[2]
+    img = lambda y, x: n_text + y * gridW + x
+    for h in (0, H - 1):
+        q, k, v, g = (t[0, h].float().cpu().numpy() for t in (Q, K, V, dO))
+        rows = np.unique(np.concatenate([[0, 63, img(0, 0), img(0, 223), img(223, 0), img(223, 223), img(15, 16), img(111, 112)],
+                                         rng.integers(0, N, size=120)]))
+        ref_o = orc.attention_rows(q, k, v, rows, n_text, gridH, gridW, r)
+        max_abs, rel_rms = error_metrics(O[0, h].float().cpu().numpy()[rows], ref_o)
+        assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (h, max_abs, rel_rms)
+        check_grad("dQ", dQ[0, h].float().cpu().numpy()[rows], orc.backward_dq_rows(q, k, v, g, rows, n_text, gridH, gridW, r))
+        cols = np.unique(np.concatenate([[5, img(0, 0), img(223, 223), img(7, 8), img(112, 111)], rng.integers(n_text, N, size=30)]))
+        rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
+        check_grad("dK", dK[0, h].float().cpu().numpy()[cols], rK)
+        check_grad("dV", dV[0, h].float().cpu().numpy()[cols], rV)
+
+
 def test_backward_rejects_bad_arguments():
     n_text, gridH, gridW, r, d = 8, 16, 16, 4, 128
     Q, K, V = make_qkv_shape(1, 1, n_text, gridH, gridW, d, "bf16", seed=1, device="cuda:0")
