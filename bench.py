@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--prologue", action="store_true",
                     help="time the forward pass with the query/key prologue (RMS norm, rotary embedding, logit scale) fused in, "
                          "against the plain forward pass and against the prologue as two passes of their own")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the short timings of the other paths (backward, head_dim 64, smaller images, one row band) that the "
+                         "default run appends to its line as `also_measured`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -198,7 +201,74 @@ def main():
         result["check_vs_oracle"] = {"rows": int(len(rows)), "max_abs": float(np.abs(diff).max()),
                                      "rel_rms": float(np.sqrt((diff ** 2).sum() / (ref ** 2).sum()))}
     ctx.destroy()
+    if args.workload == "flux-8k-r16" and args.mask == "disc" and args.layout == "bhnd" and not args.no_also:
+        del Q, K, V, O
+        torch.cuda.empty_cache()
+        result["also_measured"] = also_measured(w, dev)
     print(json.dumps(result))
+
+
+def also_measured(w, dev):
+    """Short timings of the other paths of the library, appended to the default run's line so that every round's
+    record holds them: wall-clock mean per call between two synchronisations, inputs resident, nothing skipped.  They
+    are not checked against the oracle here (the -m gpu tests and each path's own bench mode do that)."""
+    import dataclasses
+    import torch
+    from paper_2412_16112_amd import clear_attn as ca
+    from paper_2412_16112_amd.inputs import WORKLOADS, make_qkv
+
+    def timed(step, warmup, steps):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    out = {}
+    # forward pass on the smaller images of the paper's tables and on a head_dim-64 shape (many calls where a call is
+    # short: a few dozen of them are over before the clock has settled)
+    for name, warmup, steps in [("flux-1024", 100, 400), ("flux-2048-r16", 50, 200), ("flux-4096-r16", 10, 40), ("sd35l-4096-r16", 10, 40)]:
+        wl = WORKLOADS[name]
+        Q, K, V = make_qkv(wl, dev)
+        O = torch.empty_like(Q)
+        ctx = ca.ClearAttn(wl.n_text, wl.gridH, wl.gridW, wl.head_dim, wl.r, ca.CLEAR_BF16)
+        ms = timed(lambda: ctx.forward(Q, K, V, O), warmup, steps)
+        useful = 4.0 * ca.clear_attn_mask_count(wl.n_text, wl.gridH, wl.gridW, wl.r) * wl.head_dim * wl.B * wl.H
+        out["forward " + name] = {"ms_per_step": ms, "steps": steps, "useful_tflops": useful / (ms * 1e-3) / 1e12}
+        ctx.destroy()
+        del Q, K, V, O
+    # backward pass on the headline shape
+    Q, K, V = make_qkv(w, dev)
+    g = torch.Generator(device=dev).manual_seed(w.seed + 1000)
+    dO = torch.randn(Q.shape, generator=g, device=dev, dtype=torch.float32).to(Q.dtype)
+    ctx = ca.ClearAttn(w.n_text, w.gridH, w.gridW, w.head_dim, w.r, ca.CLEAR_BF16)
+    O, lse = ctx.forward_lse(Q, K, V)
+    ms = timed(lambda: ctx.backward(Q, K, V, O, dO, lse), 2, 5)
+    useful = 10.0 * ca.clear_attn_mask_count(w.n_text, w.gridH, w.gridW, w.r) * w.head_dim * w.B * w.H
+    out["backward " + w.name] = {"ms_per_step": ms, "steps": 5, "useful_tflops": useful / (ms * 1e-3) / 1e12}
+    ctx.destroy()
+    del Q, K, V, O, dO, lse
+    torch.cuda.empty_cache()
+    # one row band of eight (its image queries with the r - 1 halo rows, its text queries, the merge of eight partials)
+    n_bands = 8
+    y0, y1, ht, hb = ca.clear_attn_band_layout(w.gridH, w.r, n_bands, n_bands // 2)
+    rows = ht + (y1 - y0) + hb
+    Q, K, V = make_qkv(dataclasses.replace(w, gridH=rows), dev)
+    O = torch.empty_like(Q)
+    ctx = ca.ClearAttn(w.n_text, rows, w.gridW, w.head_dim, w.r, ca.CLEAR_BF16)
+    to = torch.empty((w.B, w.H, w.n_text, w.head_dim), dtype=torch.float32, device=dev)
+    tl = torch.empty((w.B, w.H, w.n_text), dtype=torch.float32, device=dev)
+
+    def band_step():
+        ctx.forward_band(Q, K, V, O, ht, ht + (y1 - y0), True, to, tl)
+        ca.clear_attn_merge_text([to] * n_bands, [tl] * n_bands, O, w.n_text, ca.CLEAR_MERGE_AVERAGE)
+
+    out["forward %s, one row band of %d" % (w.name, n_bands)] = {"ms_per_step": timed(band_step, 20, 100), "steps": 100}
+    ctx.destroy()
+    return out
 
 
 def bench_prologue(args, w, dev):
