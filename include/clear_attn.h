@@ -109,7 +109,9 @@ int clear_attn_forward_noalloc(clear_attn_ctx* ctx, const void* Q, const void* K
  * (1..256) forward passes back to back on `stream` with a HIP event between the kernels, and
  * SYNCHRONISES.  phase_ms[0..2] receive the average milliseconds per launch, inside that sequence,
  * of (0) the image-query kernel (Eq. 3's windowed rows), (1) the text-query kernel (dense rows,
- * split along the keys) and (2) the merge of those splits.  O holds a valid result afterwards.
+ * split along the keys) and (2) the merge of those splits.  O holds a valid result afterwards.  The three
+ * kernels are launched one by one here also for the problem sizes at which clear_attn_forward sends the first two
+ * out as one launch (same code, same key splits, same bits).
  */
 int clear_attn_forward_profile(clear_attn_ctx* ctx, const void* Q, const void* K, const void* V,
                                void* O, int B, int H, int n_text, int gridH, int gridW,
