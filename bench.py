@@ -21,6 +21,18 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
 
+def forward_kernel_sources_digest():
+    """SHA-256 over the sources the forward kernels and their launch shape are built from: a stored counter reading
+    (profiles/hbm_traffic.json) carries the digest it was taken on, so a reading that the kernels have moved away from
+    shows in the bench line instead of going stale silently."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("kernels_bf16.hip", "kernels_bf16_d64.hip", "bf16_common.h", "block_class.h", "clear_internal.h", "schedule.cpp", "clear_attn_api.cpp"):
+        with open(os.path.join(ROOT, "paper_2412_16112_amd", "csrc", name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read() + b"\0")
+    return h.hexdigest()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,7 +64,12 @@ def main():
                          "default run appends to its line as `also_measured`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
+    ap.add_argument("--kernel-sources-digest", action="store_true",
+                    help="print the digest of the forward kernels' sources (what a new entry of profiles/hbm_traffic.json records) and exit")
     args = ap.parse_args()
+    if args.kernel_sources_digest:
+        print(forward_kernel_sources_digest())
+        return
     if args.copy_calibration:
         import torch
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -142,16 +159,20 @@ def main():
     img_ms = phase_ms[0]
     # HBM-side bytes of the dominant kernel: counter readings of separate rocprofv3 runs (FETCH_SIZE, then WRITE_SIZE), kept
     # with the commit they were taken at; stale once that kernel changes, which is why the commit is printed beside them
-    traffic, traffic_at = None, None
+    # (and the digest of the kernel sources they were taken on, compared below with the sources as they are now)
+    traffic, traffic_at, traffic_current = None, None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             entry = json.load(f).get(w.name if args.mask == "disc" else "", {})
         traffic, traffic_at = entry.get("image_query_kernel_bytes_per_launch"), entry.get("measured_at")
+        if traffic is not None and entry.get("forward_kernel_sources_sha256"):
+            traffic_current = entry["forward_kernel_sources_sha256"] == forward_kernel_sources_digest()
     roofline = {
         "bound": "mfma", "kernel": "clear_fwd_bf16_kernel<image queries>",
         "achieved": img_flop / (img_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": img_flop / (img_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_measured_at_commit": traffic_at,
+        "traffic_measured_on_current_kernel_sources": traffic_current,
         "traffic_over_algorithmic": (traffic / (w.B * w.H * 2.0 * (w.N + w.gridH * w.gridW) * w.head_dim * 2.0)) if traffic else None,
         "kernel_ms": {"image_query": phase_ms[0], "text_query": phase_ms[1], "text_merge": phase_ms[2]},
     }
