@@ -8,6 +8,16 @@ from oracle import clear_oracle as orc
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
 
 
+def max_abs_bar(dtype, ref):
+    """The max-abs bar for outputs of any magnitude.  TOL's 2e-2 is meant for outputs of order one (a softmax average
+    over many keys).  A row that averages two or three keys (r = 1, hardly any text) returns values as large as V's
+    own, 4 and more, and there the rounding of the bf16 output alone is half an ulp = 2^-9 of the value, the
+    rounding of the probabilities to bf16 as much again per term: 2^-7 of the largest reference value bounds both."""
+    if dtype != "bf16":
+        return TOL[dtype][0]
+    return max(TOL[dtype][0], 2.0 ** -7 * float(np.abs(np.asarray(ref)).max()))
+
+
 def error_metrics(got, ref):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)

@@ -14,7 +14,7 @@ import torch
 from oracle import clear_oracle as orc
 from paper_2412_16112_amd import clear_attn as ca
 from paper_2412_16112_amd.inputs import make_qkv_shape
-from tests.parity_util import TOL, error_metrics
+from tests.parity_util import TOL, error_metrics, max_abs_bar
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -58,7 +58,7 @@ def _check_forward(dtype, d, B, H, n_text, gh, gw, r, seed):
             got = O[b, h].float().cpu().numpy()
             assert np.isfinite(got).all()
             max_abs, rel_rms = error_metrics(got, ref)
-            assert max_abs <= tol[0] and rel_rms <= tol[1], (b, h, max_abs, rel_rms)
+            assert max_abs <= max_abs_bar(dtype, ref) and rel_rms <= tol[1], (b, h, max_abs, rel_rms)
             np.testing.assert_allclose(lse[b, h].cpu().numpy(), m + np.log(l), rtol=0, atol=3e-3 if dtype == "bf16" else 1e-4)
     return Qd, Kd, Vd
 
@@ -101,8 +101,14 @@ def test_random_shapes_backward(B, H, n_text, gh, gw, r, seed):
             for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), refs):
                 got = got[b, h].float().cpu().numpy()
                 max_abs, rel_rms = error_metrics(got, ref)
-                scale = max(float(np.abs(ref).max()), 1e-30)
-                assert np.isfinite(got).all() and max_abs <= TOL["bf16"][0] * scale and rel_rms <= TOL["bf16"][1], (name, b, h, max_abs, scale, rel_rms)
+                scale = float(np.abs(ref).max())
+                assert np.isfinite(got).all()
+                if scale < 1e-4:
+                    # a gradient that vanishes identically (r = 1 without text: every token sees only itself, P = 1 and
+                    # dS = dP - delta = 0): what is left is the rounding of two fp32 sums taken in different orders
+                    assert max_abs <= 1e-4, (name, b, h, max_abs, scale)
+                else:
+                    assert max_abs <= TOL["bf16"][0] * scale and rel_rms <= TOL["bf16"][1], (name, b, h, max_abs, scale, rel_rms)
 
 
 def _mask_shapes(seed, n, max_side):
@@ -135,7 +141,7 @@ def test_random_shapes_other_masks(kind, shift, H, n_text, gh, gw, r, d, seed):
     got = O.float().cpu().numpy()
     assert np.isfinite(got).all()
     max_abs, rel_rms = error_metrics(got, ref)
-    assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
+    assert max_abs <= max_abs_bar("bf16", ref) and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
 
 
 def _band_shapes(seed, n):
@@ -159,4 +165,4 @@ def test_random_shapes_row_bands(n_text, gh, gw, r, n_bands, d, seed):
     O = run_bands(Q, K, V, n_text, gh, gw, r, n_bands, ca.CLEAR_MERGE_EXACT)
     ref = orc.attention(Q.float().cpu().numpy(), K.float().cpu().numpy(), V.float().cpu().numpy(), n_text, gh, gw, r)
     max_abs, rel_rms = error_metrics(O.float().cpu().numpy(), ref)
-    assert max_abs <= TOL["bf16"][0] and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
+    assert max_abs <= max_abs_bar("bf16", ref) and rel_rms <= TOL["bf16"][1], (max_abs, rel_rms)
