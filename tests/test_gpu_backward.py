@@ -113,6 +113,24 @@ def test_backward_flux_2048_sampled():
     check_grad("dV", dV[0, 0].float().cpu().numpy()[cols], rV)
 
 
+def test_backward_wide_grid_sampled():
+    """A grid more than 16 row tiles wide (400 columns): the row tiles are dealt to the workgroups in 2 x 16 blocks."""
+    n_text, gridH, gridW, r, H = 48, 40, 400, 8, 2
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, H, seed=39)
+    rng = np.random.default_rng(11)
+    N = Q.shape[2]
+    img = lambda y, x: n_text + y * gridW + x
+    for h in range(H):
+        q, k, v, g = (t[0, h].float().cpu().numpy() for t in (Q, K, V, dO))
+        rows = np.unique(np.concatenate([[0, 47, img(0, 0), img(0, 399), img(39, 0), img(39, 399), img(15, 255), img(16, 256), img(31, 271), img(32, 272)],
+                                         rng.integers(0, N, size=150)]))
+        check_grad("dQ", dQ[0, h].float().cpu().numpy()[rows], orc.backward_dq_rows(q, k, v, g, rows, n_text, gridH, gridW, r))
+        cols = np.unique(np.concatenate([[7, img(0, 0), img(39, 399), img(16, 255), img(15, 256), img(33, 383), img(2, 384)], rng.integers(n_text, N, size=40)]))
+        rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
+        check_grad("dK", dK[0, h].float().cpu().numpy()[cols], rK)
+        check_grad("dV", dV[0, h].float().cpu().numpy()[cols], rV)
+
+
 @pytest.mark.slow
 def test_backward_many_workgroups_sampled():
     """96 heads on a 224 x 224 grid: more than 64 image workgroups per CU, where the backward pass sends its four
