@@ -35,8 +35,17 @@ constexpr int ROW_BYTES = D * 2;     // one token row of K or V
 constexpr int ROWS_PER_LOAD = 1024 / ROW_BYTES;  // token rows one LDS-direct wave load covers
 constexpr int TILE_KEYS = kKeyTileKeys;
 constexpr int TILE_BYTES = TILE_KEYS * ROW_BYTES;  // 16 KB for K, same for V
+// How many matrix instructions ahead the forward tile pipeline reads its LDS operands.  At 128 channels the image-query
+// kernel sits at its 168-register limit (three waves per SIMD with the loading waves): with two slots ahead, and the
+// fourth operand buffer that needs, the compiler keeps a query fragment in scratch memory and reloads it inside every
+// tile (a 16-byte scratch load and a full wait in front of a matrix instruction; 4 % of the kernel's time), with one
+// slot ahead nothing in the tile loops is spilled.  64 channels have the registers for two.
 #ifndef CLEAR_OPERAND_PREFETCH
+#if CLEAR_HEAD_DIM == 128
+#define CLEAR_OPERAND_PREFETCH 1
+#else
 #define CLEAR_OPERAND_PREFETCH 2
+#endif
 #endif
 #ifndef CLEAR_TILES_PER_STAGE
 #define CLEAR_TILES_PER_STAGE 2
