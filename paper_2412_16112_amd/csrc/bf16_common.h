@@ -171,12 +171,14 @@ constexpr unsigned V_HI = (1u << 5) | (unsigned)(8 * ROW_BYTES);
 struct TileAddr {
     unsigned kb, vb0, vb1;
 };
-__device__ __forceinline__ TileAddr tile_addr(unsigned tile_lds, const LaneOffsets& lo)
+// (v_half: where in the staged tile the half that is read transposed starts; the forward kernels read K row-wise
+// from the first half and V transposed from the second)
+__device__ __forceinline__ TileAddr tile_addr(unsigned tile_lds, const LaneOffsets& lo, unsigned v_half = TILE_BYTES)
 {
     TileAddr ta;
     ta.kb = tile_lds + lo.k0;
-    ta.vb0 = tile_lds + TILE_BYTES + lo.v0;
-    ta.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
+    ta.vb0 = tile_lds + v_half + lo.v0;
+    ta.vb1 = tile_lds + v_half + (lo.v0 ^ V_HI);
     return ta;
 }
 
@@ -282,16 +284,18 @@ __device__ __forceinline__ float max_block(const f32x16& s)
 typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
 typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
-__device__ __forceinline__ bf16x8 read_k_operand(const TileAddr& ta, int blk, int ks)
+// (extra: a constant byte offset on top, e.g. TILE_BYTES for the second half of a staged tile, so that both halves
+// share the lane's swizzled addresses and differ in the instruction's immediate offset only)
+__device__ __forceinline__ bf16x8 read_k_operand(const TileAddr& ta, int blk, int ks, unsigned extra = 0)
 {
-    return *(lds_bf16x8_ptr)(size_t)((ta.kb ^ (unsigned)(ks << 5)) + (unsigned)(blk * 32 * ROW_BYTES));
+    return *(lds_bf16x8_ptr)(size_t)((ta.kb ^ (unsigned)(ks << 5)) + (unsigned)(blk * 32 * ROW_BYTES) + extra);
 }
 
 // V^T fragment for the contraction over key slots 16 s2 + 4 hh + {0..3} and 16 s2 + 8 + 4 hh + {0..3} of
 // block blk, channels 32 db .. 32 db + 31: two 16-bit transpose reads.
-__device__ __forceinline__ bf16x8 read_v_operand(const TileAddr& ta, int blk, int s2, int db)
+__device__ __forceinline__ bf16x8 read_v_operand(const TileAddr& ta, int blk, int s2, int db, unsigned extra = 0)
 {
-    const unsigned imm = (unsigned)(blk * 32 * ROW_BYTES + s2 * 16 * ROW_BYTES);
+    const unsigned imm = (unsigned)(blk * 32 * ROW_BYTES + s2 * 16 * ROW_BYTES) + extra;
     const short4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(size_t)((ta.vb0 ^ (unsigned)(db << 6)) + imm));
     const short4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(size_t)((ta.vb1 ^ (unsigned)(db << 6)) + imm));
     union { struct { short4v lo, hi; } h; bf16x8 v; } u;
@@ -300,23 +304,23 @@ __device__ __forceinline__ bf16x8 read_v_operand(const TileAddr& ta, int blk, in
     return u.v;
 }
 
-__device__ __forceinline__ f32x16 qk_block(const TileAddr& ta, int blk, const bf16x8 (&qf)[KS])
+__device__ __forceinline__ f32x16 qk_block(const TileAddr& ta, int blk, const bf16x8 (&qf)[KS], unsigned extra = 0)
 {
     f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(ta, blk, ks), qf[ks], s, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(ta, blk, ks, extra), qf[ks], s, 0, 0, 0);
     return s;
 }
 
 // O^T += V_blk^T P^T for one 32-key block.  The contraction step s2 pairs P registers 8*s2 .. 8*s2+7
 // with key slots 16*s2 + 4*hh + {0..3} and 16*s2 + 8 + 4*hh + {0..3}.
-__device__ __forceinline__ void pv_block(f32x16 (&oacc)[NDB], const TileAddr& ta, int blk, const bf16x8 (&pf)[2])
+__device__ __forceinline__ void pv_block(f32x16 (&oacc)[NDB], const TileAddr& ta, int blk, const bf16x8 (&pf)[2], unsigned extra = 0)
 {
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db), pf[s2], oacc[db], 0, 0, 0);
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_operand(ta, blk, s2, db, extra), pf[s2], oacc[db], 0, 0, 0);
 }
 
 // Raises a kernel's dynamic-LDS limit once per device (function attributes belong to the device's copy of the

@@ -33,6 +33,9 @@
 #ifndef CLEAR_BWD_PIPELINED_KV
 #define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64)  // dK + dV blocks hand-ordered too where the registers allow it
 #endif
+#ifndef CLEAR_BWD_KV_OPERAND_PREFETCH
+#define CLEAR_BWD_KV_OPERAND_PREFETCH 2
+#endif
 #ifndef CLEAR_BWD_PIPELINED_Q
 #define CLEAR_BWD_PIPELINED_Q 1  // dQ blocks as a hand-ordered pipeline (0: the compiler's order, as for dK and dV)
 #endif
@@ -270,14 +273,11 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
     // One 32-column block of a staged tile.
     auto do_block = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma, const float* tile_stats) __attribute__((always_inline)) {
         constexpr int MASK = decltype(mask_tag)::value;
-        TileAddr t1, t2, tt;
-        t1.kb = tile_lds + lo.k0;                                        // C1, row-wise
-        t2.kb = tile_lds + TILE_BYTES + lo.k0;                           // C2, row-wise
-        const unsigned tbase = tile_lds + (MODE == kBwdV ? TILE_BYTES : 0);  // tile read transposed for the accumulation
-        tt.vb0 = tbase + lo.v0;
-        tt.vb1 = tbase + (lo.v0 ^ V_HI);
-        t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = 0;
-        f32x16 s = qk_block(t1, blk, r1f);
+        // C1 is read row-wise for the scores and (dQ, dK) transposed for the accumulation; C2, TILE_BYTES further on
+        // in the staged tile, through the same lane addresses and an immediate offset
+        const TileAddr ta = tile_addr(tile_lds, lo, 0);
+        constexpr unsigned kTransposedHalf = MODE == kBwdV ? TILE_BYTES : 0;  // the tile read transposed for the accumulation
+        f32x16 s = qk_block(ta, blk, r1f);
         apply_mask<MASK, CODE>(s, blk, ma);
         bf16x8 xf[2];
         if (MODE == kBwdV) {
@@ -287,7 +287,7 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
                 xf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l2));
             }
         } else {
-            const f32x16 dp = qk_block(t2, blk, r2f);
+            const f32x16 dp = qk_block(ta, blk, r2f, TILE_BYTES);
             bf16x8 pf[2];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -300,14 +300,10 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
             }
             if constexpr (MODE == kBwdKV) {
                 // dV += dO^T P from the same probabilities (the dO tile read transposed)
-                TileAddr tv;
-                tv.kb = 0;
-                tv.vb0 = tile_lds + TILE_BYTES + lo.v0;
-                tv.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
-                pv_block(acc_v, tv, blk, pf);
+                pv_block(acc_v, ta, blk, pf, TILE_BYTES);
             }
         }
-        pv_block(acc, tt, blk, xf);
+        pv_block(acc, ta, blk, xf, kTransposedHalf);
     };
 
     // The same block for dQ (lse and delta are the lane's own scalars, 64 accumulator registers: there is room)
@@ -318,18 +314,13 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
     //   slots [2 KS, end)    dQ^T += K^T dS^T       | dS = P (dP - delta) first, in slot 2 KS
     auto do_block_q = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma) __attribute__((always_inline)) {
         constexpr int MASK = decltype(mask_tag)::value;
-        TileAddr t1, t2, tt;
-        t1.kb = tile_lds + lo.k0;
-        t2.kb = tile_lds + TILE_BYTES + lo.k0;
-        tt.vb0 = tile_lds + lo.v0;
-        tt.vb1 = tile_lds + (lo.v0 ^ V_HI);
-        t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = 0;
+        const TileAddr ta = tile_addr(tile_lds, lo, 0);
         constexpr int S_END = KS, DP_END = 2 * KS, NSLOT = 2 * KS + 2 * NDB;
         auto operand = [&](int slot) {
-            if (slot < S_END) return read_k_operand(t1, blk, slot);
-            if (slot < DP_END) return read_k_operand(t2, blk, slot - S_END);
+            if (slot < S_END) return read_k_operand(ta, blk, slot);
+            if (slot < DP_END) return read_k_operand(ta, blk, slot - S_END, TILE_BYTES);
             const int i = slot - DP_END;  // s2-major, so that consecutive instructions write different accumulators
-            return read_v_operand(tt, blk, i / NDB, i % NDB);
+            return read_v_operand(ta, blk, i / NDB, i % NDB);
         };
         constexpr int PD = 2, RING = PD + 2;
         bf16x8 op[RING];
@@ -376,22 +367,15 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
     //   last 2 NDB slots         dK^T += Q^T dS^T
     auto do_block_kv = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma, const float* tile_stats) __attribute__((always_inline)) {
         constexpr int MASK = decltype(mask_tag)::value;
-        TileAddr t1, t2, tt, tv;
-        t1.kb = tile_lds + lo.k0;
-        t2.kb = tile_lds + TILE_BYTES + lo.k0;
-        tt.vb0 = tile_lds + lo.v0;
-        tt.vb1 = tile_lds + (lo.v0 ^ V_HI);
-        tv.vb0 = tile_lds + TILE_BYTES + lo.v0;
-        tv.vb1 = tile_lds + TILE_BYTES + (lo.v0 ^ V_HI);
-        t1.vb0 = t1.vb1 = t2.vb0 = t2.vb1 = tt.kb = tv.kb = 0;
+        const TileAddr ta = tile_addr(tile_lds, lo, 0);
         constexpr int S_END = KS, DP_END = 2 * KS, DV_END = DP_END + 2 * NDB, NSLOT = DV_END + 2 * NDB;
         auto operand = [&](int slot) {
-            if (slot < S_END) return read_k_operand(t1, blk, slot);
-            if (slot < DP_END) return read_k_operand(t2, blk, slot - S_END);
-            if (slot < DV_END) return read_v_operand(tv, blk, (slot - DP_END) / NDB, (slot - DP_END) % NDB);
-            return read_v_operand(tt, blk, (slot - DV_END) / NDB, (slot - DV_END) % NDB);
+            if (slot < S_END) return read_k_operand(ta, blk, slot);
+            if (slot < DP_END) return read_k_operand(ta, blk, slot - S_END, TILE_BYTES);
+            if (slot < DV_END) return read_v_operand(ta, blk, (slot - DP_END) / NDB, (slot - DP_END) % NDB, TILE_BYTES);
+            return read_v_operand(ta, blk, (slot - DV_END) / NDB, (slot - DV_END) % NDB);
         };
-        constexpr int PD = 2, RING = PD + 2;
+        constexpr int PD = CLEAR_BWD_KV_OPERAND_PREFETCH, RING = PD + 2;
         bf16x8 op[RING];
 #pragma unroll
         for (int i = 0; i < PD; ++i) op[i] = operand(i);
