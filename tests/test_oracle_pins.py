@@ -133,7 +133,7 @@ def _rand(shape, seed):
 
 
 def test_attention_vs_python_triple_loop_tiny():
-    """BASELINE tiny config (16x16 grid, 8 text tokens, r=4, d=64) against loops written out here."""
+    """The tiny configuration (16x16 grid, 8 text tokens, r=4, d=64) against loops written out here."""
     n_text, gh, gw, r, d = 8, 16, 16, 4, 64
     N = n_text + gh * gw
     Q, K, V = _rand((N, d), 0), _rand((N, d), 1), _rand((N, d), 2)
