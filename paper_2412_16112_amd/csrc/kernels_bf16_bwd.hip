@@ -36,6 +36,14 @@
 #ifndef CLEAR_BWD_KV_OPERAND_PREFETCH
 #define CLEAR_BWD_KV_OPERAND_PREFETCH 2
 #endif
+// dK + dV blocks in the compiler's order (128 channels): form the probabilities and round them to bf16 before the dP
+// products, and take dS from those rounded values.  With the fp32 scores dead that early the block fits the 256
+// registers of two waves per SIMD without reloading K and V fragments from scratch memory inside the loop (20
+// registers spilled outside it instead of 60 with two reloads per block); dS then carries the rounding of P that dV's
+// operand has anyway.
+#ifndef CLEAR_BWD_KV_EARLY_P
+#define CLEAR_BWD_KV_EARLY_P (CLEAR_HEAD_DIM == 128)
+#endif
 #ifndef CLEAR_BWD_PIPELINED_Q
 #define CLEAR_BWD_PIPELINED_Q 1  // dQ blocks as a hand-ordered pipeline (0: the compiler's order, as for dK and dV)
 #endif
@@ -286,6 +294,23 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
                 const float l2 = COLSTAT ? tile_stats[32 * blk + 8 * (r >> 2) + 4 * hh + (r & 3)] : lse2_row;
                 xf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l2));
             }
+        } else if constexpr (MODE == kBwdKV && CLEAR_BWD_KV_EARLY_P) {
+            // The probabilities first, rounded to bf16 (they are the operand of the dV product anyway), so that the
+            // fp32 scores are dead before dP is formed: eight registers less at the block's peak.
+            bf16x8 pf[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float l2 = COLSTAT ? tile_stats[32 * blk + 8 * (r >> 2) + 4 * hh + (r & 3)] : lse2_row;
+                pf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l2));
+            }
+            asm volatile("" : "+v"(pf[0]), "+v"(pf[1]));  // (keeps the conversion in front of the dP products)
+            const f32x16 dp = qk_block(ta, blk, r2f, TILE_BYTES);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float dl = COLSTAT ? tile_stats[TILE_KEYS + 32 * blk + 8 * (r >> 2) + 4 * hh + (r & 3)] : delta_row;
+                xf[r >> 3][r & 7] = (__bf16)((float)pf[r >> 3][r & 7] * (dp[r] - dl));
+            }
+            pv_block(acc_v, ta, blk, pf, TILE_BYTES);
         } else {
             const f32x16 dp = qk_block(ta, blk, r2f, TILE_BYTES);
             bf16x8 pf[2];
