@@ -96,6 +96,14 @@ __device__ __forceinline__ void load_to_lds_16B(const void* gbase, unsigned voff
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
 }
 
+// This lane's index in its wave from the hardware's lane count (two instructions, no register kept live for it).
+__device__ __forceinline__ int fresh_lane_id()
+{
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {

@@ -31,7 +31,13 @@
 #define CLEAR_BWD_FUSED_KV 1
 #endif
 #ifndef CLEAR_BWD_PIPELINED_KV
-#define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64)  // dK + dV blocks hand-ordered too where the registers allow it
+#define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64 ? 1 : 2)  // dK + dV blocks hand-ordered too: 1 = do_block_kv, 2 = do_block_kv_early, 0 = the compiler's order
+#endif
+#ifndef CLEAR_BWD_KV_FRESH_ADDR
+#define CLEAR_BWD_KV_FRESH_ADDR 1
+#endif
+#ifndef CLEAR_BWD_KV_RING_SLACK
+#define CLEAR_BWD_KV_RING_SLACK 1
 #endif
 #ifndef CLEAR_BWD_KV_OPERAND_PREFETCH
 #define CLEAR_BWD_KV_OPERAND_PREFETCH 2
@@ -61,6 +67,8 @@
 
 namespace clear {
 namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 enum BwdMode : int { kBwdQ = 0, kBwdK = 1, kBwdV = 2, kBwdKV = 3 };
 
@@ -136,25 +144,43 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
     const float* const lse = p.lse + (long long)bh * p.N;
     const float* const delta = p.delta + (long long)bh * p.N;
 
-    // ---- this lane's row
-    int wy0 = 0, wx0 = 0, ry = 0, rx = 0;
-    int r_token;
-    bool r_valid, wave_has_rows;
+    // ---- this wave's rows, and this lane's one among them.  What depends on the lane (row coordinates, token, validity,
+    // the half of the wave) is worked out again from the hardware's lane count wherever it is needed (here, per masked
+    // tile, in the epilogue) instead of being carried through the tile loop: the fused dK / dV kernel has no register
+    // to spare there, and a value spilled to scratch memory costs, on its way back, a wait for every load in flight.
+    int wy0 = 0, wx0 = 0, r0 = 0;
+    bool wave_has_rows;
     if (LINROWS) {
-        const int r0 = rt * (NW * 32) + wave * 32;
-        r_token = r0 + qi;
-        r_valid = r_token < p.n_text;
+        r0 = rt * (NW * 32) + wave * 32;
         wave_has_rows = r0 < p.n_text;
-        if (!r_valid) r_token = p.n_text - 1;
     } else {
         wy0 = (rt / p.n_qtx) * (NWY * kWaveQH) + (wave / NWX) * kWaveQH;
         wx0 = (rt % p.n_qtx) * (NWX * kWaveQW) + (wave % NWX) * kWaveQW;
-        ry = wy0 + (qi >> 3);
-        rx = wx0 + (qi & 7);
-        r_valid = ry < rH && rx < rW;
         wave_has_rows = wy0 < rH && wx0 < rW;
-        r_token = p.n_text + (imin(ry, rH - 1) * stride + r_oy) * p.gridW + imin(rx, rW - 1) * stride + r_ox;
     }
+    struct LaneRow {
+        int hh, ry, rx, token;
+        bool valid;
+    };
+    auto lane_row = [&]() {
+        LaneRow L;
+        const int ln = fresh_lane_id();
+        const int q = ln & 31;
+        L.hh = ln >> 5;
+        L.ry = L.rx = 0;
+        if (LINROWS) {
+            L.token = r0 + q;
+            L.valid = L.token < p.n_text;
+            if (!L.valid) L.token = p.n_text - 1;
+        } else {
+            L.ry = wy0 + (q >> 3);
+            L.rx = wx0 + (q & 7);
+            L.valid = L.ry < rH && L.rx < rW;
+            L.token = p.n_text + (imin(L.ry, rH - 1) * stride + r_oy) * p.gridW + imin(L.rx, rW - 1) * stride + r_ox;
+        }
+        return L;
+    };
+    const int r_token = lane_row().token;
     // B operands: KS contraction steps of 16 channels, this lane supplying channels 16 s + 8 hh .. + 7
     bf16x8 r1f[KS], r2f[KS];
 #pragma unroll
@@ -226,17 +252,21 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
     auto issue_tile = [&](int i, unsigned lds_tile) {
         int a, b;
         tile_origin(i, a, b);
+        // The lane's place in the tile is worked out again from the hardware's lane count: values kept in registers
+        // since the kernel's start get spilled in the fused dK / dV kernel, and their reload from scratch memory would
+        // wait for every load issued before it, the staged tile in front included.
+        const int ln = fresh_lane_id();
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
             const int ii = wave * NI + n;
-            const int row = ROWS_PER_LOAD * ii + lane / CHUNKS;
+            const int row = ROWS_PER_LOAD * ii + ln / CHUNKS;
             const int token = slot_token(a, b, row);
-            const unsigned chunk_off = (unsigned)(((lane % CHUNKS) ^ swz(row)) << 4);
+            const unsigned chunk_off = (unsigned)(((ln % CHUNKS) ^ swz(row)) << 4);
             load_to_lds_16B(C1, (unsigned)token * c1_pitch + chunk_off, lds_tile + ii * 1024);
             load_to_lds_16B(C2, (unsigned)token * c2_pitch + chunk_off, lds_tile + TILE_BYTES + ii * 1024);
         }
     };
-    float st_lse2 = 0.f, st_delta = 0.f;  // in flight: statistics of slot `lane` of tile `wave` of the next stage
+    float st_lse = 0.f, st_delta = 0.f;  // in flight: statistics of slot `lane` of tile `wave` of the next stage
     auto issue_stage = [&](int t, int buf) {
         const int len = stage_len(t);
 #pragma unroll
@@ -245,16 +275,17 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
         if (COLSTAT && wave < len) {
             int a, b;
             tile_origin(t + wave, a, b);
-            const int token = slot_token(a, b, lane);
-            st_lse2 = lse[token] * LOG2E;
+            const int token = slot_token(a, b, fresh_lane_id());
+            st_lse = lse[token];  // (scaled when it is published: no wait for it here)
             st_delta = delta[token];
         }
     };
     auto publish_stats = [&](int buf, int len) {  // called before the barrier that opens stage buffer buf
         if (COLSTAT && wave < len) {
             float* dst = stats + ((buf * TPS + wave) * 2) * TILE_KEYS;
-            dst[lane] = st_lse2;
-            dst[TILE_KEYS + lane] = st_delta;
+            const int ln = fresh_lane_id();
+            dst[ln] = st_lse * LOG2E;
+            dst[TILE_KEYS + ln] = st_delta;
         }
     };
 
@@ -448,6 +479,83 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
         static_for<NSLOT>(run_slot);
     };
 
+    // The same products for 128 channels, where the registers do not hold fp32 scores and dP together with the
+    // operand ring: the probabilities are rounded to bf16 as soon as the scores are complete (see
+    // CLEAR_BWD_KV_EARLY_P), dV follows at once, and dS then takes the place of P in the same registers,
+    //   slots [0, KS)            S = Q k^T
+    //   next 2 NDB slots         dV^T += dO^T P^T     | first half of P before them, second half under the first NDB
+    //   next KS slots            dP = dO v^T
+    //   last 2 NDB slots         dK^T += Q^T dS^T     | dS = P (dP - delta) likewise, over P
+    auto do_block_kv_early = [&](auto mask_tag, unsigned tile_lds, int blk, const MaskArgs& ma, const float* tile_stats) __attribute__((always_inline)) {
+        constexpr int MASK = decltype(mask_tag)::value;
+        TileAddr ta = tile_addr(tile_lds, lo, 0);
+        constexpr int S_END = KS, DV_END = S_END + 2 * NDB, DP_END = DV_END + KS, NSLOT = DP_END + 2 * NDB;
+        auto operand = [&](int slot) {
+            // the lane addresses of the 8 + 8 operand positions are formed again at every read (one XOR each) instead
+            // of living in sixteen registers through the loop
+            if (CLEAR_BWD_KV_FRESH_ADDR) asm volatile("" : "+v"(ta.kb), "+v"(ta.vb0), "+v"(ta.vb1));
+            if (slot < S_END) return read_k_operand(ta, blk, slot);
+            if (slot < DV_END) return read_v_operand(ta, blk, (slot - S_END) / NDB, (slot - S_END) % NDB, TILE_BYTES);
+            if (slot < DP_END) return read_k_operand(ta, blk, slot - DV_END, TILE_BYTES);
+            return read_v_operand(ta, blk, (slot - DP_END) / NDB, (slot - DP_END) % NDB);
+        };
+        constexpr int PD = CLEAR_BWD_KV_OPERAND_PREFETCH, RING = PD + CLEAR_BWD_KV_RING_SLACK;
+        bf16x8 op[RING];
+#pragma unroll
+        for (int i = 0; i < PD; ++i) op[i] = operand(i);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 sc = zero, dp = zero;
+        bf16x8 pf[2];  // P, then dS
+        const float* const st = tile_stats + 32 * blk + 4 * (fresh_lane_id() >> 5);  // statistics of this lane's 16 columns: 4 groups of 4
+        auto p_group = [&](int g) __attribute__((always_inline)) {
+            const f32x4 l2 = *(const f32x4*)(st + 8 * g);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) pf[g >> 1][4 * (g & 1) + u] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[4 * g + u], c, -l2[u]));
+        };
+        auto ds_group = [&](int g) __attribute__((always_inline)) {
+            const f32x4 dl = *(const f32x4*)(st + TILE_KEYS + 8 * g);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                // P back from the packed operand registers: an even element is the low half of its word
+                const unsigned w = __builtin_bit_cast(u32x4, pf[g >> 1])[2 * (g & 1) + (u >> 1)];
+                const float pr = __builtin_bit_cast(float, (u & 1) ? (w & 0xffff0000u) : (w << 16));
+                pf[g >> 1][4 * (g & 1) + u] = (__bf16)(pr * (dp[4 * g + u] - dl[u]));
+            }
+        };
+        auto run_slot = [&](auto slot_tag) __attribute__((always_inline)) {
+            constexpr int slot = decltype(slot_tag)::value;
+            if (slot + PD < NSLOT) op[(slot + PD) % RING] = operand(slot + PD);
+            if (slot == S_END) {
+                apply_mask<MASK, CODE>(sc, blk, ma);
+                p_group(0);
+                p_group(1);
+            }
+            constexpr int LATE = NDB > 2 ? 2 : 1;  // the second half is due at slot NDB of its product
+            if (slot == S_END + 1) p_group(2);
+            if (slot == S_END + LATE) p_group(3);
+            if (slot == DP_END) {
+                ds_group(0);
+                ds_group(1);
+            }
+            if (slot == DP_END + 1) ds_group(2);
+            if (slot == DP_END + LATE) ds_group(3);
+            if (slot < S_END)
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], r1f[slot], sc, 0, 0, 0);
+            else if (slot < DV_END) {
+                constexpr int i = slot >= S_END && slot < DV_END ? slot - S_END : 0;
+                acc_v[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf[i / NDB], acc_v[i % NDB], 0, 0, 0);
+            } else if (slot < DP_END)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], r2f[slot >= DV_END && slot < DP_END ? slot - DV_END : 0], dp, 0, 0, 0);
+            else {
+                constexpr int i = slot >= DP_END ? slot - DP_END : 0;
+                acc[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[slot % RING], pf[i / NDB], acc[i % NDB], 0, 0, 0);
+            }
+            SCHED_FENCE();
+        };
+        static_assert(NDB >= 2, "the second half of P and of dS is formed under the first NDB slots of its product");
+        static_for<NSLOT>(run_slot);
+    };
+
     int pf_tile = 0;
     int pend_len = 0;  // tiles of the stage whose statistics are in flight
     auto begin_stage = [&](int buf) {
@@ -470,8 +578,13 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
             if (run0) do_block_q(mask_tag, tile_lds, 0, ma);
             if (run1) do_block_q(mask_tag, tile_lds, 1, ma);
         } else if constexpr (MODE == kBwdKV && CLEAR_BWD_PIPELINED_KV) {
-            if (run0) do_block_kv(mask_tag, tile_lds, 0, ma, tile_stats);
-            if (run1) do_block_kv(mask_tag, tile_lds, 1, ma, tile_stats);
+            if constexpr (CLEAR_BWD_PIPELINED_KV == 2) {
+                if (run0) do_block_kv_early(mask_tag, tile_lds, 0, ma, tile_stats);
+                if (run1) do_block_kv_early(mask_tag, tile_lds, 1, ma, tile_stats);
+            } else {
+                if (run0) do_block_kv(mask_tag, tile_lds, 0, ma, tile_stats);
+                if (run1) do_block_kv(mask_tag, tile_lds, 1, ma, tile_stats);
+            }
         } else {
             if (run0) do_block(mask_tag, tile_lds, 0, ma, tile_stats);
             if (run1) do_block(mask_tag, tile_lds, 1, ma, tile_stats);
@@ -512,10 +625,11 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
             cls1 = classify_image_block_spec(spec, wy0, wx0, kWaveQH, kWaveQW, ta + kKeyBlockH, tb, kKeyBlockH, kKeyBlockW, p.gridH, p.gridW);
         }
         MaskArgs ma;
-        ma.hh = hh;
+        const LaneRow tile_row = lane_row();
+        ma.hh = tile_row.hh;
         ma.a = ta;
         ma.b = linear ? lin_limit : tb;
-        ma.qy = ry; ma.qx = rx; ma.gridH = cH; ma.gridW = cW; ma.r2 = p.r2;
+        ma.qy = tile_row.ry; ma.qx = tile_row.rx; ma.gridH = cH; ma.gridW = cW; ma.r2 = p.r2;
         ma.kind = p.mask_kind; ma.r = p.mask_r; ma.shift = p.mask_shift;
         ma.row[0] = ma.row[1] = mask_tbl;
         if (!LINROWS && !linear && p.mask_tbl) {
@@ -554,34 +668,35 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
             run_category(std::integral_constant<int, kMaskTable>{}, t, cb3, buf);
         run_category(std::integral_constant<int, kMaskImage>{}, t, cb4, buf);
     }
-
     // ---- epilogue
-    if (!r_valid) return;
+    const LaneRow out_row = lane_row();
+    if (!out_row.valid) return;
+    const int out_token = out_row.token, out_hh = out_row.hh;
     const float out_scale = MODE == kBwdV ? 1.0f : p.scale;  // dQ and dK carry the 1 / sqrt(d) of the logits
     if (LINROWS) {
         // partial sums of this column split: [mode][bh][split][row][d] fp32
         constexpr int slot0 = MODE == kBwdKV ? (int)kBwdK : MODE;
-        float* wo = p.ws + ((((long long)slot0 * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
+        float* wo = p.ws + ((((long long)slot0 * p.B * p.H + bh) * p.n_splits + split) * p.n_text + out_token) * D;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v = {acc[db][4 * g] * out_scale, acc[db][4 * g + 1] * out_scale, acc[db][4 * g + 2] * out_scale, acc[db][4 * g + 3] * out_scale};
-                *(f32x4*)(wo + 32 * db + 8 * g + 4 * hh) = v;
+                *(f32x4*)(wo + 32 * db + 8 * g + 4 * out_hh) = v;
             }
         if constexpr (MODE == kBwdKV) {
-            float* wv = p.ws + ((((long long)kBwdV * p.B * p.H + bh) * p.n_splits + split) * p.n_text + r_token) * D;
+            float* wv = p.ws + ((((long long)kBwdV * p.B * p.H + bh) * p.n_splits + split) * p.n_text + out_token) * D;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     f32x4 v = {acc_v[db][4 * g], acc_v[db][4 * g + 1], acc_v[db][4 * g + 2], acc_v[db][4 * g + 3]};
-                    *(f32x4*)(wv + 32 * db + 8 * g + 4 * hh) = v;
+                    *(f32x4*)(wv + 32 * db + 8 * g + 4 * out_hh) = v;
                 }
         }
     } else {
         const TensorStrides& outs = MODE == kBwdQ ? p.dqs : (MODE == kBwdV ? p.dvs : p.dks);
-        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdV ? p.dV : p.dK)) + batch * outs.sb + head * outs.sh + (long long)r_token * outs.sn;
+        __bf16* orow = (__bf16*)(MODE == kBwdQ ? p.dQ : (MODE == kBwdV ? p.dV : p.dK)) + batch * outs.sb + head * outs.sh + (long long)out_token * outs.sn;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -589,10 +704,10 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
                 bf16x4 v;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) v[u] = (__bf16)(acc[db][4 * g + u] * out_scale);
-                *(bf16x4*)(orow + 32 * db + 8 * g + 4 * hh) = v;
+                *(bf16x4*)(orow + 32 * db + 8 * g + 4 * out_hh) = v;
             }
         if constexpr (MODE == kBwdKV) {
-            __bf16* vrow = (__bf16*)p.dV + batch * p.dvs.sb + head * p.dvs.sh + (long long)r_token * p.dvs.sn;
+            __bf16* vrow = (__bf16*)p.dV + batch * p.dvs.sb + head * p.dvs.sh + (long long)out_token * p.dvs.sn;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -600,7 +715,7 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
                     bf16x4 v;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) v[u] = (__bf16)acc_v[db][4 * g + u];
-                    *(bf16x4*)(vrow + 32 * db + 8 * g + 4 * hh) = v;
+                    *(bf16x4*)(vrow + 32 * db + 8 * g + 4 * out_hh) = v;
                 }
         }
     }
