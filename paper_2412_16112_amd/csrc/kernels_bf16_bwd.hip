@@ -33,6 +33,9 @@
 #ifndef CLEAR_BWD_PIPELINED_KV
 #define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64 ? 1 : 2)  // dK + dV blocks hand-ordered too: 1 = do_block_kv, 2 = do_block_kv_early, 0 = the compiler's order
 #endif
+#ifndef CLEAR_BWD_ISSUE_SHARE
+#define CLEAR_BWD_ISSUE_SHARE 2
+#endif
 #ifndef CLEAR_BWD_KV_FRESH_ADDR
 #define CLEAR_BWD_KV_FRESH_ADDR 1
 #endif
@@ -81,6 +84,7 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
 {
     constexpr int NWY = kBf16NWY, NWX = kBf16NWX, NW = NWY * NWX;
     constexpr int NI = TILE_KEYS / ROWS_PER_LOAD / NW;  // 1 KB load instructions per wave per tile, for each of the two tiles
+    constexpr int ISSUE_SHARE = CLEAR_BWD_ISSUE_SHARE;  // 2: the waves take turns, half of them staging a whole stage
     constexpr bool COLSTAT = MODE != kBwdQ;  // lse / delta indexed by column
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];  // [NBUF][TPS][C1 tile | C2 tile], then the column statistics
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -257,8 +261,8 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
         // wait for every load issued before it, the staged tile in front included.
         const int ln = fresh_lane_id();
 #pragma unroll
-        for (int n = 0; n < NI; ++n) {
-            const int ii = wave * NI + n;
+        for (int n = 0; n < NI * ISSUE_SHARE; ++n) {
+            const int ii = (wave % (NW / ISSUE_SHARE)) * (NI * ISSUE_SHARE) + n;
             const int row = ROWS_PER_LOAD * ii + ln / CHUNKS;
             const int token = slot_token(a, b, row);
             const unsigned chunk_off = (unsigned)(((ln % CHUNKS) ^ swz(row)) << 4);
@@ -267,11 +271,16 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
         }
     };
     float st_lse = 0.f, st_delta = 0.f;  // in flight: statistics of slot `lane` of tile `wave` of the next stage
+    // Half of the waves stage a whole stage, the other half the next one (each SIMD holds one wave of either half): while
+    // one wave of a SIMD stands at its load instructions the other one is already at its matrix products.
+    int issue_turn = 0;
     auto issue_stage = [&](int t, int buf) {
         const int len = stage_len(t);
+        const bool mine = ISSUE_SHARE == 1 || (wave / (NW / ISSUE_SHARE)) == (issue_turn & (ISSUE_SHARE - 1));
+        ++issue_turn;
 #pragma unroll
         for (int j = 0; j < TPS; ++j)
-            if (j < len) issue_tile(t + j, lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
+            if (j < len && mine) issue_tile(t + j, lds_base + (unsigned)buf * STAGE_BYTES + (unsigned)j * (2 * TILE_BYTES));
         if (COLSTAT && wave < len) {
             int a, b;
             tile_origin(t + wave, a, b);
