@@ -128,7 +128,10 @@ struct BwdParams {
     const void* V;
     const void* dO;
     const float* lse;    // [B*H][N] natural log of the softmax denominators (from the forward pass)
-    const float* delta;  // [B*H][N] dO_i . O_i (computed by the launcher into the context's workspace)
+    const float* delta;  // [B*H][N] dO_i . O_i (in the context's workspace: from the delta kernel, or from the dQ kernels, see delta_out)
+    const void* O;       // the forward output, read where delta is formed inside the dQ kernels
+    float* delta_out;    // not null: the dQ kernels form delta of their own rows from O and dO, use it and store it here for
+                         // the dK / dV kernels launched after them (null: every kernel reads `delta`)
     void* dQ;
     void* dK;
     void* dV;
@@ -151,7 +154,8 @@ struct BwdParams {
     int n_tq_tiles, n_splits, split_keys;
     float* ws;  // [3 (dQ, dK, dV)][B*H][n_splits][n_text][head_dim]
 };
-// phase: kBwdPhaseAll, or one kernel of the pass: delta first; the image-row and text-row kernels are independent
+// phase: kBwdPhaseAll (the dQ kernels, which form delta on their way, then the dK / dV kernels, then the reduction),
+// or one kernel of the pass: delta first; the image-row and text-row kernels are independent
 // of each other; the reduction of the text-row partial sums comes after the two text-row kernels.
 // kBwdPhaseFour: the four kernels between delta and the reduction in one launch.
 enum BwdPhase : int { kBwdPhaseAll = -1, kBwdPhaseDelta = 0, kBwdPhaseImageQ = 1, kBwdPhaseImageKV = 2, kBwdPhaseTextQ = 3, kBwdPhaseTextKV = 4, kBwdPhaseReduce = 5, kBwdPhaseFour = 6 };

@@ -197,7 +197,23 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
     float lse2_row = 0.f, delta_row = 0.f;
     if (!COLSTAT) {
         lse2_row = lse[r_token] * LOG2E;
-        delta_row = delta[r_token];
+        if (p.delta_out) {
+            // delta of this lane's row from the dO fragments it holds and the matching pieces of its O row; the other half
+            // of the row's channels sits 32 lanes away
+            const __bf16* orow = head_of(p.O, p.os) + (long long)r_token * p.os.sn + 8 * (fresh_lane_id() >> 5);
+            float part = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 o = *(const bf16x8*)(orow + 16 * s);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) part += (float)o[j] * (float)r2f[s][j];
+            }
+            delta_row = part + __shfl_xor(part, 32, 64);
+            const LaneRow own = lane_row();
+            if (own.valid && own.hh == 0 && split == 0) p.delta_out[(long long)bh * p.N + own.token] = delta_row;
+        } else {
+            delta_row = delta[r_token];
+        }
     }
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -834,7 +850,8 @@ hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta,
     const int BH = p.B * p.H;
     const bool all = phase == kBwdPhaseAll;
     hipError_t e = hipSuccess;
-    if (all || phase == kBwdPhaseDelta) {
+    // (kBwdPhaseAll: no delta kernel; the dQ kernels form delta and run before the dK / dV kernels, which read it)
+    if (phase == kBwdPhaseDelta) {
         const long long rows = (long long)BH * p.N;
         constexpr int rows_per_block = 256 / CHUNKS;
         hipLaunchKernelGGL(clear_bwd_delta_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), dim3(256), 0, stream, (const __bf16*)O, p.os, (const __bf16*)p.dO, p.dos, p.H, p.N, delta, rows);
@@ -850,7 +867,14 @@ hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta,
                                    : launch_bwd_all<kCodeGeneric>(p, nimg, nlin4, stream);
     }
 #endif
-    if (e == hipSuccess && (all || phase == kBwdPhaseImageQ)) e = launch_bwd<kBwdQ, false>(p, nimg, stream);
+    const int nlin = p.n_text > 0 ? BH * p.n_tq_tiles * p.n_splits : 0;
+    BwdParams pq = p;  // for the dQ kernels
+    if (all) {
+        pq.O = O;
+        pq.delta_out = delta;
+    }
+    if (e == hipSuccess && (all || phase == kBwdPhaseImageQ)) e = launch_bwd<kBwdQ, false>(pq, nimg, stream);
+    if (e == hipSuccess && nlin > 0 && (all || phase == kBwdPhaseTextQ)) e = launch_bwd<kBwdQ, true>(pq, nlin, stream);
     if (e == hipSuccess && (all || phase == kBwdPhaseImageKV)) {
 #if CLEAR_BWD_FUSED_KV
         e = launch_bwd<kBwdKV, false>(p, nimg, stream);
@@ -860,8 +884,6 @@ hipError_t launch_bf16_backward(const BwdParams& p, const void* O, float* delta,
 #endif
     }
     if (e != hipSuccess || p.n_text == 0) return e;
-    const int nlin = BH * p.n_tq_tiles * p.n_splits;
-    if (all || phase == kBwdPhaseTextQ) e = launch_bwd<kBwdQ, true>(p, nlin, stream);
     if (e == hipSuccess && (all || phase == kBwdPhaseTextKV)) {
 #if CLEAR_BWD_FUSED_KV
         e = launch_bwd<kBwdKV, true>(p, nlin, stream);
