@@ -155,6 +155,52 @@ def test_backward_many_workgroups_sampled():
         check_grad("dV", dV[0, h].float().cpu().numpy()[cols], rV)
 
 
+@pytest.mark.slow
+def test_backward_many_workgroups_without_text():
+    """The same launch shape with no text token: delta, which the dQ kernel of the image rows forms on its way for the
+    dK / dV kernel launched after it, then comes from that one kernel alone."""
+    n_text, gridH, gridW, r, H = 0, 224, 224, 8, 96
+    Q, K, V, dO, O, lse, dQ, dK, dV = run_case(n_text, gridH, gridW, r, H, seed=31)
+    rng = np.random.default_rng(8)
+    N = Q.shape[2]
+    for h in (0, H // 2, H - 1):
+        q, k, v, g = (t[0, h].float().cpu().numpy() for t in (Q, K, V, dO))
+        rows = np.unique(np.concatenate([[0, 223, N - 224, N - 1], rng.integers(0, N, size=60)]))
+        check_grad("dQ", dQ[0, h].float().cpu().numpy()[rows], orc.backward_dq_rows(q, k, v, g, rows, n_text, gridH, gridW, r))
+        cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, size=30)]))
+        rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
+        check_grad("dK", dK[0, h].float().cpu().numpy()[cols], rK)
+        check_grad("dV", dV[0, h].float().cpu().numpy()[cols], rV)
+
+
+@pytest.mark.slow
+def test_backward_many_workgroups_strided_mask():
+    """The strided mask (r * r residue classes, each a dense problem of its own) at a size where the four kernels go out
+    one after the other: 128 heads x 16 classes x 9 row tiles."""
+    n_text, gridH, gridW, r, H, layer, d = 40, 160, 160, 4, 128, 6, 128
+    Q, K, V = make_qkv_shape(1, H, n_text, gridH, gridW, d, "bf16", seed=33, device="cuda:0")
+    gen = torch.Generator(device="cuda:0").manual_seed(34)
+    dO = torch.randn(Q.shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    ctx = ca.ClearAttn(n_text, gridH, gridW, d, r, ca.CLEAR_BF16, orc.MASK_STRIDED, layer)  # (the two sides number the mask kinds alike)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        dQ, dK, dV = ctx.backward(Q, K, V, O, dO, lse)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    rng = np.random.default_rng(9)
+    N = Q.shape[2]
+    with orc.mask_kind(orc.MASK_STRIDED, layer):
+        for h in (0, H - 1):
+            q, k, v, g = (t[0, h].float().cpu().numpy() for t in (Q, K, V, dO))
+            rows = np.unique(np.concatenate([[0, n_text - 1, n_text, N - 1], rng.integers(0, N, size=60)]))
+            check_grad("dQ", dQ[0, h].float().cpu().numpy()[rows], orc.backward_dq_rows(q, k, v, g, rows, n_text, gridH, gridW, r))
+            cols = np.unique(np.concatenate([[3, n_text, N - 1], rng.integers(0, N, size=30)]))
+            rK, rV = orc.backward_dkv_cols(q, k, v, g, cols, n_text, gridH, gridW, r)
+            check_grad("dK", dK[0, h].float().cpu().numpy()[cols], rK)
+            check_grad("dV", dV[0, h].float().cpu().numpy()[cols], rV)
+
+
 def test_backward_rejects_bad_arguments():
     n_text, gridH, gridW, r, d = 8, 16, 16, 4, 128
     Q, K, V = make_qkv_shape(1, 1, n_text, gridH, gridW, d, "bf16", seed=1, device="cuda:0")
