@@ -18,9 +18,11 @@
 // lse and delta belong to the query: a per-lane scalar for dQ, a per-column vector (staged next to the tile)
 // for dK and dV.  Text rows sum over every token: they are split along the columns into partial sums that a
 // small kernel adds up, like the text-query rows of the forward pass.  dK and dV of a key tile are produced
-// by one pass from one S and one dP (the separate modes remain for reference).  The dQ blocks are a hand-ordered
-// pipeline like the forward kernel's tiles (do_block_q), and so are the dK / dV blocks at head_dim 64 (do_block_kv);
-// at head_dim 128 the dK / dV blocks are plain block-by-block code.
+// by one pass from one S and one dP (the separate modes remain for reference).  The blocks are hand-ordered
+// pipelines like the forward kernel's tiles: do_block_q for dQ, do_block_kv for dK + dV at head_dim 64 and
+// do_block_kv_early at head_dim 128 (do_block, the compiler's order, serves the separate dK and dV modes).
+// delta is formed by the dQ kernels on their way when they run before the dK / dV kernels (BwdParams::delta_out),
+// otherwise by clear_bwd_delta_kernel.
 #include <hip/hip_runtime.h>
 
 #include "bf16_common.h"
@@ -31,25 +33,24 @@
 #define CLEAR_BWD_FUSED_KV 1
 #endif
 #ifndef CLEAR_BWD_PIPELINED_KV
-#define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64 ? 1 : 2)  // dK + dV blocks hand-ordered too: 1 = do_block_kv, 2 = do_block_kv_early, 0 = the compiler's order
+#define CLEAR_BWD_PIPELINED_KV (CLEAR_HEAD_DIM == 64 ? 1 : 2)  // dK + dV blocks: 1 = do_block_kv, 2 = do_block_kv_early, 0 = do_block (the compiler's order)
 #endif
 #ifndef CLEAR_BWD_ISSUE_SHARE
-#define CLEAR_BWD_ISSUE_SHARE 2
+#define CLEAR_BWD_ISSUE_SHARE 2  // 2: the waves stage whole stages in turns, half of them each time; 1: every wave its share of every stage
 #endif
 #ifndef CLEAR_BWD_KV_FRESH_ADDR
-#define CLEAR_BWD_KV_FRESH_ADDR 1
+#define CLEAR_BWD_KV_FRESH_ADDR 1  // do_block_kv_early: operand addresses formed at every read (0: sixteen registers hold them; spills)
 #endif
 #ifndef CLEAR_BWD_KV_RING_SLACK
-#define CLEAR_BWD_KV_RING_SLACK 1
+#define CLEAR_BWD_KV_RING_SLACK 1  // do_block_kv_early: entries of the operand ring beyond the prefetch distance
 #endif
 #ifndef CLEAR_BWD_KV_OPERAND_PREFETCH
-#define CLEAR_BWD_KV_OPERAND_PREFETCH 2
+#define CLEAR_BWD_KV_OPERAND_PREFETCH 2  // slots between an LDS operand read and the matrix instruction that takes it (3, 4: spills, slower)
 #endif
-// dK + dV blocks in the compiler's order (128 channels): form the probabilities and round them to bf16 before the dP
-// products, and take dS from those rounded values.  With the fp32 scores dead that early the block fits the 256
-// registers of two waves per SIMD without reloading K and V fragments from scratch memory inside the loop (20
-// registers spilled outside it instead of 60 with two reloads per block); dS then carries the rounding of P that dV's
-// operand has anyway.
+// do_block at 128 channels (only reached with CLEAR_BWD_PIPELINED_KV = 0): form the probabilities and round them to
+// bf16 before the dP products, and take dS from those rounded values, which then carries the rounding of P that dV's
+// operand has anyway.  do_block_kv_early does the same: with the fp32 scores dead that early the block fits the 256
+// registers of two waves per SIMD.
 #ifndef CLEAR_BWD_KV_EARLY_P
 #define CLEAR_BWD_KV_EARLY_P (CLEAR_HEAD_DIM == 128)
 #endif
@@ -440,8 +441,8 @@ __device__ __forceinline__ void clear_bwd_bf16_workgroup(const BwdParams& p, con
         static_for<NSLOT>(run_slot);
     };
 
-    // The fused dK + dV block in the same manner, 2 KS + 4 NDB matrix instructions.  Used at head_dim 64 only: at
-    // 128 channels the kernel has no registers for the operand ring (tried: more spills, a slower pass).
+    // The fused dK + dV block in the same manner, 2 KS + 4 NDB matrix instructions.  Used at head_dim 64; at 128
+    // channels fp32 scores, dP and an operand ring do not fit the registers together (see do_block_kv_early).
     //   slots [0, KS)            S = Q k^T
     //   slots [KS, 2 KS)         dP = dO v^T          | mask, P = 2^(S c - lse) of the finished S
     //   next 2 NDB slots         dV^T += dO^T P^T     | dS = P (dP - delta)
