@@ -327,8 +327,8 @@ __device__ __forceinline__ void clear_fwd_bf16_workgroup(const FwdParams& p, con
     {
         const __bf16* qrow = Qh + (long long)q_token * p.qs.sn + 8 * hh;
 #pragma unroll
-        for (int s = 0; s < KS; ++s)
-            if (!loader) qf[s] = *(const bf16x8*)(qrow + 16 * s);
+        for (int s = 0; s < KS; ++s)  // (read once: non-temporal, so that the rows do not push K and V tiles out of the L2)
+            if (!loader) qf[s] = __builtin_nontemporal_load((const bf16x8*)(qrow + 16 * s));
     }
     const const_int_ptr row_ptr = (const_int_ptr)p.row_ptr, col_idx = (const_int_ptr)p.col_idx, n_plain = (const_int_ptr)p.n_plain;
     const const_u64_ptr mask_tbl = (const_u64_ptr)p.mask_tbl;
@@ -806,7 +806,7 @@ __device__ __forceinline__ void clear_fwd_bf16_workgroup(const FwdParams& p, con
             const f32x4 chunk = *(const f32x4*)(wbase + row * OROW + (lane % CHUNKS) * 16);
             if (oy < qH && ox < qW && oy >= p.own_y0 && oy < p.own_y1) {
                 __bf16* orow = (__bf16*)p.O + batch * p.os.sb + head * p.os.sh + ((long long)p.n_text + (long long)((oy - y_shift) * stride + q_oy) * p.gridW + ox * stride + q_ox) * p.os.sn;
-                *(f32x4*)(orow + (lane % CHUNKS) * 8) = chunk;
+                __builtin_nontemporal_store(chunk, (f32x4*)(orow + (lane % CHUNKS) * 8));  // whole rows, never read again here
             }
         }
     }
