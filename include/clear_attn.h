@@ -28,10 +28,8 @@
  * context share its workspaces, so they must be ordered among themselves: enqueue them on one stream, or make the
  * later call's stream wait for the earlier call; use one context per stream for concurrent calls.
  * All functions run on the current HIP device; a context belongs to the device current at create.
- * Streams: work is enqueued on the stream passed in and is complete when that stream has reached the end of
- * the call's work.  For small problems a forward call also uses a stream the context owns (default priority),
- * forked from and joined to the caller's stream with events, so that independent kernels of the call overlap;
- * nothing of this is visible to the caller beyond the order on its own stream.
+ * Streams: every call enqueues all of its work on the stream passed in, and on no other; the work is complete when
+ * that stream has reached the end of it.
  */
 #ifndef CLEAR_ATTN_H
 #define CLEAR_ATTN_H
