@@ -1,5 +1,5 @@
 /*
- * clear_attn.h -- C ABI of the MI355X (gfx950) CLEAR local-attention forward pass.
+ * clear_attn.h -- C ABI of the MI355X (gfx950) CLEAR local attention: forward pass, backward pass, row bands.
  *
  * The operation (arXiv 2412.16112): softmax attention of Eq. 1 (Sec. 2),
  *     O = softmax(Q K^T / sqrt(head_dim)) V,
@@ -166,7 +166,8 @@ int clear_attn_executed_pairs(const clear_attn_ctx* ctx, unsigned long long* pai
  *                      _copy) is that of one class, a ceil(gridH / r) x ceil(gridW / r) grid; clear_attn_schedule_
  *                      host_masked returns CLEAR_ERR_UNSUPPORTED for it.
  * Every other entry point takes a square or Swin context unchanged (forward, forward_band, backward, ...); the
- * executed work differs: only the disc has precomputed lane masks, they use the arithmetic element mask. */
+ * executed work differs: the square window has precomputed lane masks like the disc; Swin windows run whole or
+ * skipped blocks when r and shift are multiples of 8 and the arithmetic element mask otherwise. */
 typedef enum { CLEAR_MASK_DISC = 0, CLEAR_MASK_SQUARE = 1, CLEAR_MASK_SWIN = 2, CLEAR_MASK_STRIDED = 3 } clear_mask_kind;
 int clear_attn_create_masked(clear_attn_ctx** out, int n_text, int gridH, int gridW, int head_dim, int r,
                              int dtype, int mask_kind, int shift);
