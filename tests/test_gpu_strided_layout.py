@@ -140,6 +140,27 @@ def test_training_pair_in_token_major_storage(d):
         assert torch.equal(a, b.contiguous())
 
 
+def test_training_pair_in_token_major_storage_many_workgroups():
+    """The same at a size where the backward pass sends its kernels out one after the other (more than 64 image
+    workgroups per CU) and the dQ kernels form delta from the O rows themselves, through O's strides."""
+    B, H, n_text, gh, gw, r, d = 1, 96, 64, 224, 224, 8, 128
+    Q, K, V = make_qkv_shape(B, H, n_text, gh, gw, d, "bf16", seed=760, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(761)
+    dO = torch.randn(Q.shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    ctx = ca.ClearAttn(n_text, gh, gw, d, r, ca.CLEAR_BF16)
+    try:
+        O, lse = ctx.forward_lse(Q, K, V)
+        dQ, dK, dV = ctx.backward(Q, K, V, O, dO, lse)
+        Qs, Ks, Vs, dOs, Os = (token_major(t) for t in (Q, K, V, dO, O))
+        dQs, dKs, dVs = ctx.backward_strided(Qs, Ks, Vs, Os, dOs, lse)
+        torch.cuda.synchronize()
+    finally:
+        ctx.destroy()
+    assert not dQs.is_contiguous()
+    for a, b in ((dQ, dQs), (dK, dKs), (dV, dVs)):
+        assert torch.equal(a, b.contiguous())
+
+
 def test_autograd_takes_transposed_views():
     from paper_2412_16112_amd.autograd import clear_attention, clear_context_cache
     B, H, n_text, gh, gw, d, r = 1, 2, 16, 24, 24, 128, 5
