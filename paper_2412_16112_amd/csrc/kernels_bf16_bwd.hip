@@ -755,8 +755,8 @@ __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_kernel(const BwdParams 
 
 // The four independent kernels of a backward pass in one launch, longest workgroups first: [0, n_image) dK and dV of
 // the image keys, [n_image, 2 n_image) dQ of the image queries, then n_text_wgs workgroups for dK and dV of the text
-// keys and as many for dQ of the text queries.  For problems of a few rounds of workgroups, where four launches on two
-// streams leave CUs idle between them.
+// keys and as many for dQ of the text queries.  For problems of a few rounds of workgroups, where four launches, one
+// after the other or on two streams, leave CUs idle between them.  (delta comes from clear_bwd_delta_kernel here.)
 template <int CODE>
 __global__ void __launch_bounds__(512, 1) clear_bwd_bf16_all_kernel(const BwdParams p, const int n_image, const int n_text_wgs)
 {
